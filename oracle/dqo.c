@@ -1,0 +1,358 @@
+/*
+ * dqo -- CPU oracle for the DQ-SGD stochastic gradient quantizer hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the GPU library is
+ * checked against.  It shares no code with the GPU library and is never called from it; only the
+ * tests, the smoke check and the benchmark's cpu_baseline leg may load it.
+ *
+ * What it computes, following the paper (arXiv 2107.14575):
+ *   - the element-wise uniform (EWU) quantizer of Section 4.1, Eq. (5)-(6):
+ *       Q_b[g_j] = ||g|| * sgn(g_j) * zeta(g_j, s),  zeta in {0, 1/s, ..., 1}, stochastic rounding
+ *       with round-up probability p_r = s*|g_j|/||g|| - l;
+ *   - the wire message whose size Eq. (7) counts: one sign bit plus the level bits per element
+ *     (the norm travels beside it, the B_pre bits of Eq. (7));
+ *   - the server average of Algorithm 1 (line "Average") / Eq. (2): (1/W) * sum_i Q_b[g^(i)];
+ *   - the bit rule Eq. (17) with the mean square of worker norms G-bar_t^2 of Lemma 1.
+ *
+ * Conventions (the paper is silent or ambiguous on each; every choice is listed in the design
+ * notes of the repository):
+ *   - b counts LEVEL bits: s = 2^b - 1 levels, wire width b + 1.  The paper's b is b + 1.
+ *   - the norm is the l2 norm, taken per tensor ("segment"); G-bar^2 uses the whole-gradient norm,
+ *     i.e. the sum of squared segment norms of a worker.
+ *   - tensors live in a padded flat index space P: segment l starts at P_l, P_0 = 0,
+ *     P_{l+1} = P_l + 128*ceil(len_l/128).  Pad elements are ignored on input and encode as zero.
+ *   - randomness: Philox4x32-10 (Salmon et al., SC'11), counter {lo32(P>>2), hi32(P>>2), worker,
+ *     step}, key {lo32(seed), hi32(seed)}; element P uses output word P&3; u = (r>>8) * 2^-24;
+ *     round up iff u < p (strict).
+ *   - all float arithmetic touching the rounding decision is single IEEE binary32 operations
+ *     (compile with -ffp-contract=off); the norm and the average accumulate in binary64.
+ *
+ * Pins (tests that do not use this file to check itself): Philox known answers and a big-integer
+ * Python twin; exact enumeration of rounding outcomes for d <= 4; Monte-Carlo unbiasedness and
+ * the Lemma 1 variance bound; grid reproduction; zero vector; numpy.linalg.norm; the closed form
+ * of the Eq. (16) constraint for the bit rule.  Nothing here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#define DQO_OK 0
+#define DQO_ERR_INVALID_ARG (-1)
+
+#define DQO_GRANULE 128
+
+/* ------------------------------------------------------------------------------------------- */
+/* Philox4x32-10: 10 rounds of two 32x32->64 multiplies; the key is bumped by the Weyl constants  */
+/* between rounds (9 bumps).  Written from the published definition of the generator.             */
+/* ------------------------------------------------------------------------------------------- */
+void dqo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t prod0 = M0 * (uint64_t)c0;
+        uint64_t prod1 = M1 * (uint64_t)c2;
+        uint32_t hi0 = (uint32_t)(prod0 >> 32), lo0 = (uint32_t)prod0;
+        uint32_t hi1 = (uint32_t)(prod1 >> 32), lo1 = (uint32_t)prod1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        if (round != 9) { k0 += W0; k1 += W1; }
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* Layout helpers                                                                                 */
+/* ------------------------------------------------------------------------------------------- */
+static int64_t padded_len(int64_t len)
+{
+    return (len + DQO_GRANULE - 1) / DQO_GRANULE * DQO_GRANULE;
+}
+
+/* D' = total padded elements; -1 on invalid input */
+int64_t dqo_padded_elems(const int64_t *seg_len, int32_t n_seg)
+{
+    if (!seg_len || n_seg < 1) return -1;
+    int64_t total = 0;
+    for (int32_t l = 0; l < n_seg; ++l) {
+        if (seg_len[l] < 0) return -1;
+        total += padded_len(seg_len[l]);
+    }
+    return total;
+}
+
+/* start of segment l in the padded space */
+int64_t dqo_seg_start(const int64_t *seg_len, int32_t n_seg, int32_t l)
+{
+    int64_t p = 0;
+    (void)n_seg;
+    for (int32_t k = 0; k < l; ++k) p += padded_len(seg_len[k]);
+    return p;
+}
+
+/* bytes of one worker's message: sign plane D'/8 then level plane D'*b/8 */
+int64_t dqo_packed_bytes(const int64_t *seg_len, int32_t n_seg, int b)
+{
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0 || b < 1 || b > 8) return -1;
+    return dp / 8 + dp * b / 8;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* O1: per-worker, per-segment l2 norm (the ||g||_p of Eq. (5) with p = 2).                       */
+/* Squares of binary32 values are exact in binary64; the sum runs in index order in binary64.    */
+/* ------------------------------------------------------------------------------------------- */
+int dqo_norm(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+             int32_t M, float *norms /* [M][n_seg] */)
+{
+    if (!seg_len || !grads || !norms || n_seg < 1 || M < 1) return DQO_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < M; ++i) {
+        const float *g = grads + (int64_t)i * worker_stride;
+        int64_t start = 0;
+        for (int32_t l = 0; l < n_seg; ++l) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < seg_len[l]; ++j) {
+                double x = (double)g[start + j];
+                acc += x * x;
+            }
+            norms[(int64_t)i * n_seg + l] = (float)sqrt(acc);
+            start += padded_len(seg_len[l]);
+        }
+    }
+    return DQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* O2: the bit rule, Eq. (17), in level-bit convention.                                           */
+/*   G2 = (1/M) sum_i sum_l N_{i,l}^2                  (G-bar_t^2 of Lemma 1)                     */
+/*   s* = sqrt(T/eps_hat) * alpha^((T-1-t)/2) * sqrt(G2)                                          */
+/* Eq. (17) reads b_paper = log2(s* + 1) + 1, i.e. 2^(b_paper-1) - 1 = s*; with b = b_paper - 1   */
+/* and rounding up to an integer this is: the smallest b with 2^b - 1 >= s*, clamped.             */
+/* ------------------------------------------------------------------------------------------- */
+int dqo_select_bits(const float *norms /* [M][n_seg] */, int32_t M, int32_t n_seg, int64_t t,
+                    int64_t T, double eps_hat_q, double alpha, int b_min, int b_max, int *b_out,
+                    double *gbar_out)
+{
+    if (!norms || !b_out || M < 1 || n_seg < 1 || T < 1 || t < 0 || t >= T) return DQO_ERR_INVALID_ARG;
+    if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQO_ERR_INVALID_ARG;
+    if (b_min < 1 || b_max > 8 || b_min > b_max) return DQO_ERR_INVALID_ARG;
+    double sum = 0.0;
+    for (int32_t i = 0; i < M; ++i)
+        for (int32_t l = 0; l < n_seg; ++l) {
+            double n = (double)norms[(int64_t)i * n_seg + l];
+            sum += n * n;
+        }
+    double G2 = sum / (double)M;
+    double gbar = sqrt(G2);
+    double s_star = sqrt((double)T / eps_hat_q) * pow(alpha, (double)(T - 1 - t) / 2.0) * gbar;
+    int b = b_max;
+    for (int cand = b_min; cand <= b_max; ++cand) {
+        double levels = (double)((1 << cand) - 1);
+        if (levels >= s_star) { b = cand; break; }
+    }
+    *b_out = b;
+    if (gbar_out) *gbar_out = gbar;
+    return DQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* O3: sign and stochastic level of every element (Eq. (5)-(6)).                                  */
+/* sign[i][P], level[i][P] are one byte per padded element; pads get 0/0.                         */
+/* ------------------------------------------------------------------------------------------- */
+static int norm_is_usable(float N)
+{
+    return N >= 0x1p-100f; /* false for zero, tiny and NaN norms: the zero-vector path */
+}
+
+int dqo_quantize(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+                 int32_t M, const float *norms /* [M][n_seg] */, int b, uint64_t seed,
+                 uint32_t step, uint32_t worker_base, uint8_t *sign /* [M][D'] */,
+                 uint8_t *level /* [M][D'] */)
+{
+    if (!seg_len || !grads || !norms || !sign || !level) return DQO_ERR_INVALID_ARG;
+    if (n_seg < 1 || M < 1 || b < 1 || b > 8) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    const uint32_t s_int = (1u << b) - 1u;
+    const float s = (float)s_int;
+    const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < M; ++i) {
+        const float *g = grads + (int64_t)i * worker_stride;
+        uint8_t *sg = sign + (int64_t)i * dp;
+        uint8_t *lv = level + (int64_t)i * dp;
+        memset(sg, 0, (size_t)dp);
+        memset(lv, 0, (size_t)dp);
+        int64_t start = 0;
+        for (int32_t l = 0; l < n_seg; ++l) {
+            const float N = norms[(int64_t)i * n_seg + l];
+            const int usable = norm_is_usable(N);
+            const float scale = usable ? s / N : 0.0f; /* one binary32 division per segment */
+            for (int64_t j = 0; j < seg_len[l]; ++j) {
+                const int64_t P = start + j;
+                const float x = g[P];
+                uint32_t bits;
+                memcpy(&bits, &x, 4);
+                sg[P] = (uint8_t)(bits >> 31);
+                if (!usable) { lv[P] = 0; continue; }
+                float a = fabsf(x) * scale;       /* s*|g_j|/||g||, one rounding            */
+                a = fminf(a, s);                  /* |g_j|/||g|| may round above 1          */
+                const float fl = floorf(a);       /* l of Eq. (6)                            */
+                const float p = a - fl;           /* p_r of Eq. (6); exact                   */
+                const uint64_t quad = (uint64_t)P >> 2;
+                const uint32_t ctr[4] = { (uint32_t)quad, (uint32_t)(quad >> 32),
+                                          worker_base + (uint32_t)i, step };
+                uint32_t r[4];
+                dqo_philox4x32_10(ctr, key, r);
+                const float u = (float)(r[P & 3] >> 8) * 0x1p-24f; /* exact, in [0,1)        */
+                lv[P] = (uint8_t)((uint32_t)fl + (u < p ? 1u : 0u));
+            }
+            start += padded_len(seg_len[l]);
+        }
+    }
+    return DQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* O4: the message.  Sign plane: bit P of a little-endian bit array (byte P>>3, bit P&7).         */
+/* Level plane: element P occupies bits [P*b, P*b+b), least significant level bit first.          */
+/* ------------------------------------------------------------------------------------------- */
+static void put_bits(uint8_t *plane, int64_t bit_pos, int width, uint32_t value)
+{
+    for (int k = 0; k < width; ++k) {
+        int64_t q = bit_pos + k;
+        if ((value >> k) & 1u) plane[q >> 3] |= (uint8_t)(1u << (q & 7));
+    }
+}
+
+static uint32_t get_bits(const uint8_t *plane, int64_t bit_pos, int width)
+{
+    uint32_t value = 0;
+    for (int k = 0; k < width; ++k) {
+        int64_t q = bit_pos + k;
+        value |= (uint32_t)((plane[q >> 3] >> (q & 7)) & 1u) << k;
+    }
+    return value;
+}
+
+/* one worker: codes (one byte each) -> message of dp/8 + dp*b/8 bytes */
+int dqo_pack(const uint8_t *sign, const uint8_t *level, int64_t dp, int b, uint8_t *packed)
+{
+    if (!sign || !level || !packed || dp < 0 || dp % DQO_GRANULE || b < 1 || b > 8)
+        return DQO_ERR_INVALID_ARG;
+    uint8_t *sign_plane = packed;
+    uint8_t *level_plane = packed + dp / 8;
+    memset(packed, 0, (size_t)(dp / 8 + dp * b / 8));
+    for (int64_t P = 0; P < dp; ++P) {
+        put_bits(sign_plane, P, 1, sign[P]);
+        put_bits(level_plane, P * b, b, level[P]);
+    }
+    return DQO_OK;
+}
+
+int dqo_unpack(const uint8_t *packed, int64_t dp, int b, uint8_t *sign, uint8_t *level)
+{
+    if (!sign || !level || !packed || dp < 0 || dp % DQO_GRANULE || b < 1 || b > 8)
+        return DQO_ERR_INVALID_ARG;
+    const uint8_t *sign_plane = packed;
+    const uint8_t *level_plane = packed + dp / 8;
+    for (int64_t P = 0; P < dp; ++P) {
+        sign[P] = (uint8_t)get_bits(sign_plane, P, 1);
+        level[P] = (uint8_t)get_bits(level_plane, P * b, b);
+    }
+    return DQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* O5: dequantize and average (Algorithm 1, server side; Eq. (2) divides by W).                   */
+/*   unit_{i,l} = N_{i,l} / s  (binary32; 0 on the zero-vector path)                              */
+/*   v_{i,P} = level * unit, negated when the sign bit is set                                     */
+/*   out_P = (float)( (sum_i (double)v_{i,P}) / M ); pads are +0.                                 */
+/* ------------------------------------------------------------------------------------------- */
+int dqo_dequant_reduce(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign /* [M][D'] */,
+                       const uint8_t *level /* [M][D'] */, int32_t M,
+                       const float *norms /* [M][n_seg] */, int b, float *out /* [D'] */)
+{
+    if (!seg_len || !sign || !level || !norms || !out) return DQO_ERR_INVALID_ARG;
+    if (n_seg < 1 || M < 1 || b < 1 || b > 8) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    const float s = (float)((1u << b) - 1u);
+    for (int64_t P = 0; P < dp; ++P) out[P] = 0.0f;
+    int64_t start = 0;
+    for (int32_t l = 0; l < n_seg; ++l) {
+        const int64_t len = seg_len[l];
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < len; ++j) {
+            const int64_t P = start + j;
+            double acc = 0.0;
+            for (int32_t i = 0; i < M; ++i) {
+                const float N = norms[(int64_t)i * n_seg + l];
+                const float unit = norm_is_usable(N) ? N / s : 0.0f;
+                float v = (float)level[(int64_t)i * dp + P] * unit;
+                if (sign[(int64_t)i * dp + P]) v = -v;
+                acc += (double)v;
+            }
+            out[P] = (float)(acc / (double)M);
+        }
+        start += padded_len(len);
+    }
+    return DQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* Whole passes on messages, the shape the GPU library's entry points have.                       */
+/* ------------------------------------------------------------------------------------------- */
+
+/* quantize + pack for M workers; worker i's message starts at packed + i*packed_stride.
+ * scratch must hold 2*D' bytes per worker: 2*M*D' in total. */
+int dqo_quantize_pack(const int64_t *seg_len, int32_t n_seg, const float *grads,
+                      int64_t worker_stride, int32_t M, const float *norms, int b, uint64_t seed,
+                      uint32_t step, uint32_t worker_base, uint8_t *packed, int64_t packed_stride,
+                      uint8_t *scratch)
+{
+    if (!packed || !scratch) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0 || b < 1 || b > 8 || packed_stride < dp / 8 + dp * b / 8) return DQO_ERR_INVALID_ARG;
+    uint8_t *sign = scratch, *level = scratch + (int64_t)M * dp;
+    int rc = dqo_quantize(seg_len, n_seg, grads, worker_stride, M, norms, b, seed, step,
+                          worker_base, sign, level);
+    if (rc != DQO_OK) return rc;
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < M; ++i)
+        dqo_pack(sign + (int64_t)i * dp, level + (int64_t)i * dp, dp, b,
+                 packed + (int64_t)i * packed_stride);
+    return DQO_OK;
+}
+
+/* unpack + dequantize + average; scratch as above */
+int dqo_unpack_dequant_reduce(const int64_t *seg_len, int32_t n_seg, const uint8_t *packed,
+                              int64_t packed_stride, int32_t M, const float *norms, int b,
+                              float *out, uint8_t *scratch)
+{
+    if (!packed || !scratch) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0 || b < 1 || b > 8 || M < 1) return DQO_ERR_INVALID_ARG;
+    uint8_t *sign = scratch, *level = scratch + (int64_t)M * dp;
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < M; ++i)
+        dqo_unpack(packed + (int64_t)i * packed_stride, dp, b, sign + (int64_t)i * dp,
+                   level + (int64_t)i * dp);
+    return dqo_dequant_reduce(seg_len, n_seg, sign, level, M, norms, b, out);
+}
+
+/* threads the parallel loops use (1 when built without OpenMP) */
+#ifdef _OPENMP
+#include <omp.h>
+int dqo_num_threads(void) { return omp_get_max_threads(); }
+void dqo_set_num_threads(int n) { if (n > 0) omp_set_num_threads(n); }
+#else
+int dqo_num_threads(void) { return 1; }
+void dqo_set_num_threads(int n) { (void)n; }
+#endif
