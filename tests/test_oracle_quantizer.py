@@ -233,3 +233,33 @@ def test_steps_workers_and_seeds_decorrelate(oracle):
     assert np.array_equal(l0, l0b)            # and the draw is reproducible
     _, lw = oracle.quantize([512], grads[1:], norms[1:], 6, 1, 0, worker_base=1)
     assert np.array_equal(lw[0], l0[1])       # worker ids are global
+
+
+def test_round_up_threshold_is_strict_and_24_bit(oracle):
+    """With N = s the scale is exactly 1 and a = p = g for g in [0,1).  Place g exactly on the
+    element's own uniform u = (r>>8)/2^24 (r from the big-integer Philox): u < p is false there,
+    and true one lattice step above -- so the comparison is strict and u has 24 bits."""
+    b = 3
+    N = np.float32(7.0)
+    step, worker = 5, 2
+    d = 48
+    dp = oracle.padded_elems([d])
+    u = np.array([pyref.element_random_word(P, worker, step, SEED) >> 8 for P in range(d)], dtype=np.int64)
+    assert (u & 1).any() and not (u & 1).all()
+    for delta, want in ((0, 0), (1, 1), (-1, 0)):
+        g = np.zeros((1, dp), dtype=np.float32)
+        g[0, :d] = ((u + delta).astype(np.float64) * 2.0 ** -24).astype(np.float32)
+        ok = (u + delta > 0) & (u + delta < (1 << 24))
+        _, level = oracle.quantize([d], g, np.array([[N]], dtype=np.float32), b, SEED, step, worker_base=worker)
+        assert np.all(level[0, :d][ok] == want)
+
+
+def test_norm_smaller_than_an_element_still_clamps(oracle):
+    """The norm is an input: if it is too small for the data (a = 2s here) the level stays s."""
+    g = np.zeros((1, 128), dtype=np.float32)
+    g[0, :3] = [0.5, -1.0, 0.25]
+    for b in (1, 4, 8):
+        s = (1 << b) - 1
+        _, level = oracle.quantize([3], g, np.array([[0.5]], dtype=np.float32), b, SEED, 0)
+        assert level[0, 0] == s and level[0, 1] == s
+        assert level[0, 2] in (s // 2, s // 2 + 1)
