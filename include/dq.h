@@ -1,0 +1,118 @@
+/*
+ * dq -- MI355X (gfx950) stochastic gradient quantizer: the per-iteration data-parallel hot path of
+ * DQ-SGD (arXiv 2107.14575, "Dynamic Quantization in SGD for Communication-Efficient Distributed
+ * Learning").
+ *
+ * One step of the path, for M workers simulated on one GPU (Algorithm 1):
+ *     dq_norm                    ||g^(i)||_2 per worker and tensor          (the norm in Eq. (5))
+ *     dq_select_bits             b_t from the dynamic rule                   (Eq. (17))
+ *     dq_quantize_pack           sign + stochastic level per element, packed (Eq. (5)-(6), Eq. (7))
+ *     dq_unpack_dequant_reduce   server average of the M messages            (Alg. 1 "Average", Eq. (2))
+ *
+ * CONVENTIONS
+ *   b       number of LEVEL bits, 1..8.  s = 2^b - 1 quantization levels; one element costs b + 1
+ *           bits on the wire (sign + level).  The paper counts the sign bit inside its b, so
+ *           b_paper = b + 1 and its s = 2^(b_paper-1) - 1 is the same s.
+ *   layout  Tensors ("segments") live in a padded flat index space P.  Segment l starts at P_l with
+ *           P_0 = 0 and P_{l+1} = P_l + 128*ceil(len_l/128); D' = P_{n_seg}.  Gradients, the output
+ *           and both bit planes are indexed by P.  Pad elements are ignored on input, encode as
+ *           zero bits and are written as +0.0f on output.
+ *   message One worker's message is [sign plane | level plane]: sign plane = D'/8 bytes, bit P of a
+ *           little-endian bit array (byte P>>3, bit P&7), set when the IEEE sign bit of g_P is set;
+ *           level plane = D'*b/8 bytes, element P in bits [P*b, P*b+b), least significant level bit
+ *           first.  The norms and b travel beside the message (the B_pre bits of Eq. (7)).
+ *   random  Element P of worker w at iteration `step` uses word P&3 of
+ *           Philox4x32-10(counter = {lo32(P>>2), hi32(P>>2), w, step}, key = {lo32(seed), hi32(seed)});
+ *           u = (word >> 8) * 2^-24; the level rounds up iff u < p_r (Eq. (6)).
+ *
+ * MEMORY    Pointers named *_dev are device pointers on the plan's GPU, 16-byte aligned, owned by
+ *           the caller and borrowed until the enqueued work has finished.  Pointers named *_host
+ *           are host pointers, read or written before the call returns.  The library allocates
+ *           only the plan's tables (dq_plan_create / dq_plan_destroy).
+ * STREAMS   Device entry points enqueue on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *           the default stream) and return without synchronising.
+ * ERRORS    Every int-returning function returns DQ_OK (0) or a negative dq_status; nothing
+ *           throws, aborts or sets errno.  On error nothing has been enqueued.
+ */
+#ifndef DQ_H
+#define DQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dq_status {
+    DQ_OK = 0,
+    DQ_ERR_INVALID_ARG = -1, /* null pointer, b outside 1..8, M < 1, misalignment, short stride ... */
+    DQ_ERR_HIP = -2,         /* a HIP runtime call failed (no device, launch failure)            */
+    DQ_ERR_ALLOC = -3        /* host or device allocation of the plan failed                     */
+} dq_status;
+
+#define DQ_GRANULE 128      /* segments are padded to a multiple of this many elements            */
+#define DQ_MAX_WORKERS 64   /* largest M one call accepts                                         */
+#define DQ_MIN_NORM 0x1p-100f /* a norm that is not >= this (zero, tiny, NaN) quantizes to zeros   */
+
+typedef struct dq_plan dq_plan_t; /* opaque, immutable after creation, bound to one GPU */
+
+/* Builds the layout of n_seg tensors of seg_len_host[l] >= 0 elements and uploads its tables to
+ * the current HIP device.  Without a usable device the plan is still created for the host-side
+ * size queries below, and every device entry point given it returns DQ_ERR_HIP. */
+int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_plan_t** plan_out);
+void dq_plan_destroy(dq_plan_t* plan);
+
+int32_t dq_plan_num_segments(const dq_plan_t* plan);
+int64_t dq_plan_padded_elems(const dq_plan_t* plan);               /* D'                              */
+int64_t dq_plan_segment_start(const dq_plan_t* plan, int32_t l);   /* P_l; -1 if l is out of range    */
+int64_t dq_packed_bytes(const dq_plan_t* plan, int b);             /* per worker: D'/8 + D'*b/8; -1 on bad b */
+int64_t dq_workspace_bytes(const dq_plan_t* plan, int M);          /* scratch dq_norm needs; -1 on bad M */
+int dq_plan_has_device(const dq_plan_t* plan);                     /* 1 if the tables are on a GPU    */
+
+/* N[i][l] = ||g_l^(i)||_2, the norm of Eq. (5) (p = 2), for worker i's tensor l.
+ *   grads_dev            [M] gradients in padded layout, worker i at grads_dev + i*worker_stride_elems
+ *   worker_stride_elems  >= D', multiple of 4
+ *   norms_dev            [M][n_seg] float, written
+ *   workspace_dev        dq_workspace_bytes(plan, M) bytes of scratch, 16-byte aligned
+ * Squares accumulate in binary64 in a fixed order, so the result is reproducible run to run. */
+int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
+            float* norms_dev, void* workspace_dev, void* hip_stream);
+
+/* The bit rule, Eq. (17), in level-bit convention.  Pure host code, no GPU work.
+ *   Gbar^2 = (1/M) sum_i sum_l N[i][l]^2        (mean square of the workers' gradient norms, Lemma 1)
+ *   s*     = sqrt(T/eps_hat_q) * alpha^((T-1-t)/2) * Gbar
+ *   b      = the smallest integer in [b_min, b_max] with 2^b - 1 >= s*, else b_max
+ * which is Eq. (17) rounded up to an integer (b_paper = b + 1), so the error constraint of
+ * Eq. (16) still holds.  Requires 0 <= t < T, eps_hat_q > 0, 0 < alpha <= 1, 1 <= b_min <= b_max <= 8.
+ *   norms_host  [M][n_seg] float;  b_out receives b;  gbar_out (nullable) receives Gbar. */
+int dq_select_bits(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
+                   double eps_hat_q, double alpha, int b_min, int b_max, int* b_out,
+                   double* gbar_out);
+
+/* EWU quantizer of Eq. (5)-(6) fused with the packing of the message whose size Eq. (7) counts.
+ * For worker w = worker_base + i, element P of tensor l with norm N = norms_dev[i][l]:
+ *     a = min(|g_P| * (s / N), s);  level = floor(a) + [u < a - floor(a)]      (binary32, no FMA)
+ * and level = 0 for every element of a tensor whose norm is not >= DQ_MIN_NORM.
+ *   norms_dev   [M][n_seg] float, read (normally dq_norm's output)
+ *   packed_dev  [M] messages, worker i at packed_dev + i*packed_worker_stride_bytes, written in
+ *               full (dq_packed_bytes bytes each, pad bits zero)
+ *   packed_worker_stride_bytes  >= dq_packed_bytes(plan, b), multiple of 16
+ * Non-finite gradient values never cause an out-of-range access; their codes are unspecified. */
+int dq_quantize_pack(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                     int M, const float* norms_dev, int b, uint64_t seed, uint32_t step,
+                     uint32_t worker_base, uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                     void* hip_stream);
+
+/* Server side of Algorithm 1: out_P = (1/M) sum_i sgn_{i,P} * level_{i,P} * (N[i][l] / s), every
+ * worker's message read once.  The sum runs in binary32 over i ascending, then times 1/M.
+ *   out_dev  [D'] float, written in full (pads +0.0f). */
+int dq_unpack_dequant_reduce(const dq_plan_t* plan, const uint8_t* packed_dev,
+                             int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
+                             int b, float* out_dev, void* hip_stream);
+
+const char* dq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DQ_H */

@@ -169,15 +169,20 @@ static int norm_is_usable(float N)
     return N >= 0x1p-100f; /* false for zero, tiny and NaN norms: the zero-vector path */
 }
 
-int dqo_quantize(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
-                 int32_t M, const float *norms /* [M][n_seg] */, int b, uint64_t seed,
-                 uint32_t step, uint32_t worker_base, uint8_t *sign /* [M][D'] */,
-                 uint8_t *level /* [M][D'] */)
+/* Range form: only padded indices p_begin <= P < p_end (both multiples of 128) are computed.
+ * grads points at element p_begin of worker 0 and worker i's slice starts worker_stride later;
+ * sign/level are [M][p_end - p_begin].  The Philox counter uses the absolute index P. */
+int dqo_quantize_range(const int64_t *seg_len, int32_t n_seg, const float *grads,
+                       int64_t worker_stride, int32_t M, const float *norms /* [M][n_seg] */, int b,
+                       uint64_t seed, uint32_t step, uint32_t worker_base, int64_t p_begin,
+                       int64_t p_end, uint8_t *sign, uint8_t *level)
 {
     if (!seg_len || !grads || !norms || !sign || !level) return DQO_ERR_INVALID_ARG;
     if (n_seg < 1 || M < 1 || b < 1 || b > 8) return DQO_ERR_INVALID_ARG;
     int64_t dp = dqo_padded_elems(seg_len, n_seg);
-    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    if (dp < 0 || p_begin < 0 || p_end > dp || p_begin > p_end) return DQO_ERR_INVALID_ARG;
+    if (p_begin % DQO_GRANULE || p_end % DQO_GRANULE) return DQO_ERR_INVALID_ARG;
+    const int64_t span = p_end - p_begin;
     const uint32_t s_int = (1u << b) - 1u;
     const float s = (float)s_int;
     const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
@@ -185,10 +190,10 @@ int dqo_quantize(const int64_t *seg_len, int32_t n_seg, const float *grads, int6
 #pragma omp parallel for schedule(static)
     for (int32_t i = 0; i < M; ++i) {
         const float *g = grads + (int64_t)i * worker_stride;
-        uint8_t *sg = sign + (int64_t)i * dp;
-        uint8_t *lv = level + (int64_t)i * dp;
-        memset(sg, 0, (size_t)dp);
-        memset(lv, 0, (size_t)dp);
+        uint8_t *sg = sign + (int64_t)i * span;
+        uint8_t *lv = level + (int64_t)i * span;
+        memset(sg, 0, (size_t)span);
+        memset(lv, 0, (size_t)span);
         int64_t start = 0;
         for (int32_t l = 0; l < n_seg; ++l) {
             const float N = norms[(int64_t)i * n_seg + l];
@@ -196,11 +201,13 @@ int dqo_quantize(const int64_t *seg_len, int32_t n_seg, const float *grads, int6
             const float scale = usable ? s / N : 0.0f; /* one binary32 division per segment */
             for (int64_t j = 0; j < seg_len[l]; ++j) {
                 const int64_t P = start + j;
-                const float x = g[P];
+                if (P < p_begin || P >= p_end) continue;
+                const int64_t q = P - p_begin;
+                const float x = g[q];
                 uint32_t bits;
                 memcpy(&bits, &x, 4);
-                sg[P] = (uint8_t)(bits >> 31);
-                if (!usable) { lv[P] = 0; continue; }
+                sg[q] = (uint8_t)(bits >> 31);
+                if (!usable) { lv[q] = 0; continue; }
                 float a = fabsf(x) * scale;       /* s*|g_j|/||g||, one rounding            */
                 a = fminf(a, s);                  /* |g_j|/||g|| may round above 1          */
                 const float fl = floorf(a);       /* l of Eq. (6)                            */
@@ -211,12 +218,23 @@ int dqo_quantize(const int64_t *seg_len, int32_t n_seg, const float *grads, int6
                 uint32_t r[4];
                 dqo_philox4x32_10(ctr, key, r);
                 const float u = (float)(r[P & 3] >> 8) * 0x1p-24f; /* exact, in [0,1)        */
-                lv[P] = (uint8_t)((uint32_t)fl + (u < p ? 1u : 0u));
+                lv[q] = (uint8_t)((uint32_t)fl + (u < p ? 1u : 0u));
             }
             start += padded_len(seg_len[l]);
         }
     }
     return DQO_OK;
+}
+
+int dqo_quantize(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+                 int32_t M, const float *norms /* [M][n_seg] */, int b, uint64_t seed,
+                 uint32_t step, uint32_t worker_base, uint8_t *sign /* [M][D'] */,
+                 uint8_t *level /* [M][D'] */)
+{
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    return dqo_quantize_range(seg_len, n_seg, grads, worker_stride, M, norms, b, seed, step,
+                              worker_base, 0, dp, sign, level);
 }
 
 /* ------------------------------------------------------------------------------------------- */
@@ -275,35 +293,50 @@ int dqo_unpack(const uint8_t *packed, int64_t dp, int b, uint8_t *sign, uint8_t 
 /*   v_{i,P} = level * unit, negated when the sign bit is set                                     */
 /*   out_P = (float)( (sum_i (double)v_{i,P}) / M ); pads are +0.                                 */
 /* ------------------------------------------------------------------------------------------- */
-int dqo_dequant_reduce(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign /* [M][D'] */,
-                       const uint8_t *level /* [M][D'] */, int32_t M,
-                       const float *norms /* [M][n_seg] */, int b, float *out /* [D'] */)
+/* Range form: codes are [M][p_end - p_begin] for padded indices p_begin <= P < p_end (multiples
+ * of 128); out has p_end - p_begin entries. */
+int dqo_dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign,
+                             const uint8_t *level, int32_t M, const float *norms /* [M][n_seg] */,
+                             int b, int64_t p_begin, int64_t p_end, float *out)
 {
     if (!seg_len || !sign || !level || !norms || !out) return DQO_ERR_INVALID_ARG;
     if (n_seg < 1 || M < 1 || b < 1 || b > 8) return DQO_ERR_INVALID_ARG;
     int64_t dp = dqo_padded_elems(seg_len, n_seg);
-    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    if (dp < 0 || p_begin < 0 || p_end > dp || p_begin > p_end) return DQO_ERR_INVALID_ARG;
+    if (p_begin % DQO_GRANULE || p_end % DQO_GRANULE) return DQO_ERR_INVALID_ARG;
+    const int64_t span = p_end - p_begin;
     const float s = (float)((1u << b) - 1u);
-    for (int64_t P = 0; P < dp; ++P) out[P] = 0.0f;
+    for (int64_t q = 0; q < span; ++q) out[q] = 0.0f;
     int64_t start = 0;
     for (int32_t l = 0; l < n_seg; ++l) {
         const int64_t len = seg_len[l];
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < len; ++j) {
             const int64_t P = start + j;
+            if (P < p_begin || P >= p_end) continue;
+            const int64_t q = P - p_begin;
             double acc = 0.0;
             for (int32_t i = 0; i < M; ++i) {
                 const float N = norms[(int64_t)i * n_seg + l];
                 const float unit = norm_is_usable(N) ? N / s : 0.0f;
-                float v = (float)level[(int64_t)i * dp + P] * unit;
-                if (sign[(int64_t)i * dp + P]) v = -v;
+                float v = (float)level[(int64_t)i * span + q] * unit;
+                if (sign[(int64_t)i * span + q]) v = -v;
                 acc += (double)v;
             }
-            out[P] = (float)(acc / (double)M);
+            out[q] = (float)(acc / (double)M);
         }
         start += padded_len(len);
     }
     return DQO_OK;
+}
+
+int dqo_dequant_reduce(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign /* [M][D'] */,
+                       const uint8_t *level /* [M][D'] */, int32_t M,
+                       const float *norms /* [M][n_seg] */, int b, float *out /* [D'] */)
+{
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    return dqo_dequant_reduce_range(seg_len, n_seg, sign, level, M, norms, b, 0, dp, out);
 }
 
 /* ------------------------------------------------------------------------------------------- */

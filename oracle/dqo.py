@@ -55,6 +55,11 @@ def lib():
                                       C.POINTER(C.c_int), C.POINTER(C.c_double)]
         L.dqo_quantize.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, f32p, C.c_int,
                                    C.c_uint64, C.c_uint32, C.c_uint32, u8p, u8p]
+        L.dqo_quantize_range.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, f32p, C.c_int,
+                                         C.c_uint64, C.c_uint32, C.c_uint32, C.c_int64, C.c_int64,
+                                         u8p, u8p]
+        L.dqo_dequant_reduce_range.argtypes = [i64p, C.c_int32, u8p, u8p, C.c_int32, f32p, C.c_int,
+                                               C.c_int64, C.c_int64, f32p]
         L.dqo_pack.argtypes = [u8p, u8p, C.c_int64, C.c_int, u8p]
         L.dqo_unpack.argtypes = [u8p, C.c_int64, C.c_int, u8p, u8p]
         L.dqo_dequant_reduce.argtypes = [i64p, C.c_int32, u8p, u8p, C.c_int32, f32p, C.c_int, f32p]
@@ -158,6 +163,38 @@ def quantize(seg_len, grads, norms, b, seed, step, worker_base=0):
                               _p(n, C.c_float), b, seed, step, worker_base,
                               _p(sign, C.c_uint8), _p(level, C.c_uint8)), "quantize")
     return sign, level
+
+
+def quantize_range(seg_len, grads_slice, norms, b, seed, step, p_begin, p_end, worker_base=0):
+    """Codes of padded indices [p_begin, p_end) only; grads_slice is [M][>= p_end - p_begin] and
+    holds exactly those elements.  -> (sign, level) uint8 [M][p_end - p_begin]."""
+    s = _segs(seg_len)
+    span = int(p_end - p_begin)
+    g = _grads2d(grads_slice, span)
+    M = g.shape[0]
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    sign = np.zeros((M, span), dtype=np.uint8)
+    level = np.zeros((M, span), dtype=np.uint8)
+    _check(lib().dqo_quantize_range(_p(s, C.c_int64), s.size, _p(g, C.c_float), g.shape[1], M,
+                                    _p(n, C.c_float), b, seed, step, worker_base, p_begin, p_end,
+                                    _p(sign, C.c_uint8), _p(level, C.c_uint8)), "quantize_range")
+    return sign, level
+
+
+def dequant_reduce_range(seg_len, sign, level, norms, b, p_begin, p_end):
+    s = _segs(seg_len)
+    span = int(p_end - p_begin)
+    sg = np.ascontiguousarray(np.asarray(sign, dtype=np.uint8))
+    lv = np.ascontiguousarray(np.asarray(level, dtype=np.uint8))
+    M = sg.shape[0]
+    if sg.shape != (M, span) or lv.shape != (M, span):
+        raise ValueError("codes must be [M][p_end - p_begin]")
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    out = np.zeros(span, dtype=np.float32)
+    _check(lib().dqo_dequant_reduce_range(_p(s, C.c_int64), s.size, _p(sg, C.c_uint8),
+                                          _p(lv, C.c_uint8), M, _p(n, C.c_float), b, p_begin, p_end,
+                                          _p(out, C.c_float)), "dequant_reduce_range")
+    return out
 
 
 def pack(sign, level, b):

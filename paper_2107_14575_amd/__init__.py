@@ -1,0 +1,17 @@
+"""MI355X-native stochastic gradient quantizer: the data-parallel hot path of DQ-SGD
+(arXiv 2107.14575).  Every step of the path runs in hand-written HIP kernels behind the C ABI
+declared in ``include/dq.h``; this package only marshals arguments (``binding``) and holds the
+seeded synthetic workload generators (``workloads``)."""
+from .binding import (  # noqa: F401
+    DQError,
+    Plan,
+    library_path,
+    load_library,
+    norm,
+    quantize_pack,
+    select_bits,
+    unpack_dequant_reduce,
+)
+
+__all__ = ["DQError", "Plan", "library_path", "load_library", "norm", "quantize_pack",
+           "select_bits", "unpack_dequant_reduce"]

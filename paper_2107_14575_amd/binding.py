@@ -1,0 +1,182 @@
+"""Thin ctypes binding of libdq.so.  Argument marshalling only: pointers, sizes and the current
+torch stream go straight to the C ABI (``include/dq.h``); no arithmetic of the method happens here
+and there is no fallback -- without the built library every call raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libdq.so")
+
+DQ_OK = 0
+GRANULE = 128
+MAX_WORKERS = 64
+
+EXPORTS = (
+    "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems",
+    "dq_plan_segment_start", "dq_packed_bytes", "dq_workspace_bytes", "dq_plan_has_device",
+    "dq_norm", "dq_select_bits", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_status_string",
+)
+
+
+class DQError(RuntimeError):
+    def __init__(self, what: str, status: int, text: str):
+        super().__init__(f"{what}: {text} (status {status})")
+        self.status = status
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """dlopen the in-tree libdq.so; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2107_14575_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(_LIB_PATH)
+    vp, i64, i32, f32p = C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_float)
+    L.dq_plan_create.argtypes = [C.POINTER(i64), i32, C.POINTER(vp)]
+    L.dq_plan_create.restype = C.c_int
+    L.dq_plan_destroy.argtypes = [vp]
+    L.dq_plan_destroy.restype = None
+    L.dq_plan_num_segments.argtypes = [vp]
+    L.dq_plan_num_segments.restype = i32
+    L.dq_plan_padded_elems.argtypes = [vp]
+    L.dq_plan_padded_elems.restype = i64
+    L.dq_plan_segment_start.argtypes = [vp, i32]
+    L.dq_plan_segment_start.restype = i64
+    L.dq_packed_bytes.argtypes = [vp, C.c_int]
+    L.dq_packed_bytes.restype = i64
+    L.dq_workspace_bytes.argtypes = [vp, C.c_int]
+    L.dq_workspace_bytes.restype = i64
+    L.dq_plan_has_device.argtypes = [vp]
+    L.dq_plan_has_device.restype = C.c_int
+    L.dq_norm.argtypes = [vp, vp, i64, C.c_int, vp, vp, vp]
+    L.dq_norm.restype = C.c_int
+    L.dq_select_bits.argtypes = [f32p, C.c_int, C.c_int, i64, i64, C.c_double, C.c_double,
+                                 C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_double)]
+    L.dq_select_bits.restype = C.c_int
+    L.dq_quantize_pack.argtypes = [vp, vp, i64, C.c_int, vp, C.c_int, C.c_uint64, C.c_uint32,
+                                   C.c_uint32, vp, i64, vp]
+    L.dq_quantize_pack.restype = C.c_int
+    L.dq_unpack_dequant_reduce.argtypes = [vp, vp, i64, C.c_int, vp, C.c_int, vp, vp]
+    L.dq_unpack_dequant_reduce.restype = C.c_int
+    L.dq_status_string.argtypes = [C.c_int]
+    L.dq_status_string.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def _check(what: str, status: int) -> None:
+    if status != DQ_OK:
+        raise DQError(what, status, load_library().dq_status_string(status).decode())
+
+
+def _stream_handle(stream) -> int:
+    """hipStream_t of a torch stream (default: torch's current stream), as an integer."""
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+class Plan:
+    """Layout of a list of tensors in the padded flat index space (see ``include/dq.h``)."""
+
+    def __init__(self, seg_len):
+        lens = np.ascontiguousarray(np.asarray(seg_len, dtype=np.int64).reshape(-1))
+        L = load_library()
+        handle = C.c_void_p()
+        _check("dq_plan_create",
+               L.dq_plan_create(lens.ctypes.data_as(C.POINTER(C.c_int64)), lens.size, C.byref(handle)))
+        self._h = handle
+        self.seg_len = lens
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            load_library().dq_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("plan is closed")
+        return self._h
+
+    @property
+    def n_seg(self) -> int:
+        return int(load_library().dq_plan_num_segments(self.handle))
+
+    @property
+    def padded_elems(self) -> int:
+        return int(load_library().dq_plan_padded_elems(self.handle))
+
+    @property
+    def has_device(self) -> bool:
+        return bool(load_library().dq_plan_has_device(self.handle))
+
+    def segment_start(self, l: int) -> int:
+        return int(load_library().dq_plan_segment_start(self.handle, l))
+
+    def packed_bytes(self, b: int) -> int:
+        return int(load_library().dq_packed_bytes(self.handle, b))
+
+    def workspace_bytes(self, M: int) -> int:
+        return int(load_library().dq_workspace_bytes(self.handle, M))
+
+
+def norm(plan: Plan, grads, norms_out, workspace, stream=None) -> None:
+    """grads: float32 CUDA tensor [M][stride]; norms_out: float32 CUDA [M][n_seg];
+    workspace: CUDA byte tensor of plan.workspace_bytes(M)."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    _check("dq_norm", load_library().dq_norm(plan.handle, grads.data_ptr(), stride, M,
+                                             norms_out.data_ptr(), workspace.data_ptr(),
+                                             _stream_handle(stream)))
+
+
+def select_bits(norms_host, t: int, T: int, eps_hat_q: float, alpha: float, b_min: int, b_max: int):
+    """norms_host: host float32 array [M][n_seg] -> (b, Gbar)."""
+    n = np.ascontiguousarray(np.asarray(norms_host, dtype=np.float32))
+    if n.ndim != 2:
+        raise ValueError("norms must be [M][n_seg]")
+    b = C.c_int(0)
+    gbar = C.c_double(0.0)
+    _check("dq_select_bits",
+           load_library().dq_select_bits(n.ctypes.data_as(C.POINTER(C.c_float)), n.shape[0], n.shape[1],
+                                         t, T, eps_hat_q, alpha, b_min, b_max, C.byref(b), C.byref(gbar)))
+    return int(b.value), float(gbar.value)
+
+
+def quantize_pack(plan: Plan, grads, norms, b: int, seed: int, step: int, packed_out,
+                  worker_base: int = 0, stream=None) -> None:
+    """packed_out: uint8 CUDA tensor [M][stride_bytes], written in full per message."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    _check("dq_quantize_pack",
+           load_library().dq_quantize_pack(plan.handle, grads.data_ptr(), stride, M, norms.data_ptr(), b,
+                                           seed, step, worker_base, packed_out.data_ptr(),
+                                           int(packed_out.stride(0)), _stream_handle(stream)))
+
+
+def unpack_dequant_reduce(plan: Plan, packed, norms, b: int, out, stream=None) -> None:
+    """packed: uint8 CUDA [M][stride_bytes]; out: float32 CUDA [D']."""
+    M = int(packed.shape[0])
+    _check("dq_unpack_dequant_reduce",
+           load_library().dq_unpack_dequant_reduce(plan.handle, packed.data_ptr(), int(packed.stride(0)), M,
+                                                   norms.data_ptr(), b, out.data_ptr(),
+                                                   _stream_handle(stream)))

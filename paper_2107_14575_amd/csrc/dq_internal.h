@@ -1,0 +1,65 @@
+// Internal declarations shared by the translation units of libdq (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dq.h"
+
+// One piece of a segment handed to one workgroup of the norm kernel: `count` valid elements
+// starting at padded index `start` (a multiple of 128), all inside segment `seg`.
+struct dq_norm_item {
+    int64_t start;
+    int32_t count;
+    int32_t seg;
+};
+
+constexpr int DQ_NORM_CHUNK = 4096; // elements per norm item (one workgroup, 4 float4 per lane)
+
+struct dq_plan {
+    int32_t n_seg;
+    int64_t padded_elems; // D'
+    int64_t* seg_len;     // host [n_seg]
+    int64_t* seg_start;   // host [n_seg + 1]
+    int32_t n_items;      // norm work items
+    int device;           // HIP device the tables live on, -1 if none
+    // device tables.  Kernels address segments through a compact index c that counts only the
+    // non-empty ones, so consecutive granules differ by at most one in c.
+    int32_t* d_granule_cseg;       // [D'/128]  compact segment index of each 128-element granule
+    int32_t* d_cseg_seg;           // [n_nonempty] segment l of compact index c
+    int64_t* d_cseg_valid_end;     // [n_nonempty] P_l + len_l: first padded index past the data
+    dq_norm_item* d_items;         // [n_items]
+    int32_t* d_seg_item_begin;     // [n_seg + 1] items of segment l are [begin[l], begin[l+1])
+};
+
+static inline bool dq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks shared by the device entry points; returns DQ_OK when `plan` can launch work on its GPU
+// and makes that GPU current.
+int dq_plan_check_device(const dq_plan* plan);
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies, key
+// bumped by the Weyl constants between rounds.  The three-input XOR is one v_bitop3_b32.
+__device__ __forceinline__ uint32_t dq_xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
+__device__ __forceinline__ void dq_philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = static_cast<uint64_t>(M0) * c0;
+        const uint64_t p1 = static_cast<uint64_t>(M1) * c2;
+        const uint32_t n0 = dq_xor3(static_cast<uint32_t>(p1 >> 32), c1, k0);
+        const uint32_t n2 = dq_xor3(static_cast<uint32_t>(p0 >> 32), c3, k1);
+        c1 = static_cast<uint32_t>(p1);
+        c3 = static_cast<uint32_t>(p0);
+        c0 = n0;
+        c2 = n2;
+        k0 += W0;
+        k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}

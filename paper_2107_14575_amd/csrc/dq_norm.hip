@@ -1,0 +1,95 @@
+// dq_norm: l2 norm per (worker, segment) -- the ||g|| of Eq. (5) with p = 2.
+//
+// Two passes, both deterministic.  Pass 1: one workgroup per (norm item, worker) sums the squares
+// of up to 4096 valid elements in binary64 (squares of binary32 values are exact there): per-lane
+// partial, wavefront shuffle tree, then the four wave sums through LDS in wave order.  Pass 2: one
+// wavefront per (segment, worker) adds that segment's item partials in a fixed order and takes
+// the square root.  HBM traffic: 4 bytes read per element, plus 8 bytes per 4096 elements.
+#include "dq_internal.h"
+
+namespace {
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+    return v; // lane 0 holds the sum
+}
+
+__global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ grads,
+                                                      int64_t worker_stride,
+                                                      const dq_norm_item* __restrict__ items,
+                                                      int32_t n_items, double* __restrict__ partial)
+{
+    __shared__ double wave_part[4];
+    const int item_id = blockIdx.x;
+    const int w = blockIdx.y;
+    const dq_norm_item item = items[item_id];
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride + item.start;
+    const int tid = threadIdx.x;
+
+    float4 v[DQ_NORM_CHUNK / 1024];
+#pragma unroll
+    for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
+        const int e = (k * 256 + tid) * 4;
+        // the padded allocation is a multiple of 128 elements, so a float4 that starts inside the
+        // item's valid range never leaves the worker's buffer
+        v[k] = e < item.count ? *reinterpret_cast<const float4*>(g + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
+        const int e = (k * 256 + tid) * 4;
+        const double x0 = e + 0 < item.count ? static_cast<double>(v[k].x) : 0.0;
+        const double x1 = e + 1 < item.count ? static_cast<double>(v[k].y) : 0.0;
+        const double x2 = e + 2 < item.count ? static_cast<double>(v[k].z) : 0.0;
+        const double x3 = e + 3 < item.count ? static_cast<double>(v[k].w) : 0.0;
+        acc = __builtin_fma(x0, x0, acc);
+        acc = __builtin_fma(x1, x1, acc);
+        acc = __builtin_fma(x2, x2, acc);
+        acc = __builtin_fma(x3, x3, acc);
+    }
+    acc = wave_sum(acc);
+    if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0)
+        partial[static_cast<int64_t>(w) * n_items + item_id] =
+            ((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3];
+}
+
+__global__ __launch_bounds__(64) void k_norm_finish(const double* __restrict__ partial, int32_t n_items,
+                                                    const int32_t* __restrict__ seg_item_begin,
+                                                    int32_t n_seg, float* __restrict__ norms)
+{
+    const int seg = blockIdx.x;
+    const int w = blockIdx.y;
+    const int begin = seg_item_begin[seg], end = seg_item_begin[seg + 1];
+    const double* p = partial + static_cast<int64_t>(w) * n_items;
+    double acc = 0.0;
+    for (int i = begin + static_cast<int>(threadIdx.x); i < end; i += 64) acc += p[i];
+    acc = wave_sum(acc);
+    if (threadIdx.x == 0) norms[static_cast<int64_t>(w) * n_seg + seg] = static_cast<float>(sqrt(acc));
+}
+
+} // namespace
+
+extern "C" int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                       int M, float* norms_dev, void* workspace_dev, void* hip_stream)
+{
+    if (!plan || !grads_dev || !norms_dev || !workspace_dev) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
+    if (worker_stride_elems < plan->padded_elems || (worker_stride_elems & 3)) return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(grads_dev) || !dq_aligned16(workspace_dev) || (reinterpret_cast<uintptr_t>(norms_dev) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    double* partial = static_cast<double*>(workspace_dev);
+    if (plan->n_items > 0) {
+        hipLaunchKernelGGL(k_norm_partial, dim3(plan->n_items, M), dim3(256), 0, stream, grads_dev,
+                           worker_stride_elems, plan->d_items, plan->n_items, partial);
+    }
+    hipLaunchKernelGGL(k_norm_finish, dim3(plan->n_seg, M), dim3(64), 0, stream, partial, plan->n_items,
+                       plan->d_seg_item_begin, plan->n_seg, norms_dev);
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}

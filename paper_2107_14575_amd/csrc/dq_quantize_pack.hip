@@ -1,0 +1,201 @@
+// dq_quantize_pack: the EWU quantizer of Eq. (5)-(6) fused with the packing of the message whose
+// size Eq. (7) counts.
+//
+// Work split.  One workgroup (256 lanes) owns TILES consecutive tiles of 2048 padded elements of
+// one worker; a lane owns 8 consecutive elements of each tile (two 16-byte loads, two Philox
+// blocks), so its output is exactly one sign byte and B level bytes.  Those bytes are staged in
+// LDS and leave the workgroup as 16-byte stores that cover each plane's bytes contiguously.
+//
+// Per-segment state.  The scale s/N and the end of the valid range of every segment the
+// workgroup touches (at most one per 128-element granule) are put in LDS once per workgroup, so
+// the one binary32 division per (worker, segment) is never on a lane's critical path.
+//
+// HBM traffic per element: 4 bytes read, (B+1)/8 bytes written, plus 4 bytes per 128 elements for
+// the granule table.
+#include "dq_internal.h"
+
+namespace {
+
+constexpr int QP_THREADS = 256;
+constexpr int QP_PER_LANE = 8;
+constexpr int QP_TILE = QP_THREADS * QP_PER_LANE; // 2048 elements
+
+template <int B> struct level_word { using type = uint64_t; };
+template <> struct level_word<1> { using type = uint32_t; };
+template <> struct level_word<2> { using type = uint32_t; };
+template <> struct level_word<3> { using type = uint32_t; };
+template <> struct level_word<4> { using type = uint32_t; };
+
+// Writes the low B bytes of v at dst (LDS, byte offset a multiple of B) with naturally aligned
+// stores only.
+template <int B, typename W>
+__device__ __forceinline__ void stage_bytes(uint8_t* dst, W v)
+{
+    if constexpr (B == 8) {
+        *reinterpret_cast<uint64_t*>(dst) = v;
+    } else if constexpr (B == 4) {
+        *reinterpret_cast<uint32_t*>(dst) = static_cast<uint32_t>(v);
+    } else if constexpr (B % 2 == 0) {
+#pragma unroll
+        for (int k = 0; k < B / 2; ++k) reinterpret_cast<uint16_t*>(dst)[k] = static_cast<uint16_t>(v >> (16 * k));
+    } else {
+#pragma unroll
+        for (int k = 0; k < B; ++k) dst[k] = static_cast<uint8_t>(v >> (8 * k));
+    }
+}
+
+template <int B, int TILES>
+__global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
+    const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
+    const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems,
+    uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
+    int64_t packed_stride)
+{
+    using lw_t = typename level_word<B>::type;
+    constexpr int CHUNK = QP_TILE * TILES;
+    constexpr int MAX_LOCAL_SEG = CHUNK / DQ_GRANULE;
+    constexpr float S = static_cast<float>((1 << B) - 1);
+
+    __shared__ float lds_scale[MAX_LOCAL_SEG];
+    __shared__ int64_t lds_valid_end[MAX_LOCAL_SEG];
+    __shared__ __align__(16) uint8_t lds_sign[TILES * QP_THREADS];
+    __shared__ __align__(16) uint8_t lds_level[TILES * QP_THREADS * B];
+
+    const int tid = threadIdx.x;
+    const int w = blockIdx.y;
+    const int64_t chunk0 = static_cast<int64_t>(blockIdx.x) * CHUNK;
+    const int64_t chunk_end = chunk0 + CHUNK < padded_elems ? chunk0 + CHUNK : padded_elems;
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride;
+
+    // this lane's inputs first, so the loads are in flight while the segment table is built
+    float4 x[TILES][2];
+    int32_t seg[TILES];
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        const int64_t P = chunk0 + it * QP_TILE + tid * QP_PER_LANE;
+        if (P < chunk_end) {
+            x[it][0] = *reinterpret_cast<const float4*>(g + P);
+            x[it][1] = *reinterpret_cast<const float4*>(g + P + 4);
+            seg[it] = granule_cseg[P >> 7];
+        } else {
+            x[it][0] = x[it][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            seg[it] = 0;
+        }
+    }
+
+    // compact segment indices grow by at most one per granule, so the chunk's segments fit the table
+    const int32_t seg_first = granule_cseg[chunk0 >> 7];
+    const int32_t seg_last = granule_cseg[(chunk_end - 1) >> 7];
+    if (tid <= seg_last - seg_first) {
+        const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]];
+        lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f; // zero, tiny or NaN norm: every level 0
+        lds_valid_end[tid] = cseg_valid_end[seg_first + tid];
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        const int64_t P = chunk0 + it * QP_TILE + tid * QP_PER_LANE;
+        if (P < chunk_end) {
+            const int local = seg[it] - seg_first;
+            const float scale = lds_scale[local];
+            const int64_t n_valid = lds_valid_end[local] - P; // elements of this lane inside the tensor
+
+            const uint64_t quad = static_cast<uint64_t>(P) >> 2; // even: quad + 1 cannot carry
+            uint32_t r[8];
+            {
+                uint32_t r0[4], r1[4];
+                dq_philox4x32_10(static_cast<uint32_t>(quad), static_cast<uint32_t>(quad >> 32),
+                                 worker_base + w, step, key0, key1, r0);
+                dq_philox4x32_10(static_cast<uint32_t>(quad) + 1u, static_cast<uint32_t>(quad >> 32),
+                                 worker_base + w, step, key0, key1, r1);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) { r[k] = r0[k]; r[4 + k] = r1[k]; }
+            }
+            const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
+                                 x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
+            uint32_t sign = 0;
+            lw_t level = 0;
+#pragma unroll
+            for (int k = QP_PER_LANE - 1; k >= 0; --k) {
+                // (sign << 1) | sign bit of v[k]; element 0 ends up in bit 0
+                sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31);
+                const float a = fminf(fabsf(v[k]) * scale, S);       // s|g|/N, one rounding, clamped
+                const float p = __builtin_amdgcn_fractf(a);           // a - floor(a), exact
+                const float u = static_cast<float>(r[k] >> 8) * 0x1p-24f; // exact, in [0,1)
+                const uint32_t lv = static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
+                level = static_cast<lw_t>(level << B) | lv;
+            }
+            if (n_valid < QP_PER_LANE) { // the tensor ends inside this lane's eight elements
+                const int nv = n_valid > 0 ? static_cast<int>(n_valid) : 0;
+                sign &= (1u << nv) - 1u;
+                level &= static_cast<lw_t>((static_cast<uint64_t>(1) << (nv * B)) - 1u);
+            }
+            lds_sign[it * QP_THREADS + tid] = static_cast<uint8_t>(sign);
+            stage_bytes<B>(&lds_level[(it * QP_THREADS + tid) * B], level);
+        }
+    }
+    __syncthreads();
+
+    // 16-byte stores; every plane of a chunk is a whole number of 16-byte pieces because the
+    // chunk holds a multiple of 128 elements
+    uint8_t* msg = packed + static_cast<int64_t>(w) * packed_stride;
+    const int n_elems = static_cast<int>(chunk_end - chunk0);
+    {
+        uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
+        const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
+        for (int i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+    }
+    {
+        uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + (chunk0 >> 3) * B);
+        const uint4* src = reinterpret_cast<const uint4*>(lds_level);
+        for (int i = tid; i < n_elems / 128 * B; i += QP_THREADS) dst[i] = src[i];
+    }
+}
+
+template <int B>
+int launch(const dq_plan* plan, const float* grads, int64_t worker_stride, int M, const float* norms,
+           uint64_t seed, uint32_t step, uint32_t worker_base, uint8_t* packed, int64_t packed_stride,
+           hipStream_t stream)
+{
+    constexpr int TILES = 2;
+    constexpr int CHUNK = QP_TILE * TILES;
+    const int64_t n_chunks = (plan->padded_elems + CHUNK - 1) / CHUNK;
+    if (n_chunks > INT32_MAX) return DQ_ERR_INVALID_ARG;
+    hipLaunchKernelGGL((k_quantize_pack<B, TILES>), dim3(static_cast<unsigned>(n_chunks), M), dim3(QP_THREADS), 0,
+                       stream, grads, worker_stride, norms, plan->n_seg, plan->d_granule_cseg,
+                       plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, static_cast<uint32_t>(seed),
+                       static_cast<uint32_t>(seed >> 32), step, worker_base, packed, packed_stride);
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
+} // namespace
+
+extern "C" int dq_quantize_pack(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                                int M, const float* norms_dev, int b, uint64_t seed, uint32_t step,
+                                uint32_t worker_base, uint8_t* packed_dev,
+                                int64_t packed_worker_stride_bytes, void* hip_stream)
+{
+    if (!plan || !grads_dev || !norms_dev || !packed_dev) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS || b < 1 || b > 8) return DQ_ERR_INVALID_ARG;
+    if (worker_stride_elems < plan->padded_elems || (worker_stride_elems & 3)) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < dq_packed_bytes(plan, b) || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(grads_dev) || !dq_aligned16(packed_dev) || (reinterpret_cast<uintptr_t>(norms_dev) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    if (plan->padded_elems == 0) return DQ_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    switch (b) {
+    case 1: return launch<1>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
+    case 2: return launch<2>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
+    case 3: return launch<3>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
+    case 4: return launch<4>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
+    case 5: return launch<5>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
+    case 6: return launch<6>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
+    case 7: return launch<7>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
+    default: return launch<8>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
+    }
+}

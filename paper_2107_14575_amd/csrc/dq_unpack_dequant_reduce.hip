@@ -1,0 +1,171 @@
+// dq_unpack_dequant_reduce: the server average of Algorithm 1 / Eq. (2),
+//     out_P = (1/M) sum_i sgn_{i,P} * level_{i,P} * (N_{i,l} / s),
+// with every worker's message read exactly once.
+//
+// Work split.  One workgroup (256 lanes) owns 8192 consecutive padded elements; a lane owns 32 of
+// them, so per worker it reads one sign dword and B level dwords -- every load is dword aligned
+// for every B -- and keeps 32 binary32 accumulators.  Per (worker, element): field extract,
+// convert, put the sign bit on the worker's unit (shift, v_and_or), one FMA.
+//
+// The 32 results of a lane are consecutive in memory, so storing them directly would be 16-byte
+// pieces 128 bytes apart; they go through LDS (XOR-swizzled 16-byte slots, conflict free both
+// ways) and leave as fully coalesced 16-byte stores.
+//
+// The units N/s of the segments a workgroup touches are computed once per workgroup into LDS.
+//
+// HBM traffic per output element: M(B+1)/8 bytes read, 4 bytes written.
+#include "dq_internal.h"
+
+namespace {
+
+constexpr int UR_THREADS = 256;
+constexpr int UR_PER_LANE = 32;
+constexpr int UR_TILE = UR_THREADS * UR_PER_LANE; // 8192 elements
+constexpr int UR_MAX_LOCAL_SEG = UR_TILE / DQ_GRANULE;
+
+// level k (0..31) of a lane's B dwords; fields may straddle two dwords when B is not a power of two
+template <int B>
+__device__ __forceinline__ uint32_t level_field(const uint32_t (&wd)[B], int k)
+{
+    const int bit = k * B;
+    const int word = bit >> 5, off = bit & 31;
+    if (off + B <= 32) return __builtin_amdgcn_ubfe(wd[word], off, B);
+    // straddles: funnel-shift the pair down, then mask
+    const uint32_t lo = __builtin_amdgcn_alignbit(wd[word + 1 < B ? word + 1 : word], wd[word], off);
+    return lo & ((1u << B) - 1u);
+}
+
+template <int B>
+__global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
+    const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
+    int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, float inv_M, float* __restrict__ out)
+{
+    constexpr float S = static_cast<float>((1 << B) - 1);
+    extern __shared__ __align__(16) uint8_t lds_raw[];
+    float4* lds_out = reinterpret_cast<float4*>(lds_raw);                       // [UR_TILE / 4]
+    float* lds_unit = reinterpret_cast<float*>(lds_raw + UR_TILE * sizeof(float)); // [local seg][M]
+
+    const int tid = threadIdx.x;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * UR_TILE;
+    const int64_t tile_end = tile0 + UR_TILE < padded_elems ? tile0 + UR_TILE : padded_elems;
+    const int64_t P0 = tile0 + tid * UR_PER_LANE;
+    const bool active = P0 < tile_end;
+
+    const int32_t seg_first = granule_cseg[tile0 >> 7];
+    const int32_t seg_last = granule_cseg[(tile_end - 1) >> 7];
+    const int n_local = seg_last - seg_first + 1; // <= UR_MAX_LOCAL_SEG: compact indices grow by <= 1 per granule
+    for (int i = tid; i < n_local * M; i += UR_THREADS) {
+        const int local = i / M, w = i - local * M;
+        const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + local]];
+        lds_unit[i] = N >= DQ_MIN_NORM ? N / S : 0.0f;
+    }
+    int local = 0;
+    int64_t n_valid = 0;
+    if (active) {
+        const int32_t c = granule_cseg[P0 >> 7];
+        local = c - seg_first;
+        n_valid = cseg_valid_end[c] - P0;
+    }
+    __syncthreads();
+
+    float acc[UR_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = 0.0f;
+
+    if (active) {
+        const uint8_t* sign_ptr = packed + (P0 >> 3);
+        const uint8_t* level_ptr = packed + (padded_elems >> 3) + (P0 >> 3) * B;
+        const float* unit_ptr = lds_unit + local * M;
+#pragma unroll 4
+        for (int w = 0; w < M; ++w) {
+            const uint32_t sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
+            const uint32_t* lp = reinterpret_cast<const uint32_t*>(level_ptr + static_cast<int64_t>(w) * packed_stride);
+            uint32_t wd[B];
+            if constexpr (B % 4 == 0) {
+#pragma unroll
+                for (int q = 0; q < B / 4; ++q) {
+                    const uint4 t = reinterpret_cast<const uint4*>(lp)[q];
+                    wd[4 * q] = t.x; wd[4 * q + 1] = t.y; wd[4 * q + 2] = t.z; wd[4 * q + 3] = t.w;
+                }
+            } else if constexpr (B % 2 == 0) {
+#pragma unroll
+                for (int q = 0; q < B / 2; ++q) {
+                    const uint2 t = reinterpret_cast<const uint2*>(lp)[q];
+                    wd[2 * q] = t.x; wd[2 * q + 1] = t.y;
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < B; ++q) wd[q] = lp[q];
+            }
+            const float unit = unit_ptr[w];
+#pragma unroll
+            for (int k = 0; k < UR_PER_LANE; ++k) {
+                const float lv = static_cast<float>(level_field<B>(wd, k));
+                // sign bit of element k on top of the unit, whose own sign bit is always clear
+                const float su = __uint_as_float(__float_as_uint(unit) | ((sg << (31 - k)) & 0x80000000u));
+                acc[k] = __builtin_fmaf(lv, su, acc[k]);
+            }
+        }
+        const int nv = n_valid >= UR_PER_LANE ? UR_PER_LANE : (n_valid > 0 ? static_cast<int>(n_valid) : 0);
+#pragma unroll
+        for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = k < nv ? acc[k] * inv_M : 0.0f;
+    }
+
+    // lane t of wave v holds elements [v*2048 + 32t, +32): slot (t, q) -> t*8 + (q ^ (t & 7))
+    const int wave = tid >> 6, lane = tid & 63;
+    float4* wave_out = lds_out + wave * 512;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        wave_out[lane * 8 + (q ^ (lane & 7))] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        // store j of the wave covers its elements [256j, 256j + 256); this lane takes 4 of them
+        const int src_lane = 8 * j + (lane >> 3), q = lane & 7;
+        const float4 v = wave_out[src_lane * 8 + (q ^ (src_lane & 7))];
+        const int64_t P = tile0 + wave * 2048 + 256 * j + 4 * lane;
+        if (P < tile_end) *reinterpret_cast<float4*>(out + P) = v;
+    }
+}
+
+template <int B>
+int launch(const dq_plan* plan, const uint8_t* packed, int64_t packed_stride, int M, const float* norms,
+           float* out, hipStream_t stream)
+{
+    const int64_t n_tiles = (plan->padded_elems + UR_TILE - 1) / UR_TILE;
+    if (n_tiles > INT32_MAX) return DQ_ERR_INVALID_ARG;
+    const size_t lds_bytes = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(float);
+    hipLaunchKernelGGL((k_unpack_dequant_reduce<B>), dim3(static_cast<unsigned>(n_tiles)), dim3(UR_THREADS), lds_bytes,
+                       stream, packed, packed_stride, M, norms, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg,
+                       plan->d_cseg_valid_end, plan->padded_elems, 1.0f / static_cast<float>(M), out);
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
+} // namespace
+
+extern "C" int dq_unpack_dequant_reduce(const dq_plan_t* plan, const uint8_t* packed_dev,
+                                        int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
+                                        int b, float* out_dev, void* hip_stream)
+{
+    if (!plan || !packed_dev || !norms_dev || !out_dev) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS || b < 1 || b > 8) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < dq_packed_bytes(plan, b) || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(packed_dev) || !dq_aligned16(out_dev) || (reinterpret_cast<uintptr_t>(norms_dev) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    if (plan->padded_elems == 0) return DQ_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    switch (b) {
+    case 1: return launch<1>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
+    case 2: return launch<2>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
+    case 3: return launch<3>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
+    case 4: return launch<4>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
+    case 5: return launch<5>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
+    case 6: return launch<6>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
+    case 7: return launch<7>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
+    default: return launch<8>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
+    }
+}

@@ -1,0 +1,272 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Level codes, bitstreams and b_t are compared bit for bit; norms to 1 ulp of binary32;
+the dequantized average within 1e-6 relative (spec tolerance, restated in `_check_average`)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2107_14575_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SEED = wl.QUANT_SEED
+
+
+@pytest.fixture(scope="module")
+def dq():
+    import paper_2107_14575_amd as dq
+    dq.load_library()  # raises if the HIP library is not built: no fallback
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return dq
+
+
+def _valid_mask(seg_len):
+    starts, dp = wl.seg_starts(seg_len)
+    valid = np.zeros(dp, dtype=bool)
+    for st, n in zip(starts, seg_len):
+        valid[st:st + n] = True
+    return valid
+
+
+def gpu_norm(dq, plan, grads_dev):
+    M = grads_dev.shape[0]
+    norms = torch.empty((M, plan.n_seg), dtype=torch.float32, device="cuda")
+    ws = torch.empty(plan.workspace_bytes(M), dtype=torch.uint8, device="cuda")
+    dq.norm(plan, grads_dev, norms, ws)
+    torch.cuda.synchronize()
+    return norms
+
+
+def gpu_quantize_pack(dq, plan, grads_dev, norms_dev, b, step, worker_base=0, slack=0, fill=0xA5):
+    M = grads_dev.shape[0]
+    nbytes = plan.packed_bytes(b)
+    packed = torch.full((M, nbytes + slack), fill, dtype=torch.uint8, device="cuda")
+    dq.quantize_pack(plan, grads_dev, norms_dev, b, SEED, step, packed, worker_base=worker_base)
+    torch.cuda.synchronize()
+    return packed
+
+
+def gpu_reduce(dq, plan, packed_dev, norms_dev, b):
+    out = torch.full((plan.padded_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    dq.unpack_dequant_reduce(plan, packed_dev, norms_dev, b, out)
+    torch.cuda.synchronize()
+    return out
+
+
+def _check_average(got, want, sign, level, norms, seg_len, b):
+    """|gpu - oracle| <= 1e-6 * max|oracle| overall, and per element <= 1e-6 * (1/M) sum_i |v_i|
+    (plus one binary32 denormal); pads are exactly +0."""
+    M = sign.shape[0]
+    starts, dp = wl.seg_starts(seg_len)
+    s = float((1 << b) - 1)
+    mag = np.zeros(dp, dtype=np.float64)
+    for l, (st, n) in enumerate(zip(starts, seg_len)):
+        unit = np.where(norms[:, l] >= np.float32(2.0 ** -100), norms[:, l].astype(np.float64) / s, 0.0)
+        mag[st:st + n] = (level[:, st:st + n].astype(np.float64) * unit[:, None]).sum(axis=0) / M
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    assert err.max() <= 1e-6 * max(np.abs(want).max(), 1e-300)
+    assert np.all(err <= 1e-6 * mag + 1.5e-45)
+    valid = _valid_mask(seg_len)
+    assert np.array_equal(got[~valid].view(np.uint32), np.zeros((~valid).sum(), dtype=np.uint32))
+
+
+def _one_step(dq, oracle, seg_len, grads, b, step, worker_base=0, check_norm=True):
+    """norm -> quantize+pack -> reduce on the GPU and in the oracle; the oracle is fed the GPU's
+    norms for the later stages (the norm is an input of the quantizer, and may differ in the
+    last place between two correct implementations)."""
+    plan = dq.Plan(seg_len)
+    assert plan.has_device
+    g_host = np.ascontiguousarray(grads.numpy())
+    g_dev = grads.cuda()
+    norms_dev = gpu_norm(dq, plan, g_dev)
+    norms = norms_dev.cpu().numpy()
+    if check_norm:
+        want = oracle.norm(seg_len, g_host)
+        assert np.all(np.abs(norms.astype(np.float64) - want.astype(np.float64)) <= np.spacing(want))
+    packed_dev = gpu_quantize_pack(dq, plan, g_dev, norms_dev, b, step, worker_base, slack=48)
+    packed = packed_dev.cpu().numpy()
+    nbytes = plan.packed_bytes(b)
+    want_packed = oracle.quantize_pack(seg_len, g_host, norms, b, SEED, step, worker_base)
+    assert np.array_equal(packed[:, :nbytes], want_packed)
+    assert np.all(packed[:, nbytes:] == 0xA5)             # nothing written past the message
+    out = gpu_reduce(dq, plan, packed_dev, norms_dev, b).cpu().numpy()
+    want_out = oracle.unpack_dequant_reduce(seg_len, want_packed, norms, b)
+    sign, level = oracle.quantize(seg_len, g_host, norms, b, SEED, step, worker_base)
+    _check_average(out, want_out, sign, level, norms, seg_len, b)
+    plan.close()
+    return norms
+
+
+@pytest.mark.parametrize("b", range(1, 9))
+def test_ragged_layout_every_width(dq, oracle, b):
+    seg_len, grads = wl.ragged_mix(M=3)
+    _one_step(dq, oracle, seg_len, grads, b, step=b, worker_base=5)
+
+
+def test_config1_flat_gaussian_b4(dq, oracle):
+    seg_len, grads = wl.flat_gaussian(D=1 << 20, M=4)
+    _one_step(dq, oracle, seg_len, grads, 4, step=0)
+
+
+@pytest.mark.parametrize("D", [1, 127, 128, 2048, 4096 + 128, 8192, 8192 * 3 + 640])
+def test_tile_boundaries(dq, oracle, D):
+    """sizes around the kernels' tiles (2048 / 4096 / 8192 elements) with a ragged tail"""
+    seg_len, grads = wl.flat_gaussian(D=D, M=2, config=11)
+    for b in (3, 8):
+        _one_step(dq, oracle, seg_len, grads, b, step=1)
+
+
+@pytest.mark.parametrize("M", [1, 2, 5, 16, 64])
+def test_worker_counts(dq, oracle, M):
+    seg_len, grads = wl.flat_gaussian(D=5000, M=M, config=12)
+    _one_step(dq, oracle, seg_len, grads, 5, step=2)
+
+
+def test_many_tiny_tensors(dq, oracle):
+    """more segments than granules per tile, empty tensors in between"""
+    rng = np.random.default_rng(3)
+    seg_len = [int(x) for x in rng.choice([0, 1, 2, 64, 128, 129, 300], size=400)]
+    starts, dp = wl.seg_starts(seg_len)
+    g = torch.full((2, dp), float("nan"), dtype=torch.float32)
+    gen = torch.Generator().manual_seed(33)
+    for st, n in zip(starts, seg_len):
+        g[:, st:st + n] = torch.randn((2, n), generator=gen) * 1e-2
+    for b in (1, 4, 7):
+        _one_step(dq, oracle, seg_len, g, b, step=3)
+
+
+def test_zero_and_degenerate_norms(dq, oracle):
+    """zero vector -> all-zero message and exactly +0 output; tiny / NaN norms take the same path;
+    a norm smaller than an element clamps to s"""
+    seg_len = [300, 200, 500, 100]
+    starts, dp = wl.seg_starts(seg_len)
+    plan = dq.Plan(seg_len)
+    g = torch.zeros((2, dp), dtype=torch.float32)
+    gen = torch.Generator().manual_seed(5)
+    g[:, starts[1]:starts[1] + 200] = torch.randn((2, 200), generator=gen)
+    g[:, starts[2]:starts[2] + 500] = torch.randn((2, 500), generator=gen)
+    g[:, starts[3]:starts[3] + 100] = torch.randn((2, 100), generator=gen) * 1e-38
+    g_dev = g.cuda()
+    norms_dev = gpu_norm(dq, plan, g_dev)
+    norms = norms_dev.cpu().numpy()
+    assert np.all(norms[:, 0] == 0)
+    norms[:, 1] = np.nan          # unusable norm given by the caller
+    norms[:, 2] *= 0.25           # too small for the data: levels clamp at s
+    norms_dev = torch.from_numpy(norms).cuda()
+    for b in (2, 6):
+        packed_dev = gpu_quantize_pack(dq, plan, g_dev, norms_dev, b, step=0)
+        want = oracle.quantize_pack(seg_len, g.numpy(), norms, b, SEED, 0)
+        assert np.array_equal(packed_dev.cpu().numpy(), want)
+        sign, level = oracle.unpack(want[0], dp, b)
+        assert not level[starts[0]:starts[0] + 300].any() and not level[starts[1]:starts[1] + 200].any()
+        assert level[starts[2]:starts[2] + 500].max() == (1 << b) - 1
+        out = gpu_reduce(dq, plan, packed_dev, norms_dev, b).cpu().numpy()
+        want_out = oracle.unpack_dequant_reduce(seg_len, want, norms, b)
+        assert np.array_equal(out[:starts[2]].view(np.uint32), np.zeros(starts[2], dtype=np.uint32))
+        np.testing.assert_allclose(out, want_out, rtol=1e-6, atol=1e-45)
+    plan.close()
+
+
+def test_empty_plan(dq):
+    plan = dq.Plan([0, 0])
+    assert plan.padded_elems == 0 and plan.has_device
+    g = torch.zeros((2, 4), dtype=torch.float32, device="cuda")
+    norms = torch.full((2, 2), 7.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(plan.workspace_bytes(2), dtype=torch.uint8, device="cuda")
+    dq.norm(plan, g, norms, ws)
+    packed = torch.zeros((2, 16), dtype=torch.uint8, device="cuda")
+    dq.quantize_pack(plan, g, norms, 4, SEED, 0, packed)
+    out = torch.zeros(4, dtype=torch.float32, device="cuda")
+    dq.unpack_dequant_reduce(plan, packed, norms, 4, out)
+    torch.cuda.synchronize()
+    assert np.all(norms.cpu().numpy() == 0)
+    plan.close()
+
+
+def test_grid_values_and_denormal_products(dq, oracle):
+    """exact grid values reproduce for every seed (p_r = 0), and elements whose scaled magnitude is
+    a binary32 denormal are rounded exactly as the oracle does (no flush to zero)"""
+    b, e = 4, -9
+    s = 15
+    rng = np.random.default_rng(2)
+    d = 4096 + 256
+    lev = rng.integers(0, s + 1, size=d)
+    sgn = rng.choice([-1.0, 1.0], size=d)
+    g = torch.from_numpy((lev * sgn * 2.0 ** e).astype(np.float32)).repeat(2, 1).contiguous()
+    g[1, :100] = torch.from_numpy((rng.uniform(1, 8, size=100) * 2.0 ** -140).astype(np.float32))
+    plan = dq.Plan([d])
+    norms = np.full((2, 1), s * 2.0 ** e, dtype=np.float32)
+    norms_dev = torch.from_numpy(norms).cuda()
+    g_dev = g.cuda()
+    for step in (0, 1, 2):
+        packed = gpu_quantize_pack(dq, plan, g_dev, norms_dev, b, step).cpu().numpy()
+        want = oracle.quantize_pack([d], g.numpy(), norms, b, SEED, step)
+        assert np.array_equal(packed, want)
+        _, level = oracle.unpack(packed[0], d, b)
+        assert np.array_equal(level, lev.astype(np.uint8))
+    out = gpu_reduce(dq, plan, torch.from_numpy(want[:1].copy()).cuda(), norms_dev[:1], b).cpu().numpy()
+    assert np.array_equal(out[lev > 0], g.numpy()[0][lev > 0])
+    plan.close()
+
+
+def test_non_finite_inputs_stay_in_bounds(dq):
+    """NaN / Inf gradients give unspecified codes but never write outside the message"""
+    d = 3000
+    plan = dq.Plan([d])
+    g = torch.randn((1, plan.padded_elems))
+    g[0, ::7] = float("nan")
+    g[0, 1::11] = float("inf")
+    g[0, 2::13] = -float("inf")
+    norms = torch.ones((1, 1), dtype=torch.float32, device="cuda")
+    packed = gpu_quantize_pack(dq, plan, g.cuda(), norms, 8, 0, slack=64).cpu().numpy()
+    assert np.all(packed[:, plan.packed_bytes(8):] == 0xA5)
+    out = gpu_reduce(dq, plan, torch.from_numpy(packed[:, :plan.packed_bytes(8)].copy()).cuda(), norms, 8)
+    assert out.shape[0] == plan.padded_elems
+    plan.close()
+
+
+def test_reduce_accepts_any_message(dq, oracle):
+    """the reduce pass on messages the oracle wrote from random codes (all levels, all signs),
+    every width, strided messages"""
+    rng = np.random.default_rng(8)
+    seg_len = [8192 + 130, 77]
+    starts, dp = wl.seg_starts(seg_len)
+    valid = _valid_mask(seg_len)
+    M = 7
+    plan = dq.Plan(seg_len)
+    norms = (10 ** rng.uniform(-3, 0, size=(M, 2))).astype(np.float32)
+    norms_dev = torch.from_numpy(norms).cuda()
+    for b in range(1, 9):
+        sign = (rng.integers(0, 2, size=(M, dp)) * valid).astype(np.uint8)
+        level = (rng.integers(0, 1 << b, size=(M, dp)) * valid).astype(np.uint8)
+        nbytes = plan.packed_bytes(b)
+        packed = np.zeros((M, nbytes + 32), dtype=np.uint8)
+        for i in range(M):
+            packed[i, :nbytes] = oracle.pack(sign[i], level[i], b)
+        out = gpu_reduce(dq, plan, torch.from_numpy(packed).cuda(), norms_dev, b).cpu().numpy()
+        want = oracle.dequant_reduce(seg_len, sign, level, norms, b)
+        _check_average(out, want, sign, level, norms, seg_len, b)
+    plan.close()
+
+
+def test_stream_argument_and_determinism(dq):
+    """work goes to the stream that is passed in; two runs give identical bytes"""
+    seg_len, grads = wl.ragged_mix(M=2)
+    plan = dq.Plan(seg_len)
+    g_dev = grads.cuda()
+    side = torch.cuda.Stream()
+    outs = []
+    for stream in (None, side):
+        norms = torch.empty((2, plan.n_seg), dtype=torch.float32, device="cuda")
+        ws = torch.empty(plan.workspace_bytes(2), dtype=torch.uint8, device="cuda")
+        packed = torch.zeros((2, plan.packed_bytes(3)), dtype=torch.uint8, device="cuda")
+        out = torch.empty(plan.padded_elems, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        dq.norm(plan, g_dev, norms, ws, stream=stream)
+        dq.quantize_pack(plan, g_dev, norms, 3, SEED, 9, packed, stream=stream)
+        dq.unpack_dequant_reduce(plan, packed, norms, 3, out, stream=stream)
+        (side if stream is not None else torch.cuda.current_stream()).synchronize()
+        outs.append((norms.cpu().numpy(), packed.cpu().numpy(), out.cpu().numpy()))
+    for a, c in zip(outs[0], outs[1]):
+        assert np.array_equal(a.view(np.uint8), c.view(np.uint8))
+    plan.close()

@@ -1,0 +1,130 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, its host logic
+(layout queries, the bit rule, argument validation) agrees with the oracle.  No kernel runs."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def dq():
+    import paper_2107_14575_amd as dq
+    if not os.path.exists(dq.library_path()):
+        from paper_2107_14575_amd import build
+        build.build_library()
+    dq.load_library()
+    return dq
+
+
+def test_library_exports_every_declared_symbol(dq):
+    header = open(os.path.join(ROOT, "include", "dq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dq_[a-z_0-9]+)\s*\(", header))
+    assert {"dq_norm", "dq_select_bits", "dq_quantize_pack", "dq_unpack_dequant_reduce"} <= declared
+    lib = dq.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    from paper_2107_14575_amd import binding
+    assert declared == set(binding.EXPORTS)
+
+
+def test_layout_queries_match_the_oracle(dq, oracle):
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        n_seg = int(rng.integers(1, 12))
+        seg = [int(x) for x in rng.choice([0, 1, 5, 127, 128, 129, 1000, 4096, 70001], size=n_seg)]
+        plan = dq.Plan(seg)
+        assert plan.n_seg == n_seg
+        assert plan.padded_elems == oracle.padded_elems(seg)
+        assert [plan.segment_start(l) for l in range(n_seg)] == list(oracle.seg_starts(seg))
+        for b in range(1, 9):
+            assert plan.packed_bytes(b) == oracle.packed_bytes(seg, b)
+        assert plan.packed_bytes(0) == -1 and plan.packed_bytes(9) == -1
+        assert plan.workspace_bytes(4) >= 16 and plan.workspace_bytes(0) == -1
+        assert plan.segment_start(n_seg) == -1
+        plan.close()
+
+
+def test_select_bits_bit_exact_against_the_oracle(dq, oracle):
+    rng = np.random.default_rng(1)
+    for _ in range(3000):
+        M, n_seg = int(rng.integers(1, 17)), int(rng.integers(1, 8))
+        norms = (10 ** rng.uniform(-6, 1, size=(M, n_seg))).astype(np.float32)
+        T = int(rng.integers(1, 1000))
+        t = int(rng.integers(0, T))
+        eps = float(10 ** rng.uniform(-8, 2))
+        alpha = float(rng.uniform(0.5, 1.0))
+        b_min = int(rng.integers(1, 9))
+        b_max = int(rng.integers(b_min, 9))
+        got = dq.select_bits(norms, t, T, eps, alpha, b_min, b_max)
+        want = oracle.select_bits(norms, t, T, eps, alpha, b_min, b_max)
+        assert got[0] == want[0]
+        assert abs(got[1] - want[1]) <= 1e-15 * want[1]
+
+
+def test_select_bits_rejects_bad_arguments(dq):
+    n = np.ones((2, 2), dtype=np.float32)
+    good = dict(t=0, T=10, eps_hat_q=1.0, alpha=0.9, b_min=1, b_max=8)
+    assert dq.select_bits(n, **good)[0] >= 1
+    for kw in (dict(t=-1), dict(t=10), dict(T=0), dict(eps_hat_q=0.0), dict(eps_hat_q=float("nan")),
+               dict(alpha=0.0), dict(alpha=1.5), dict(b_min=0), dict(b_max=9), dict(b_min=5, b_max=4)):
+        args = dict(good)
+        args.update(kw)
+        with pytest.raises(dq.DQError) as e:
+            dq.select_bits(n, **args)
+        assert e.value.status == -1
+
+
+def test_plan_create_rejects_bad_arguments(dq):
+    lib = dq.load_library()
+    h = C.c_void_p()
+    lens = (C.c_int64 * 2)(5, -1)
+    assert lib.dq_plan_create(lens, 2, C.byref(h)) == -1 and not h.value
+    assert lib.dq_plan_create(lens, 0, C.byref(h)) == -1
+    assert lib.dq_plan_create(None, 1, C.byref(h)) == -1
+    lib.dq_plan_destroy(None)  # harmless
+    assert lib.dq_status_string(0) == b"ok" and b"invalid" in lib.dq_status_string(-1)
+
+
+def test_device_entry_points_validate_before_touching_a_gpu(dq):
+    """Null pointers and bad sizes are rejected with DQ_ERR_INVALID_ARG whether or not a GPU is
+    present (nothing is launched)."""
+    lib = dq.load_library()
+    plan = dq.Plan([1000])
+    h = plan.handle
+    fake = 0x1000  # aligned, never dereferenced on these paths
+    assert lib.dq_norm(h, None, 1024, 1, fake, fake, None) == -1
+    assert lib.dq_norm(h, fake, 1000, 1, fake, fake, None) == -1            # stride < D'
+    assert lib.dq_norm(h, fake, 1024, 0, fake, fake, None) == -1            # M < 1
+    assert lib.dq_norm(h, fake + 4, 1024, 1, fake, fake, None) == -1        # misaligned
+    assert lib.dq_quantize_pack(h, fake, 1024, 1, fake, 0, 1, 0, 0, fake, 4096, None) == -1   # b = 0
+    assert lib.dq_quantize_pack(h, fake, 1024, 1, fake, 9, 1, 0, 0, fake, 4096, None) == -1   # b = 9
+    assert lib.dq_quantize_pack(h, fake, 1024, 1, fake, 4, 1, 0, 0, fake, 16, None) == -1     # short stride
+    assert lib.dq_quantize_pack(h, fake, 1024, 65, fake, 4, 1, 0, 0, fake, 4096, None) == -1  # M too large
+    assert lib.dq_unpack_dequant_reduce(h, fake, 4096, 1, fake, 4, None, None) == -1
+    assert lib.dq_unpack_dequant_reduce(h, fake, 4100, 1, fake, 4, fake, None) == -1          # stride % 16
+    if not plan.has_device:
+        assert lib.dq_norm(h, fake, 1024, 1, fake, fake, None) == -2
+        assert lib.dq_quantize_pack(h, fake, 1024, 1, fake, 4, 1, 0, 0, fake, 4096, None) == -2
+        assert lib.dq_unpack_dequant_reduce(h, fake, 4096, 1, fake, 4, fake, None) == -2
+    plan.close()
+
+
+def test_workload_shapes():
+    from paper_2107_14575_amd import workloads as wl
+    assert sum(wl.resnet18_cifar10_segments()) == 11_173_962
+    assert len(wl.transformer_classifier_segments()) == 102
+    seg, g = wl.ragged_mix(M=2)
+    starts, dp = wl.seg_starts(seg)
+    assert g.shape == (2, dp) and dp % 128 == 0
+    valid = np.zeros(dp, dtype=bool)
+    for st, n in zip(starts, seg):
+        valid[st:st + n] = True
+    gn = g.numpy()
+    assert np.isnan(gn[:, ~valid]).all() and np.isfinite(gn[:, valid]).all()
+    seg2, g2 = wl.ragged_mix(M=2)
+    assert np.array_equal(g2.numpy()[:, valid], gn[:, valid])

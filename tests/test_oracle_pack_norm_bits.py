@@ -240,3 +240,22 @@ def test_messages_round_trip_through_both_passes(oracle):
         a = oracle.dequant_reduce(seg, sign, level, norms, b)
         c = oracle.unpack_dequant_reduce(seg, packed, norms, b)
         assert np.array_equal(a, c)
+
+
+def test_range_forms_equal_slices_of_the_whole(oracle):
+    rng = np.random.default_rng(12)
+    seg = [300, 0, 5, 1000, 129]
+    dp = oracle.padded_elems(seg)
+    M, b = 3, 5
+    grads = (rng.standard_normal((M, dp)) * 1e-2).astype(np.float32)
+    norms = oracle.norm(seg, grads)
+    sign, level = oracle.quantize(seg, grads, norms, b, SEED, 4, worker_base=2)
+    out = oracle.dequant_reduce(seg, sign, level, norms, b)
+    for p0, p1 in ((0, 128), (256, 1024), (dp - 256, dp), (0, dp), (384, 384)):
+        sl = np.ascontiguousarray(grads[:, p0:p1]) if p1 > p0 else np.zeros((M, 1), dtype=np.float32)[:, :0].copy()
+        if p1 == p0:
+            continue
+        s2, l2 = oracle.quantize_range(seg, sl, norms, b, SEED, 4, p0, p1, worker_base=2)
+        assert np.array_equal(s2, sign[:, p0:p1]) and np.array_equal(l2, level[:, p0:p1])
+        o2 = oracle.dequant_reduce_range(seg, s2, l2, norms, b, p0, p1)
+        assert np.array_equal(o2, out[p0:p1])
