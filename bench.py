@@ -91,7 +91,7 @@ def main() -> None:
     ap.add_argument("--log2d", type=int, default=None)
     ap.add_argument("--fixed-bits", type=int, default=0, help="use this b every step instead of the rule")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-log2", type=int, default=24)
+    ap.add_argument("--cpu-sample-log2", type=int, default=26)
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build measures the one-GPU hot path only (M workers simulated in-device); "

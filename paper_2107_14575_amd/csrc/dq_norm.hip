@@ -3,7 +3,7 @@
 // Two passes, both deterministic.  Pass 1: one workgroup per (norm item, worker) sums the squares
 // of up to 4096 valid elements in binary64 (squares of binary32 values are exact there): per-lane
 // partial, wavefront shuffle tree, then the four wave sums through LDS in wave order.  Pass 2: one
-// wavefront per (segment, worker) adds that segment's item partials in a fixed order and takes
+// workgroup per (segment, worker) adds that segment's item partials in a fixed order and takes
 // the square root.  HBM traffic: 4 bytes read per element, plus 8 bytes per 4096 elements.
 #include "dq_internal.h"
 
@@ -57,18 +57,38 @@ __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ 
             ((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3];
 }
 
-__global__ __launch_bounds__(64) void k_norm_finish(const double* __restrict__ partial, int32_t n_items,
-                                                    const int32_t* __restrict__ seg_item_begin,
-                                                    int32_t n_seg, float* __restrict__ norms)
+constexpr int FINISH_THREADS = 1024;
+
+__global__ __launch_bounds__(FINISH_THREADS) void k_norm_finish(const double* __restrict__ partial, int32_t n_items,
+                                                                const int32_t* __restrict__ seg_item_begin,
+                                                                int32_t n_seg, float* __restrict__ norms)
 {
+    __shared__ double wave_part[FINISH_THREADS / 64];
     const int seg = blockIdx.x;
     const int w = blockIdx.y;
+    const int tid = threadIdx.x;
     const int begin = seg_item_begin[seg], end = seg_item_begin[seg + 1];
     const double* p = partial + static_cast<int64_t>(w) * n_items;
+    // lane-strided, in a fixed order; eight independent loads in flight per lane
     double acc = 0.0;
-    for (int i = begin + static_cast<int>(threadIdx.x); i < end; i += 64) acc += p[i];
+    int i = begin + tid;
+    for (; i + 7 * FINISH_THREADS < end; i += 8 * FINISH_THREADS) {
+        double v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = p[i + k * FINISH_THREADS];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc += v[k];
+    }
+    for (; i < end; i += FINISH_THREADS) acc += p[i];
     acc = wave_sum(acc);
-    if (threadIdx.x == 0) norms[static_cast<int64_t>(w) * n_seg + seg] = static_cast<float>(sqrt(acc));
+    if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        double total = 0.0;
+#pragma unroll
+        for (int k = 0; k < FINISH_THREADS / 64; ++k) total += wave_part[k];
+        norms[static_cast<int64_t>(w) * n_seg + seg] = static_cast<float>(sqrt(total));
+    }
 }
 
 } // namespace
@@ -89,7 +109,7 @@ extern "C" int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t wo
         hipLaunchKernelGGL(k_norm_partial, dim3(plan->n_items, M), dim3(256), 0, stream, grads_dev,
                            worker_stride_elems, plan->d_items, plan->n_items, partial);
     }
-    hipLaunchKernelGGL(k_norm_finish, dim3(plan->n_seg, M), dim3(64), 0, stream, partial, plan->n_items,
+    hipLaunchKernelGGL(k_norm_finish, dim3(plan->n_seg, M), dim3(FINISH_THREADS), 0, stream, partial, plan->n_items,
                        plan->d_seg_item_begin, plan->n_seg, norms_dev);
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
 }

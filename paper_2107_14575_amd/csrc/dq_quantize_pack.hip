@@ -16,20 +16,18 @@
 
 namespace {
 
+#ifndef DQ_QP_TILES
+#define DQ_QP_TILES 2 // tiles of 2048 elements per workgroup
+#endif
+
 constexpr int QP_THREADS = 256;
 constexpr int QP_PER_LANE = 8;
 constexpr int QP_TILE = QP_THREADS * QP_PER_LANE; // 2048 elements
 
-template <int B> struct level_word { using type = uint64_t; };
-template <> struct level_word<1> { using type = uint32_t; };
-template <> struct level_word<2> { using type = uint32_t; };
-template <> struct level_word<3> { using type = uint32_t; };
-template <> struct level_word<4> { using type = uint32_t; };
-
 // Writes the low B bytes of v at dst (LDS, byte offset a multiple of B) with naturally aligned
 // stores only.
-template <int B, typename W>
-__device__ __forceinline__ void stage_bytes(uint8_t* dst, W v)
+template <int B>
+__device__ __forceinline__ void stage_bytes(uint8_t* dst, uint64_t v)
 {
     if constexpr (B == 8) {
         *reinterpret_cast<uint64_t*>(dst) = v;
@@ -44,6 +42,25 @@ __device__ __forceinline__ void stage_bytes(uint8_t* dst, W v)
     }
 }
 
+// Four elements (one Philox block): sign bits into bits 0..3 of `sign` (shifted in from the top
+// element down), levels into a 4*B-bit little-endian field.
+template <int B>
+__device__ __forceinline__ void quantize4(const float4 x, const float scale, const uint32_t (&r)[4],
+                                          uint32_t& sign, uint32_t& level)
+{
+    constexpr float S = static_cast<float>((1 << B) - 1);
+    const float v[4] = { x.x, x.y, x.z, x.w };
+    level = 0;
+#pragma unroll
+    for (int k = 3; k >= 0; --k) {
+        sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31); // (sign << 1) | sign bit
+        const float a = fminf(fabsf(v[k]) * scale, S);                     // s|g|/N, one rounding, clamped
+        const float p = __builtin_amdgcn_fractf(a);                         // a - floor(a), exact
+        const float u = static_cast<float>(r[k] >> 8) * 0x1p-24f;           // exact, in [0,1)
+        level = (level << B) + static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
+    }
+}
+
 template <int B, int TILES>
 __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
     const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
@@ -52,85 +69,75 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
     uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
     int64_t packed_stride)
 {
-    using lw_t = typename level_word<B>::type;
     constexpr int CHUNK = QP_TILE * TILES;
     constexpr int MAX_LOCAL_SEG = CHUNK / DQ_GRANULE;
     constexpr float S = static_cast<float>((1 << B) - 1);
 
     __shared__ float lds_scale[MAX_LOCAL_SEG];
-    __shared__ int64_t lds_valid_end[MAX_LOCAL_SEG];
+    __shared__ int32_t lds_valid_end[MAX_LOCAL_SEG]; // relative to the chunk, clamped to CHUNK
     __shared__ __align__(16) uint8_t lds_sign[TILES * QP_THREADS];
     __shared__ __align__(16) uint8_t lds_level[TILES * QP_THREADS * B];
 
-    const int tid = threadIdx.x;
-    const int w = blockIdx.y;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t w = blockIdx.y;
     const int64_t chunk0 = static_cast<int64_t>(blockIdx.x) * CHUNK;
-    const int64_t chunk_end = chunk0 + CHUNK < padded_elems ? chunk0 + CHUNK : padded_elems;
-    const float* g = grads + static_cast<int64_t>(w) * worker_stride;
+    // elements of this chunk that exist (a multiple of 128, at least 128)
+    const uint32_t n_elems = static_cast<uint32_t>(padded_elems - chunk0 < CHUNK ? padded_elems - chunk0 : CHUNK);
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride + chunk0; // uniform base
+    const int32_t* gseg = granule_cseg + (chunk0 >> 7);
 
-    // this lane's inputs first, so the loads are in flight while the segment table is built
+    // This lane's inputs first, so the loads are in flight while the segment table is built.
+    // Lanes past the end of a ragged last chunk re-read its last eight elements (always in
+    // bounds); what they compute is never stored.
     float4 x[TILES][2];
     int32_t seg[TILES];
 #pragma unroll
     for (int it = 0; it < TILES; ++it) {
-        const int64_t P = chunk0 + it * QP_TILE + tid * QP_PER_LANE;
-        if (P < chunk_end) {
-            x[it][0] = *reinterpret_cast<const float4*>(g + P);
-            x[it][1] = *reinterpret_cast<const float4*>(g + P + 4);
-            seg[it] = granule_cseg[P >> 7];
-        } else {
-            x[it][0] = x[it][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-            seg[it] = 0;
-        }
+        uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        e = e < n_elems ? e : n_elems - QP_PER_LANE;
+        x[it][0] = *reinterpret_cast<const float4*>(g + e);
+        x[it][1] = *reinterpret_cast<const float4*>(g + e + 4);
+        seg[it] = gseg[e >> 7];
     }
 
     // compact segment indices grow by at most one per granule, so the chunk's segments fit the table
-    const int32_t seg_first = granule_cseg[chunk0 >> 7];
-    const int32_t seg_last = granule_cseg[(chunk_end - 1) >> 7];
-    if (tid <= seg_last - seg_first) {
+    const int32_t seg_first = gseg[0];
+    const int32_t seg_last = gseg[(n_elems - 1) >> 7];
+    if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
         const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]];
         lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f; // zero, tiny or NaN norm: every level 0
-        lds_valid_end[tid] = cseg_valid_end[seg_first + tid];
+        const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+        lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
     }
     __syncthreads();
 
+    // Philox counter words: quad index P>>2 (low word varies per lane, high word is uniform because
+    // a chunk never straddles a multiple of 2^34 elements), worker, step
+    const uint32_t quad_lo0 = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 2);
+    const uint32_t quad_hi = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 34);
+    const uint32_t worker = worker_base + w;
+
 #pragma unroll
     for (int it = 0; it < TILES; ++it) {
-        const int64_t P = chunk0 + it * QP_TILE + tid * QP_PER_LANE;
-        if (P < chunk_end) {
+        const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        if (e < n_elems) {
             const int local = seg[it] - seg_first;
             const float scale = lds_scale[local];
-            const int64_t n_valid = lds_valid_end[local] - P; // elements of this lane inside the tensor
+            const int32_t n_valid = lds_valid_end[local] - static_cast<int32_t>(e); // may be <= 0 or > 8
 
-            const uint64_t quad = static_cast<uint64_t>(P) >> 2; // even: quad + 1 cannot carry
-            uint32_t r[8];
-            {
-                uint32_t r0[4], r1[4];
-                dq_philox4x32_10(static_cast<uint32_t>(quad), static_cast<uint32_t>(quad >> 32),
-                                 worker_base + w, step, key0, key1, r0);
-                dq_philox4x32_10(static_cast<uint32_t>(quad) + 1u, static_cast<uint32_t>(quad >> 32),
-                                 worker_base + w, step, key0, key1, r1);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) { r[k] = r0[k]; r[4 + k] = r1[k]; }
-            }
-            const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
-                                 x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
-            uint32_t sign = 0;
-            lw_t level = 0;
-#pragma unroll
-            for (int k = QP_PER_LANE - 1; k >= 0; --k) {
-                // (sign << 1) | sign bit of v[k]; element 0 ends up in bit 0
-                sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31);
-                const float a = fminf(fabsf(v[k]) * scale, S);       // s|g|/N, one rounding, clamped
-                const float p = __builtin_amdgcn_fractf(a);           // a - floor(a), exact
-                const float u = static_cast<float>(r[k] >> 8) * 0x1p-24f; // exact, in [0,1)
-                const uint32_t lv = static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
-                level = static_cast<lw_t>(level << B) | lv;
-            }
-            if (n_valid < QP_PER_LANE) { // the tensor ends inside this lane's eight elements
-                const int nv = n_valid > 0 ? static_cast<int>(n_valid) : 0;
+            const uint32_t quad = quad_lo0 + (e >> 2); // even; quad + 1 cannot carry
+            uint32_t r0[4], r1[4];
+            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
+            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
+
+            uint32_t sign = 0, lv_lo, lv_hi;
+            quantize4<B>(x[it][1], scale, r1, sign, lv_hi); // elements 4..7 first: element 0 ends in bit 0
+            quantize4<B>(x[it][0], scale, r0, sign, lv_lo);
+            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * B));
+            if (n_valid < QP_PER_LANE) { // the tensor ends inside (or before) this lane's eight elements
+                const int nv = n_valid > 0 ? n_valid : 0;
                 sign &= (1u << nv) - 1u;
-                level &= static_cast<lw_t>((static_cast<uint64_t>(1) << (nv * B)) - 1u);
+                level &= (static_cast<uint64_t>(1) << (nv * B)) - 1u;
             }
             lds_sign[it * QP_THREADS + tid] = static_cast<uint8_t>(sign);
             stage_bytes<B>(&lds_level[(it * QP_THREADS + tid) * B], level);
@@ -141,16 +148,15 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
     // 16-byte stores; every plane of a chunk is a whole number of 16-byte pieces because the
     // chunk holds a multiple of 128 elements
     uint8_t* msg = packed + static_cast<int64_t>(w) * packed_stride;
-    const int n_elems = static_cast<int>(chunk_end - chunk0);
     {
         uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
         const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
-        for (int i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
     }
     {
         uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + (chunk0 >> 3) * B);
         const uint4* src = reinterpret_cast<const uint4*>(lds_level);
-        for (int i = tid; i < n_elems / 128 * B; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < n_elems / 128 * B; i += QP_THREADS) dst[i] = src[i];
     }
 }
 
@@ -159,7 +165,7 @@ int launch(const dq_plan* plan, const float* grads, int64_t worker_stride, int M
            uint64_t seed, uint32_t step, uint32_t worker_base, uint8_t* packed, int64_t packed_stride,
            hipStream_t stream)
 {
-    constexpr int TILES = 2;
+    constexpr int TILES = DQ_QP_TILES;
     constexpr int CHUNK = QP_TILE * TILES;
     const int64_t n_chunks = (plan->padded_elems + CHUNK - 1) / CHUNK;
     if (n_chunks > INT32_MAX) return DQ_ERR_INVALID_ARG;

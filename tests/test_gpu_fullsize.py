@@ -1,0 +1,162 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times.  Configs 2 and 3 are compared with the oracle in full; config 5 (16 GiB of input)
+on sampled index ranges of every worker plus properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2107_14575_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SEED = wl.QUANT_SEED
+
+
+@pytest.fixture(scope="module")
+def dq():
+    import paper_2107_14575_amd as dq
+    dq.load_library()
+    assert torch.cuda.is_available()
+    return dq
+
+
+def _buffers(plan, M, b_max=8):
+    norms = torch.empty((M, plan.n_seg), dtype=torch.float32, device="cuda")
+    ws = torch.empty(plan.workspace_bytes(M), dtype=torch.uint8, device="cuda")
+    packed = torch.zeros((M, plan.packed_bytes(b_max)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(plan.padded_elems, dtype=torch.float32, device="cuda")
+    return norms, ws, packed, out
+
+
+def _compare_full(dq, oracle, plan, seg_len, g_dev, norms_dev, packed, out, b, step):
+    M = g_dev.shape[0]
+    pk = packed[:, :plan.packed_bytes(b)]
+    dq.quantize_pack(plan, g_dev, norms_dev, b, SEED, step, pk)
+    dq.unpack_dequant_reduce(plan, pk, norms_dev, b, out)
+    torch.cuda.synchronize()
+    g_host = np.ascontiguousarray(g_dev.cpu().numpy())
+    norms = norms_dev.cpu().numpy()
+    want_pk = oracle.quantize_pack(seg_len, g_host, norms, b, SEED, step)
+    got_pk = pk.cpu().numpy()
+    assert np.array_equal(got_pk, want_pk), f"bitstream differs at b={b} step={step}"
+    want_out = oracle.unpack_dequant_reduce(seg_len, want_pk, norms, b)
+    got = out.cpu().numpy()
+    err = np.abs(got.astype(np.float64) - want_out)
+    assert err.max() <= 1e-6 * np.abs(want_out).max()
+    # per element: 1e-6 of the mean magnitude of the dequantized terms
+    starts, dp = wl.seg_starts(seg_len)
+    mag = np.zeros(dp)
+    s = float((1 << b) - 1)
+    for i in range(M):
+        _, level = oracle.unpack(want_pk[i], dp, b)
+        for l, (st, n) in enumerate(zip(starts, seg_len)):
+            unit = float(norms[i, l]) / s if norms[i, l] >= np.float32(2.0 ** -100) else 0.0
+            mag[st:st + n] += level[st:st + n] * unit
+    assert np.all(err <= 1e-6 * mag / M + 1.5e-45)
+
+
+def test_config2_resnet18_shaped_dynamic_bits(dq, oracle):
+    """62 tensors, 11.17M parameters, M = 8, 20 steps; the gradient scale decays 0.7x per step so
+    the rule of Eq. (17) walks b_t down from 8; every step's b_t matches the oracle's and the
+    bitstreams of steps 0, 7, 13 and 19 are compared in full."""
+    M, T, alpha = 8, 20, 0.9
+    seg_len, g0 = wl.resnet18_like(M=M, step=0, device="cuda")
+    plan = dq.Plan(seg_len)
+    norms_dev, ws, packed, out = _buffers(plan, M)
+    dq.norm(plan, g0, norms_dev, ws)
+    torch.cuda.synchronize()
+    n0 = norms_dev.cpu().numpy().astype(np.float64)
+    gbar0 = np.sqrt((n0 ** 2).sum() / M)
+    # eps_hat such that s* = 0.9 * 255 at t = 0: b_0 = 8
+    eps_hat = T * (alpha ** ((T - 1) / 2.0) * gbar0 / (0.9 * 255.0)) ** 2
+    trace = []
+    for t in range(T):
+        seg_len, g = wl.resnet18_like(M=M, step=t, device="cuda")
+        dq.norm(plan, g, norms_dev, ws)
+        torch.cuda.synchronize()
+        norms = norms_dev.cpu().numpy()
+        b, gbar = dq.select_bits(norms, t, T, eps_hat, alpha, 2, 8)
+        want_b, want_gbar = oracle.select_bits(norms, t, T, eps_hat, alpha, 2, 8)
+        assert b == want_b and abs(gbar - want_gbar) <= 1e-15 * want_gbar
+        trace.append(b)
+        if t in (0, 7, 13, 19):
+            want_norms = oracle.norm(seg_len, np.ascontiguousarray(g.cpu().numpy()))
+            assert np.all(np.abs(norms.astype(np.float64) - want_norms) <= np.spacing(want_norms))
+            _compare_full(dq, oracle, plan, seg_len, g, norms_dev, packed, out, b, t)
+        else:
+            pk = packed[:, :plan.packed_bytes(b)]
+            dq.quantize_pack(plan, g, norms_dev, b, SEED, t, pk)
+            dq.unpack_dequant_reduce(plan, pk, norms_dev, b, out)
+    torch.cuda.synchronize()
+    assert trace[0] == 8 and trace[-1] == 2
+    assert all(x >= y for x, y in zip(trace, trace[1:]))
+    plan.close()
+
+
+def test_config3_transformer_shaped_every_width(dq, oracle):
+    """102 tensors, 12.55M parameters with 90% of the embedding rows exactly zero, M = 16,
+    b swept over 1..8."""
+    M = 16
+    seg_len, g = wl.transformer_like(M=M, device="cuda")
+    plan = dq.Plan(seg_len)
+    norms_dev, ws, packed, out = _buffers(plan, M)
+    dq.norm(plan, g, norms_dev, ws)
+    torch.cuda.synchronize()
+    want_norms = oracle.norm(seg_len, np.ascontiguousarray(g.cpu().numpy()))
+    norms = norms_dev.cpu().numpy()
+    assert np.all(np.abs(norms.astype(np.float64) - want_norms) <= np.spacing(want_norms))
+    for b in range(1, 9):
+        _compare_full(dq, oracle, plan, seg_len, g, norms_dev, packed, out, b, step=b)
+    plan.close()
+
+
+def test_config5_large_flat_gradient_sampled(dq, oracle):
+    """D = 2^28 per worker, M = 16 (16 GiB of input).  Index ranges at the start, around the
+    middle and at the end are compared with the oracle for every worker, bit for bit; the norms
+    of two workers are compared in full; and at every element the average stays within the
+    quantization step of the true mean (|Q(g)_j - g_j| <= N/s per worker)."""
+    D, M = 1 << 28, 16
+    seg_len, g = wl.flat_student_t(D=D, M=M, device="cuda")
+    plan = dq.Plan(seg_len)
+    norms_dev, ws, packed, out = _buffers(plan, M, b_max=4)
+    dq.norm(plan, g, norms_dev, ws)
+    torch.cuda.synchronize()
+    norms = norms_dev.cpu().numpy()
+    for i in (0, M - 1):
+        want = oracle.norm(seg_len, np.ascontiguousarray(g[i:i + 1].cpu().numpy()))
+        assert abs(float(norms[i, 0]) - float(want[0, 0])) <= np.spacing(want[0, 0])
+    ranges = [(0, 1 << 16), ((1 << 27) - (1 << 15), (1 << 27) + (1 << 15)), (D - (1 << 16), D),
+              (8192 * 1237 - 128, 8192 * 1237 + 256)]
+    for b, step in ((4, 0), (3, 5)):
+        pk = packed[:, :plan.packed_bytes(b)]
+        dq.quantize_pack(plan, g, norms_dev, b, SEED, step, pk)
+        dq.unpack_dequant_reduce(plan, pk, norms_dev, b, out)
+        torch.cuda.synchronize()
+        for p0, p1 in ranges:
+            g_slice = np.ascontiguousarray(g[:, p0:p1].cpu().numpy())
+            sign, level = oracle.quantize_range(seg_len, g_slice, norms, b, SEED, step, p0, p1)
+            sign_bytes = pk[:, p0 // 8:p1 // 8].cpu().numpy()
+            lv0 = D // 8 + p0 * b // 8
+            level_bytes = pk[:, lv0:lv0 + (p1 - p0) * b // 8].cpu().numpy()
+            for i in range(M):
+                want = oracle.pack(sign[i], level[i], b)
+                assert np.array_equal(sign_bytes[i], want[:(p1 - p0) // 8]), (b, p0, i)
+                assert np.array_equal(level_bytes[i], want[(p1 - p0) // 8:]), (b, p0, i)
+            want_out = oracle.dequant_reduce_range(seg_len, sign, level, norms, b, p0, p1)
+            got = out[p0:p1].cpu().numpy()
+            s = float((1 << b) - 1)
+            mag = (level.astype(np.float64) * (norms[:, :1].astype(np.float64) / s)).sum(axis=0) / M
+            err = np.abs(got.astype(np.float64) - want_out)
+            assert np.all(err <= 1e-6 * mag + 1.5e-45), (b, p0)
+        # any-size property, evaluated on the device in chunks
+        bound = float(norms.astype(np.float64).sum() / M / ((1 << b) - 1)) * (1 + 2.0 ** -20)
+        worst = 0.0
+        for c0 in range(0, D, 1 << 26):
+            mean = g[:, c0:c0 + (1 << 26)].mean(dim=0)
+            worst = max(worst, float((out[c0:c0 + (1 << 26)] - mean).abs().max()))
+        assert worst <= bound
+        # the sign plane is the IEEE sign bit of every element (first 2^20 elements of worker 3)
+        n = 1 << 20
+        got_sign = np.unpackbits(pk[3, :n // 8].cpu().numpy(), bitorder="little")
+        assert np.array_equal(got_sign, np.signbit(g[3, :n].cpu().numpy()).astype(np.uint8))
+    plan.close()
