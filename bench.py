@@ -92,6 +92,10 @@ def main() -> None:
     ap.add_argument("--fixed-bits", type=int, default=0, help="use this b every step instead of the rule")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=26)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed region, one plain device copy of the output buffer (4*D' bytes "
+                         "read, 4*D' written): the known-size reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build measures the one-GPU hot path only (M workers simulated in-device); "
@@ -162,6 +166,11 @@ def main() -> None:
         step(t, True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+
+    if args.copy_probe:
+        probe = torch.empty_like(out)
+        probe.copy_(out)
+        torch.cuda.synchronize()
 
     ms_per_step = elapsed / args.steps * 1e3
     in_bytes = M * D * 4
