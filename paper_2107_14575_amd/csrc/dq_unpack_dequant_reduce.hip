@@ -4,8 +4,9 @@
 //
 // Work split.  One workgroup (256 lanes) owns 8192 consecutive padded elements; a lane owns 32 of
 // them, so per worker it reads one sign dword and B level dwords -- every load is dword aligned
-// for every B -- and keeps 32 binary32 accumulators.  Per (worker, element): field extract,
-// convert, put the sign bit on the worker's unit (shift, v_and_or), one FMA.
+// for every B -- and keeps 32 binary32 accumulators.  Per (worker, element): convert the level
+// (fields spread one per byte first when B divides 8, so the convert needs no extract), put the
+// sign bit on the worker's unit (shift, v_and_or), one FMA.
 //
 // The 32 results of a lane are consecutive in memory, so storing them directly would be 16-byte
 // pieces 128 bytes apart; they go through LDS (XOR-swizzled 16-byte slots, conflict free both
@@ -33,6 +34,34 @@ __device__ __forceinline__ uint32_t level_field(const uint32_t (&wd)[B], int k)
     // straddles: funnel-shift the pair down, then mask
     const uint32_t lo = __builtin_amdgcn_alignbit(wd[word + 1 < B ? word + 1 : word], wd[word], off);
     return lo & ((1u << B) - 1u);
+}
+
+// Calls f(k, (float)level_k) for the 32 levels of a lane.  When B divides 8 the fields of a dword
+// are first spread to one per byte (a shift and a mask serve four levels), so each conversion is
+// a single v_cvt_f32_ubyteN with no separate field extract.
+template <int B, typename F>
+__device__ __forceinline__ void for_each_level(const uint32_t (&wd)[B], F&& f)
+{
+    if constexpr (8 % B == 0) {
+        constexpr int R = 8 / B;                                   // fields per byte
+        constexpr uint32_t MASK = ((1u << B) - 1u) * 0x01010101u;  // one field per byte
+#pragma unroll
+        for (int w = 0; w < B; ++w) {
+#pragma unroll
+            for (int s = 0; s < R; ++s) {
+                uint32_t t = B == 8 ? wd[w] : (wd[w] >> (s * B)) & MASK;
+                // keep the spread form: without this the compiler folds shift, mask and byte select
+                // back into one field extract per level
+                if constexpr (B != 8) asm("" : "+v"(t));
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    f(w * (32 / B) + j * R + s, static_cast<float>((t >> (8 * j)) & 0xFFu));
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < UR_PER_LANE; ++k) f(k, static_cast<float>(level_field<B>(wd, k)));
+    }
 }
 
 template <int B>
@@ -77,11 +106,10 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
         const uint8_t* sign_ptr = packed + (P0 >> 3);
         const uint8_t* level_ptr = packed + (padded_elems >> 3) + (P0 >> 3) * B;
         const float* unit_ptr = lds_unit + local * M;
-#pragma unroll 4
-        for (int w = 0; w < M; ++w) {
-            const uint32_t sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
+        // one worker's sign dword and B level dwords of this lane
+        auto load_worker = [&](int w, uint32_t& sg, uint32_t (&wd)[B]) {
+            sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
             const uint32_t* lp = reinterpret_cast<const uint32_t*>(level_ptr + static_cast<int64_t>(w) * packed_stride);
-            uint32_t wd[B];
             if constexpr (B % 4 == 0) {
 #pragma unroll
                 for (int q = 0; q < B / 4; ++q) {
@@ -98,14 +126,28 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
 #pragma unroll
                 for (int q = 0; q < B; ++q) wd[q] = lp[q];
             }
-            const float unit = unit_ptr[w];
-#pragma unroll
-            for (int k = 0; k < UR_PER_LANE; ++k) {
-                const float lv = static_cast<float>(level_field<B>(wd, k));
+        };
+        auto accumulate = [&](uint32_t sg, const uint32_t (&wd)[B], float unit) {
+            for_each_level<B>(wd, [&](int k, float lv) {
                 // sign bit of element k on top of the unit, whose own sign bit is always clear
                 const float su = __uint_as_float(__float_as_uint(unit) | ((sg << (31 - k)) & 0x80000000u));
                 acc[k] = __builtin_fmaf(lv, su, acc[k]);
-            }
+            });
+        };
+        // workers four at a time, so that four messages' loads are in flight together
+        constexpr int GROUP = 4;
+        int w = 0;
+        for (; w + GROUP <= M; w += GROUP) {
+            uint32_t sg[GROUP], wd[GROUP][B];
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i) load_worker(w + i, sg[i], wd[i]);
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i) accumulate(sg[i], wd[i], unit_ptr[w + i]);
+        }
+        for (; w < M; ++w) {
+            uint32_t sg, wd[B];
+            load_worker(w, sg, wd);
+            accumulate(sg, wd, unit_ptr[w]);
         }
         const int nv = n_valid >= UR_PER_LANE ? UR_PER_LANE : (n_valid > 0 ? static_cast<int>(n_valid) : 0);
 #pragma unroll
