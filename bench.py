@@ -172,6 +172,24 @@ def main() -> None:
         probe.copy_(out)
         torch.cuda.synchronize()
 
+    def plain_kernel_ceiling(write_per_read: float, reps: int = 5):
+        """GB/s (read + written) a plain streaming kernel with no arithmetic reaches on this GPU for
+        the given write/read byte ratio: it reads up to 4 GiB of the gradients and writes into
+        the message buffer.  The practical ceiling next to the published HBM peak."""
+        n_wg = min(grads.numel() * 4, 4 << 30) // 16384
+        pieces = min(1024, int(round(1024 * write_per_read)))
+        if n_wg < 1 or packed.numel() < max(n_wg * pieces * 16, 16):
+            return None
+        dq.probe_stream(grads, packed, n_wg, pieces)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            dq.probe_stream(grads, packed, n_wg, pieces)
+        e1.record()
+        torch.cuda.synchronize()
+        return n_wg * (16384 + pieces * 16) * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
     ms_per_step = elapsed / args.steps * 1e3
     in_bytes = M * D * 4
     value = in_bytes / (elapsed / args.steps) / 1e9
@@ -208,6 +226,23 @@ def main() -> None:
             "dq_norm": rl(n_bytes, t_norm),
         },
     }
+    # what a kernel with no arithmetic reaches for the same read/write mixes (large workloads only:
+    # below 256 MiB the data sits in the Infinity Cache and the figure says nothing about HBM)
+    if M * dp * 4 >= (1 << 28):
+        b_mode = max(set(bits), key=bits.count)
+        mixes = {"read_only": 0.0, "dq_quantize_pack": (b_mode + 1) / 32.0,
+                 "dq_unpack_dequant_reduce": 4.0 / (M * (b_mode + 1) / 8.0)}
+        ceil = {k: plain_kernel_ceiling(min(v, 1.0)) for k, v in mixes.items()}
+        result["plain_kernel_ceiling"] = {
+            "what": "GB/s (read+written) of dq_probe_stream, a streaming kernel without arithmetic, at the "
+                    f"write/read byte ratio of each pass for b={b_mode}",
+            **{k: (round(v, 1) if v else None) for k, v in ceil.items()}}
+        for k in ("dq_quantize_pack", "dq_unpack_dequant_reduce"):
+            if ceil.get(k):
+                result["kernels"][k]["frac_of_plain_kernel"] = round(result["kernels"][k]["achieved"] / ceil[k], 4)
+        if ceil.get("read_only"):
+            result["kernels"]["dq_norm"]["frac_of_plain_kernel"] = round(result["kernels"]["dq_norm"]["achieved"] / ceil["read_only"], 4)
+        result["roofline"]["frac_of_plain_kernel"] = result["kernels"]["dq_quantize_pack"].get("frac_of_plain_kernel")
     if not args.no_cpu_baseline:
         b_mode = max(set(bits), key=bits.count)
         result["cpu_baseline"] = cpu_baseline(seg_len, grads, b_mode, 1 << args.cpu_sample_log2)

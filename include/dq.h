@@ -110,6 +110,14 @@ int dq_unpack_dequant_reduce(const dq_plan_t* plan, const uint8_t* packed_dev,
                              int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
                              int b, float* out_dev, void* hip_stream);
 
+/* Measurement aid, not a step of the method (for callers that report rooflines): a plain
+ * streaming kernel with no arithmetic to speak of.  Each workgroup reads 16 KiB of src_dev with
+ * 16-byte loads and writes pieces_per_wg (0..1024) 16-byte pieces derived from them to dst_dev,
+ * contiguously; n_wg workgroups.  Reads n_wg*16384 bytes, writes n_wg*pieces_per_wg*16 bytes.
+ * Timed by the caller, it gives the bandwidth this GPU reaches for a given read/write mix, the
+ * practical ceiling next to the published HBM peak.  Both pointers 16-byte aligned. */
+int dq_probe_stream(const void* src_dev, void* dst_dev, int64_t n_wg, int pieces_per_wg, void* hip_stream);
+
 const char* dq_status_string(int status);
 
 #ifdef __cplusplus

@@ -8,10 +8,11 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     norm,
+    probe_stream,
     quantize_pack,
     select_bits,
     unpack_dequant_reduce,
 )
 
-__all__ = ["DQError", "Plan", "library_path", "load_library", "norm", "quantize_pack",
+__all__ = ["DQError", "Plan", "library_path", "load_library", "norm", "probe_stream", "quantize_pack",
            "select_bits", "unpack_dequant_reduce"]

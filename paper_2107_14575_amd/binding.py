@@ -18,7 +18,8 @@ MAX_WORKERS = 64
 EXPORTS = (
     "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems",
     "dq_plan_segment_start", "dq_packed_bytes", "dq_workspace_bytes", "dq_plan_has_device",
-    "dq_norm", "dq_select_bits", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_status_string",
+    "dq_norm", "dq_select_bits", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
+    "dq_status_string",
 )
 
 
@@ -72,6 +73,8 @@ def load_library():
     L.dq_quantize_pack.restype = C.c_int
     L.dq_unpack_dequant_reduce.argtypes = [vp, vp, i64, C.c_int, vp, C.c_int, vp, vp]
     L.dq_unpack_dequant_reduce.restype = C.c_int
+    L.dq_probe_stream.argtypes = [vp, vp, i64, C.c_int, vp]
+    L.dq_probe_stream.restype = C.c_int
     L.dq_status_string.argtypes = [C.c_int]
     L.dq_status_string.restype = C.c_char_p
     _lib = L
@@ -180,3 +183,13 @@ def unpack_dequant_reduce(plan: Plan, packed, norms, b: int, out, stream=None) -
            load_library().dq_unpack_dequant_reduce(plan.handle, packed.data_ptr(), int(packed.stride(0)), M,
                                                    norms.data_ptr(), b, out.data_ptr(),
                                                    _stream_handle(stream)))
+
+
+def probe_stream(src, dst, n_wg: int, pieces_per_wg: int, stream=None) -> None:
+    """Measurement aid: plain streaming kernel, 16 KiB read per workgroup from `src`,
+    `pieces_per_wg` 16-byte pieces written to `dst` (CUDA tensors large enough for both)."""
+    if src.numel() * src.element_size() < n_wg * 16384 or \
+            dst.numel() * dst.element_size() < max(n_wg * pieces_per_wg * 16, 16):
+        raise ValueError("probe buffers too small")
+    _check("dq_probe_stream", load_library().dq_probe_stream(src.data_ptr(), dst.data_ptr(), n_wg,
+                                                             pieces_per_wg, _stream_handle(stream)))
