@@ -167,6 +167,21 @@ def main() -> None:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # the reduce pass fused with the model update of Algorithm 1 (x <- x - eta*g_hat), timed on its own
+    x_model = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    b_last = marks[-1][0]
+    pk_last = packed[:, :plan.packed_bytes(b_last)]
+    dq.unpack_dequant_reduce_update(plan, pk_last, norms_dev, b_last, 1e-3, x_model)
+    torch.cuda.synchronize()
+    u0, u1 = ev(), ev()
+    u0.record()
+    for _ in range(5):
+        dq.unpack_dequant_reduce_update(plan, pk_last, norms_dev, b_last, 1e-3, x_model)
+    u1.record()
+    torch.cuda.synchronize()
+    t_upd = u0.elapsed_time(u1) / 5
+    del x_model
+
     if args.copy_probe:
         probe = torch.empty_like(out)
         probe.copy_(out)
@@ -224,6 +239,7 @@ def main() -> None:
             "dq_quantize_pack": dict(rl(q_bytes, t_quant), fp32_in_GBps=round(in_bytes / t_quant / 1e6, 1)),
             "dq_unpack_dequant_reduce": dict(rl(r_bytes, t_red), fp32_in_GBps=round(in_bytes / t_red / 1e6, 1)),
             "dq_norm": rl(n_bytes, t_norm),
+            "dq_unpack_dequant_reduce_update": rl(dp * (M * (b_last + 1) / 8 + 8), t_upd),
         },
     }
     # what a kernel with no arithmetic reaches for the same read/write mixes (large workloads only:

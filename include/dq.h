@@ -8,6 +8,7 @@
  *     dq_select_bits             b_t from the dynamic rule                   (Eq. (17))
  *     dq_quantize_pack           sign + stochastic level per element, packed (Eq. (5)-(6), Eq. (7))
  *     dq_unpack_dequant_reduce   server average of the M messages            (Alg. 1 "Average", Eq. (2))
+ *     dq_unpack_dequant_reduce_update   the same fused with x <- x - eta*g_hat  (Alg. 1 "Update")
  *
  * CONVENTIONS
  *   b       number of LEVEL bits, 1..8.  s = 2^b - 1 quantization levels; one element costs b + 1
@@ -109,6 +110,25 @@ int dq_quantize_pack(const dq_plan_t* plan, const float* grads_dev, int64_t work
 int dq_unpack_dequant_reduce(const dq_plan_t* plan, const uint8_t* packed_dev,
                              int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
                              int b, float* out_dev, void* hip_stream);
+
+/* dq_unpack_dequant_reduce fused with the server's model update of Algorithm 1 ("Update the
+ * global parameters"): x_P <- x_P - eta * g_hat_P for every element, g_hat as above.
+ *   x_dev     [D'] float, read and written (pad elements unchanged)
+ *   ghat_dev  [D'] float or NULL: when given, g_hat is also written there as by
+ *             dq_unpack_dequant_reduce. */
+int dq_unpack_dequant_reduce_update(const dq_plan_t* plan, const uint8_t* packed_dev,
+                                    int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
+                                    int b, float eta, float* x_dev, float* ghat_dev, void* hip_stream);
+
+/* Eq. (24), the practical estimate of the convergence factor: alpha_est = (F(x_t)/F(x_0))^(1/t).
+ * Host code.  Returns -1 unless t >= 1, F_t > 0 and F_0 > 0. */
+double dq_alpha_est(double F_t, double F_0, int64_t t);
+
+/* Eq. (7), the communication cost of one iteration in bits: W * (d * (b + 1) + n_norms * B_pre),
+ * b level bits plus the sign bit per element and B_pre bits for each norm a worker sends (the
+ * paper has one norm per gradient; with per-tensor norms n_norms = n_seg).  b = 31 with
+ * n_norms = 0 is uncompressed SGD.  Host code.  Returns -1 on a negative or out-of-range argument. */
+int64_t dq_comm_cost_bits(int W, int64_t d, int b, int32_t n_norms, int B_pre);
 
 /* Measurement aid, not a step of the method (for callers that report rooflines): a plain
  * streaming kernel with no arithmetic to speak of.  Each workgroup reads 16 KiB of src_dev with

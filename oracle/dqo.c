@@ -380,6 +380,32 @@ int dqo_unpack_dequant_reduce(const int64_t *seg_len, int32_t n_seg, const uint8
     return dqo_dequant_reduce(seg_len, n_seg, sign, level, M, norms, b, out);
 }
 
+/* ------------------------------------------------------------------------------------------- */
+/* Server update of Algorithm 1: x_{t+1} = x_t - eta * g_hat_t (also Eq. (2)).  The product and   */
+/* the difference are formed in binary64 and rounded once to binary32.                            */
+/* ------------------------------------------------------------------------------------------- */
+int dqo_update(float *x, const float *ghat, int64_t n, float eta)
+{
+    if (!x || !ghat || n < 0) return DQO_ERR_INVALID_ARG;
+    for (int64_t j = 0; j < n; ++j) x[j] = (float)((double)x[j] - (double)eta * (double)ghat[j]);
+    return DQO_OK;
+}
+
+/* Eq. (24): alpha_est = [F(x_t)/F(x_0)]^(1/t); -1 when undefined */
+double dqo_alpha_est(double F_t, double F_0, int64_t t)
+{
+    if (t < 1 || !(F_t > 0.0) || !(F_0 > 0.0)) return -1.0;
+    return pow(F_t / F_0, 1.0 / (double)t);
+}
+
+/* Eq. (7), one iteration: W [ d b_paper + B_pre ] bits with b_paper = b + 1; n_norms norms of
+ * B_pre bits per worker (the paper has one). */
+int64_t dqo_comm_cost_bits(int W, int64_t d, int b, int32_t n_norms, int B_pre)
+{
+    if (W < 1 || d < 0 || b < 0 || b > 31 || n_norms < 0 || B_pre < 0) return -1;
+    return (int64_t)W * (d * (int64_t)(b + 1) + (int64_t)n_norms * B_pre);
+}
+
 /* threads the parallel loops use (1 when built without OpenMP) */
 #ifdef _OPENMP
 #include <omp.h>

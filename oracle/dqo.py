@@ -68,6 +68,11 @@ def lib():
                                         C.c_int64, u8p]
         L.dqo_unpack_dequant_reduce.argtypes = [i64p, C.c_int32, u8p, C.c_int64, C.c_int32, f32p,
                                                 C.c_int, f32p, u8p]
+        L.dqo_update.argtypes = [f32p, f32p, C.c_int64, C.c_float]
+        L.dqo_alpha_est.argtypes = [C.c_double, C.c_double, C.c_int64]
+        L.dqo_alpha_est.restype = C.c_double
+        L.dqo_comm_cost_bits.argtypes = [C.c_int, C.c_int64, C.c_int, C.c_int32, C.c_int]
+        L.dqo_comm_cost_bits.restype = C.c_int64
         L.dqo_num_threads.restype = C.c_int
         L.dqo_set_num_threads.argtypes = [C.c_int]
         _lib = L
@@ -267,3 +272,26 @@ def unpack_dequant_reduce(seg_len, packed, norms, b):
                                            _p(out, C.c_float), _p(scratch, C.c_uint8)),
            "unpack_dequant_reduce")
     return out
+
+
+def update(x, ghat, eta):
+    """in place: x <- x - eta * ghat (numpy float32 arrays of equal length)."""
+    if x.dtype != np.float32 or ghat.dtype != np.float32 or x.shape != ghat.shape or not x.flags.c_contiguous:
+        raise ValueError("x and ghat must be equal-shape C-contiguous float32 arrays")
+    g = np.ascontiguousarray(ghat)
+    _check(lib().dqo_update(_p(x, C.c_float), _p(g, C.c_float), x.size, eta), "update")
+    return x
+
+
+def alpha_est(F_t, F_0, t):
+    v = float(lib().dqo_alpha_est(F_t, F_0, t))
+    if v < 0:
+        raise ValueError("alpha_est undefined")
+    return v
+
+
+def comm_cost_bits(W, d, b, n_norms=1, B_pre=32):
+    v = int(lib().dqo_comm_cost_bits(W, d, b, n_norms, B_pre))
+    if v < 0:
+        raise ValueError("bad argument")
+    return v

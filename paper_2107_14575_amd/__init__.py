@@ -4,6 +4,9 @@ declared in ``include/dq.h``; this package only marshals arguments (``binding``)
 seeded synthetic workload generators (``workloads``)."""
 from .binding import (  # noqa: F401
     DQError,
+    alpha_est,
+    comm_cost_bits,
+    unpack_dequant_reduce_update,
     Plan,
     library_path,
     load_library,
@@ -14,5 +17,5 @@ from .binding import (  # noqa: F401
     unpack_dequant_reduce,
 )
 
-__all__ = ["DQError", "Plan", "library_path", "load_library", "norm", "probe_stream", "quantize_pack",
+__all__ = ["DQError", "alpha_est", "comm_cost_bits", "unpack_dequant_reduce_update", "Plan", "library_path", "load_library", "norm", "probe_stream", "quantize_pack",
            "select_bits", "unpack_dequant_reduce"]

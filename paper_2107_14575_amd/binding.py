@@ -19,7 +19,7 @@ EXPORTS = (
     "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems",
     "dq_plan_segment_start", "dq_packed_bytes", "dq_workspace_bytes", "dq_plan_has_device",
     "dq_norm", "dq_select_bits", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
-    "dq_status_string",
+    "dq_unpack_dequant_reduce_update", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
 )
 
 
@@ -73,6 +73,12 @@ def load_library():
     L.dq_quantize_pack.restype = C.c_int
     L.dq_unpack_dequant_reduce.argtypes = [vp, vp, i64, C.c_int, vp, C.c_int, vp, vp]
     L.dq_unpack_dequant_reduce.restype = C.c_int
+    L.dq_unpack_dequant_reduce_update.argtypes = [vp, vp, i64, C.c_int, vp, C.c_int, C.c_float, vp, vp, vp]
+    L.dq_unpack_dequant_reduce_update.restype = C.c_int
+    L.dq_alpha_est.argtypes = [C.c_double, C.c_double, i64]
+    L.dq_alpha_est.restype = C.c_double
+    L.dq_comm_cost_bits.argtypes = [C.c_int, i64, C.c_int, i32, C.c_int]
+    L.dq_comm_cost_bits.restype = i64
     L.dq_probe_stream.argtypes = [vp, vp, i64, C.c_int, vp]
     L.dq_probe_stream.restype = C.c_int
     L.dq_status_string.argtypes = [C.c_int]
@@ -193,3 +199,26 @@ def probe_stream(src, dst, n_wg: int, pieces_per_wg: int, stream=None) -> None:
         raise ValueError("probe buffers too small")
     _check("dq_probe_stream", load_library().dq_probe_stream(src.data_ptr(), dst.data_ptr(), n_wg,
                                                              pieces_per_wg, _stream_handle(stream)))
+
+
+def unpack_dequant_reduce_update(plan: Plan, packed, norms, b: int, eta: float, x, ghat=None, stream=None) -> None:
+    """x: float32 CUDA [D'], updated in place to x - eta * g_hat; ghat (optional) receives g_hat."""
+    M = int(packed.shape[0])
+    _check("dq_unpack_dequant_reduce_update",
+           load_library().dq_unpack_dequant_reduce_update(
+               plan.handle, packed.data_ptr(), int(packed.stride(0)), M, norms.data_ptr(), b, eta,
+               x.data_ptr(), None if ghat is None else ghat.data_ptr(), _stream_handle(stream)))
+
+
+def alpha_est(F_t: float, F_0: float, t: int) -> float:
+    v = float(load_library().dq_alpha_est(F_t, F_0, t))
+    if v < 0:
+        raise DQError("dq_alpha_est", -1, "invalid argument")
+    return v
+
+
+def comm_cost_bits(W: int, d: int, b: int, n_norms: int = 1, B_pre: int = 32) -> int:
+    v = int(load_library().dq_comm_cost_bits(W, d, b, n_norms, B_pre))
+    if v < 0:
+        raise DQError("dq_comm_cost_bits", -1, "invalid argument")
+    return v

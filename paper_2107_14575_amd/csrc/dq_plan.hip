@@ -213,6 +213,20 @@ extern "C" int dq_select_bits(const float* norms_host, int M, int n_seg, int64_t
     return DQ_OK;
 }
 
+// Eq. (24): alpha_est = (F(x_t) / F(x_0))^(1/t).
+extern "C" double dq_alpha_est(double F_t, double F_0, int64_t t)
+{
+    if (t < 1 || !(F_t > 0.0) || !(F_0 > 0.0)) return -1.0;
+    return pow(F_t / F_0, 1.0 / static_cast<double>(t));
+}
+
+// Eq. (7), one iteration: W * (d * b_paper + n_norms * B_pre) with b_paper = b + 1.
+extern "C" int64_t dq_comm_cost_bits(int W, int64_t d, int b, int32_t n_norms, int B_pre)
+{
+    if (W < 1 || d < 0 || b < 0 || b > 31 || n_norms < 0 || B_pre < 0) return -1;
+    return static_cast<int64_t>(W) * (d * (b + 1) + static_cast<int64_t>(n_norms) * B_pre);
+}
+
 extern "C" const char* dq_status_string(int status)
 {
     switch (status) {

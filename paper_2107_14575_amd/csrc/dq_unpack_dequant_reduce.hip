@@ -15,6 +15,9 @@
 // The units N/s of the segments a workgroup touches are computed once per workgroup into LDS.
 //
 // HBM traffic per output element: M(B+1)/8 bytes read, 4 bytes written.
+//
+// With a model vector x the epilogue also applies the update of Algorithm 1, x <- x - eta * g_hat
+// (8 more bytes per element, read and written with the same coalesced 16-byte accesses).
 #include "dq_internal.h"
 
 namespace {
@@ -68,7 +71,8 @@ template <int B>
 __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
     const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
     int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
-    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, float inv_M, float* __restrict__ out)
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, float inv_M, float* __restrict__ out,
+    float* __restrict__ x, float eta)
 {
     constexpr float S = static_cast<float>((1 << B) - 1);
     extern __shared__ __align__(16) uint8_t lds_raw[];
@@ -167,21 +171,58 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
         const int src_lane = 8 * j + (lane >> 3), q = lane & 7;
         const float4 v = wave_out[src_lane * 8 + (q ^ (src_lane & 7))];
         const int64_t P = tile0 + wave * 2048 + 256 * j + 4 * lane;
-        if (P < tile_end) *reinterpret_cast<float4*>(out + P) = v;
+        if (P < tile_end) {
+            if (out) *reinterpret_cast<float4*>(out + P) = v;
+            if (x) { // model update of Algorithm 1: x <- x - eta * g_hat (pads: g_hat is +0, x unchanged)
+                float4 xv = *reinterpret_cast<const float4*>(x + P);
+                xv.x = __builtin_fmaf(-eta, v.x, xv.x);
+                xv.y = __builtin_fmaf(-eta, v.y, xv.y);
+                xv.z = __builtin_fmaf(-eta, v.z, xv.z);
+                xv.w = __builtin_fmaf(-eta, v.w, xv.w);
+                *reinterpret_cast<float4*>(x + P) = xv;
+            }
+        }
     }
 }
 
 template <int B>
 int launch(const dq_plan* plan, const uint8_t* packed, int64_t packed_stride, int M, const float* norms,
-           float* out, hipStream_t stream)
+           float* out, float* x, float eta, hipStream_t stream)
 {
     const int64_t n_tiles = (plan->padded_elems + UR_TILE - 1) / UR_TILE;
     if (n_tiles > INT32_MAX) return DQ_ERR_INVALID_ARG;
     const size_t lds_bytes = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(float);
     hipLaunchKernelGGL((k_unpack_dequant_reduce<B>), dim3(static_cast<unsigned>(n_tiles)), dim3(UR_THREADS), lds_bytes,
                        stream, packed, packed_stride, M, norms, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg,
-                       plan->d_cseg_valid_end, plan->padded_elems, 1.0f / static_cast<float>(M), out);
+                       plan->d_cseg_valid_end, plan->padded_elems, 1.0f / static_cast<float>(M), out, x, eta);
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
+int reduce_entry(const dq_plan_t* plan, const uint8_t* packed_dev, int64_t packed_worker_stride_bytes, int M,
+                 const float* norms_dev, int b, float* out_dev, float* x_dev, float eta, void* hip_stream)
+{
+    if (!plan || !packed_dev || !norms_dev || (!out_dev && !x_dev)) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS || b < 1 || b > 8) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < dq_packed_bytes(plan, b) || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(packed_dev) || !dq_aligned16(out_dev) || !dq_aligned16(x_dev) ||
+        (reinterpret_cast<uintptr_t>(norms_dev) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    if (x_dev && !(eta == eta)) return DQ_ERR_INVALID_ARG; // NaN learning rate
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    if (plan->padded_elems == 0) return DQ_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    switch (b) {
+    case 1: return launch<1>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, x_dev, eta, stream);
+    case 2: return launch<2>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, x_dev, eta, stream);
+    case 3: return launch<3>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, x_dev, eta, stream);
+    case 4: return launch<4>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, x_dev, eta, stream);
+    case 5: return launch<5>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, x_dev, eta, stream);
+    case 6: return launch<6>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, x_dev, eta, stream);
+    case 7: return launch<7>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, x_dev, eta, stream);
+    default: return launch<8>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, x_dev, eta, stream);
+    }
 }
 
 } // namespace
@@ -190,24 +231,17 @@ extern "C" int dq_unpack_dequant_reduce(const dq_plan_t* plan, const uint8_t* pa
                                         int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
                                         int b, float* out_dev, void* hip_stream)
 {
-    if (!plan || !packed_dev || !norms_dev || !out_dev) return DQ_ERR_INVALID_ARG;
-    if (M < 1 || M > DQ_MAX_WORKERS || b < 1 || b > 8) return DQ_ERR_INVALID_ARG;
-    if (packed_worker_stride_bytes < dq_packed_bytes(plan, b) || (packed_worker_stride_bytes & 15))
-        return DQ_ERR_INVALID_ARG;
-    if (!dq_aligned16(packed_dev) || !dq_aligned16(out_dev) || (reinterpret_cast<uintptr_t>(norms_dev) & 3u))
-        return DQ_ERR_INVALID_ARG;
-    const int rc = dq_plan_check_device(plan);
-    if (rc != DQ_OK) return rc;
-    if (plan->padded_elems == 0) return DQ_OK;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    switch (b) {
-    case 1: return launch<1>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
-    case 2: return launch<2>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
-    case 3: return launch<3>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
-    case 4: return launch<4>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
-    case 5: return launch<5>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
-    case 6: return launch<6>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
-    case 7: return launch<7>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
-    default: return launch<8>(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, stream);
-    }
+    if (!out_dev) return DQ_ERR_INVALID_ARG;
+    return reduce_entry(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, b, out_dev, nullptr, 0.0f,
+                        hip_stream);
+}
+
+extern "C" int dq_unpack_dequant_reduce_update(const dq_plan_t* plan, const uint8_t* packed_dev,
+                                               int64_t packed_worker_stride_bytes, int M,
+                                               const float* norms_dev, int b, float eta, float* x_dev,
+                                               float* ghat_dev, void* hip_stream)
+{
+    if (!x_dev) return DQ_ERR_INVALID_ARG;
+    return reduce_entry(plan, packed_dev, packed_worker_stride_bytes, M, norms_dev, b, ghat_dev, x_dev, eta,
+                        hip_stream);
 }

@@ -1,0 +1,86 @@
+"""Algorithm 1 of the paper (DQ-SGD in distributed learning) as a thin loop around the library.
+
+Every numerical step of the hot path runs in the HIP kernels / C host code behind ``include/dq.h``:
+``dq_norm`` (worker norms), ``dq_select_bits`` (Eq. (17)), ``dq_quantize_pack`` (Eq. (5)-(6)),
+``dq_unpack_dequant_reduce_update`` (server average and x <- x - eta*g_hat), ``dq_alpha_est``
+(Eq. (24)), ``dq_comm_cost_bits`` (Eq. (7)).  This module only sequences them the way Algorithm 1
+does; the caller supplies the gradients (the training task is not part of this library).
+
+Protocol (Algorithm 1 with the choices the paper leaves open):
+  * lagged=True (the paper's): b_0 is an input; after iteration t the server computes b_{t+1}
+    from iteration t's norms with index t+1, and only when (t+1) % tau == 0 (the paper updates the
+    bit-width every tau iterations, tau = 100 in its experiments); otherwise b_{t+1} = b_t.
+  * lagged=False: b_t is computed from iteration t's own norms before quantizing (needs the norms
+    on the host before the quantize pass).
+  * alpha: a number, or "estimate" to use Eq. (24) with the caller's loss at the update points.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, List, Optional, Union
+
+import torch
+
+from . import binding as _b
+
+
+@dataclass
+class DQSGDResult:
+    x: "torch.Tensor"                      # x_T, padded layout
+    bits: List[int] = field(default_factory=list)       # b_t used at every iteration
+    gbar: List[float] = field(default_factory=list)     # G-bar_t
+    cost_bits: int = 0                                   # f_Q of Eq. (7), summed over iterations
+    alphas: List[float] = field(default_factory=list)   # alpha used at each bit update
+
+
+def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor", "torch.Tensor"], None],
+        M: int, T: int, eta: float, eps_hat_q: float, alpha: Union[float, str], b0: int,
+        b_min: int = 1, b_max: int = 8, tau: int = 1, lagged: bool = True, seed: int = 0,
+        loss_fn: Optional[Callable[["torch.Tensor"], float]] = None, B_pre: int = 32,
+        on_step: Optional[Callable] = None) -> DQSGDResult:
+    """grad_fn(t, x, grads_out) fills grads_out[M][D'] (float32, CUDA, padded layout) with the M
+    workers' stochastic gradients at x.  on_step(t, b_t, grads, norms_host, packed) is called after
+    the quantize pass of every iteration (tests use it to feed the same bytes to the oracle)."""
+    dp, n_seg = plan.padded_elems, plan.n_seg
+    dev = x0.device
+    x = x0.clone()
+    grads = torch.zeros((M, dp), dtype=torch.float32, device=dev)
+    norms = torch.empty((M, n_seg), dtype=torch.float32, device=dev)
+    norms_host = torch.empty((M, n_seg), dtype=torch.float32).pin_memory()
+    ws = torch.empty(plan.workspace_bytes(M), dtype=torch.uint8, device=dev)
+    packed = torch.zeros((M, plan.packed_bytes(b_max)), dtype=torch.uint8, device=dev)
+    d_true = int(plan.seg_len.sum())
+    res = DQSGDResult(x=x)
+    estimate = alpha == "estimate"
+    if estimate and (loss_fn is None or not lagged):
+        raise ValueError('alpha="estimate" needs loss_fn and the lagged protocol')
+    F0 = loss_fn(x) if estimate else None
+    cur_alpha = 1.0 if estimate else float(alpha)
+    b = int(b0)
+
+    for t in range(T):
+        grad_fn(t, x, grads)
+        _b.norm(plan, grads, norms, ws)
+        norms_host.copy_(norms, non_blocking=True)
+        if not lagged:
+            torch.cuda.current_stream().synchronize()
+            b, gb = _b.select_bits(norms_host.numpy(), t, T, eps_hat_q, cur_alpha, b_min, b_max)
+        pk = packed[:, :plan.packed_bytes(b)]
+        _b.quantize_pack(plan, grads, norms, b, seed, t, pk)
+        if on_step is not None:
+            torch.cuda.current_stream().synchronize()
+            on_step(t, b, grads, norms_host.numpy(), pk)
+        _b.unpack_dequant_reduce_update(plan, pk, norms, b, eta, x)
+        res.bits.append(b)
+        res.cost_bits += _b.comm_cost_bits(M, d_true, b, n_seg, B_pre)
+        if lagged:
+            torch.cuda.current_stream().synchronize()
+            gb = _b.select_bits(norms_host.numpy(), t, T, eps_hat_q, 1.0, b_min, b_max)[1]
+            if t + 1 < T and (t + 1) % tau == 0:
+                if estimate:
+                    cur_alpha = min(1.0, _b.alpha_est(loss_fn(x), F0, t + 1))
+                    res.alphas.append(cur_alpha)
+                b, _ = _b.select_bits(norms_host.numpy(), t + 1, T, eps_hat_q, cur_alpha, b_min, b_max)
+        res.gbar.append(gb)
+    torch.cuda.synchronize()
+    return res

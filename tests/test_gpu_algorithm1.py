@@ -1,0 +1,158 @@
+"""Algorithm 1 end to end on the GPU (config 4: l2-regularised logistic regression, M = 8 workers,
+T = 500 iterations, dynamic bits) against the same loop run through the CPU oracle on the same
+gradient bytes: identical b_t and bitstreams at every iteration, final model and loss within
+tolerance, cost accounting equal, and convergence comparable to uncompressed SGD."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2107_14575_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SEED = wl.QUANT_SEED
+
+
+@pytest.fixture(scope="module")
+def dq():
+    import paper_2107_14575_amd as dq
+    dq.load_library()
+    assert torch.cuda.is_available()
+    return dq
+
+
+@pytest.fixture(scope="module")
+def problem():
+    n, d, M, batch, lam = 262144, 4096, 8, 256, 1e-3
+    X, y, _ = wl.logistic_regression_problem(n=n, d=d, device="cuda")
+    shard = n // M
+    Xs, ys = X.view(M, shard, d), y.view(M, shard)
+
+    def grad_fn(t, x, grads):
+        off = (t * batch) % shard
+        Xb, yb = Xs[:, off:off + batch], ys[:, off:off + batch]            # [M][batch][d]
+        p = torch.sigmoid(torch.matmul(Xb, x[:d]))                           # [M][batch]
+        grads[:, :d] = torch.matmul((p - yb).unsqueeze(1), Xb).squeeze(1) / batch + lam * x[:d]
+
+    def loss_fn(x):
+        z = X @ x[:d]
+        return float((torch.nn.functional.softplus(z) - y * z).mean() + 0.5 * lam * (x[:d] ** 2).sum())
+
+    return dict(n=n, d=d, M=M, batch=batch, lam=lam, grad_fn=grad_fn, loss_fn=loss_fn)
+
+
+def test_config4_trajectory_matches_the_oracle_loop(dq, oracle, problem):
+    from paper_2107_14575_amd import dqsgd
+    # eta = 0.25: with eta = 1 plain SGD itself ends above F(x_0) on this problem (batch 256, d = 4096)
+    d, M, T, eta, alpha, tau = problem["d"], problem["M"], 500, 0.25, 0.98, 20
+    plan = dq.Plan([d])
+    dp = plan.padded_elems
+    x0 = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    # eps_hat such that the rule reaches s* = 200 (b = 8) at the last iteration for G-bar ~ 2
+    g_probe = torch.zeros((M, dp), dtype=torch.float32, device="cuda")
+    problem["grad_fn"](0, x0, g_probe)
+    gbar0 = float(np.sqrt((oracle.norm([d], g_probe.cpu().numpy()).astype(np.float64) ** 2).mean()))
+    eps_hat = T * (gbar0 / 200.0) ** 2
+
+    x_or = np.zeros(dp, dtype=np.float32)
+    state = dict(b=2, cost=0, bits=[])
+
+    def on_step(t, b, grads, norms, packed):
+        g_host = np.ascontiguousarray(grads.cpu().numpy())
+        assert b == state["b"], f"b_t differs at t={t}"
+        want = oracle.quantize_pack([d], g_host, norms, b, SEED, t)
+        assert np.array_equal(packed.cpu().numpy(), want), f"bitstream differs at t={t}"
+        ghat = oracle.unpack_dequant_reduce([d], want, norms, b)
+        oracle.update(x_or, ghat, eta)
+        state["cost"] += oracle.comm_cost_bits(M, d, b, 1, 32)
+        state["bits"].append(b)
+        if t + 1 < T and (t + 1) % tau == 0:                 # the server's lagged, tau-periodic rule
+            state["b"], _ = oracle.select_bits(norms, t + 1, T, eps_hat, alpha, 2, 8)
+
+    res = dqsgd.run(plan, x0, problem["grad_fn"], M, T, eta, eps_hat, alpha, b0=2, b_min=2, b_max=8,
+                    tau=tau, lagged=True, seed=SEED, on_step=on_step)
+    assert res.bits == state["bits"] and res.cost_bits == state["cost"]
+    assert min(res.bits) == 2 and max(res.bits) == 8           # the schedule spans the whole range
+    assert all(x <= y for x, y in zip(res.bits, res.bits[1:]))  # constant G-bar: bits only grow with t
+
+    x_gpu = res.x.cpu().numpy()
+    tol = T * (2.0 ** -23 * np.abs(x_or).max() + eta * 1e-6 * 1.0)
+    assert np.abs(x_gpu - x_or).max() <= tol
+    F0 = problem["loss_fn"](x0)
+    F_gpu = problem["loss_fn"](res.x)
+    F_or = problem["loss_fn"](torch.from_numpy(x_or).cuda())
+    assert abs(F_gpu - F_or) <= 1e-5 * F0
+
+    # uncompressed SGD on the same batches: the quantized run keeps most of its progress
+    x = x0.clone()
+    g = torch.zeros((M, dp), dtype=torch.float32, device="cuda")
+    for t in range(T):
+        problem["grad_fn"](t, x, g)
+        x -= eta * g.mean(dim=0)
+    F_sgd = problem["loss_fn"](x)
+    assert F_gpu < F0 and F_sgd < F0
+    assert F_gpu - F_sgd <= 0.05 * (F0 - F_sgd), (F0, F_sgd, F_gpu)
+    # f_Q of Eq. (7) against sending fp32: the compressed run costs (mean b_t + 1)/32 of it
+    full = T * oracle.comm_cost_bits(M, d, 31, 0, 32)
+    assert abs(res.cost_bits / full - (np.mean(res.bits) + 1 + 32 / d) / 32) < 1e-9
+    plan.close()
+
+
+def test_same_step_rule_and_alpha_estimate(dq, oracle, problem):
+    """lagged=False computes b_t from iteration t's own norms (checked against the oracle's rule);
+    alpha='estimate' uses Eq. (24) with the caller's loss at every update."""
+    from paper_2107_14575_amd import dqsgd
+    d, M, T, eta = problem["d"], problem["M"], 60, 0.25
+    plan = dq.Plan([d])
+    x0 = torch.zeros(plan.padded_elems, dtype=torch.float32, device="cuda")
+    seen = []
+
+    def on_step(t, b, grads, norms, packed):
+        want_b, _ = oracle.select_bits(norms, t, T, 0.05, 0.95, 1, 8)
+        assert b == want_b
+        seen.append(b)
+
+    res = dqsgd.run(plan, x0, problem["grad_fn"], M, T, eta, 0.05, 0.95, b0=4, tau=1, lagged=False,
+                    seed=SEED, on_step=on_step)
+    assert res.bits == seen and len(set(seen)) > 1
+    res2 = dqsgd.run(plan, x0, problem["grad_fn"], M, T, eta, 0.05, "estimate", b0=4, tau=10, lagged=True,
+                     seed=SEED, loss_fn=problem["loss_fn"])
+    assert len(res2.alphas) == 5 and all(0.0 < a <= 1.0 for a in res2.alphas)
+    assert problem["loss_fn"](res2.x) < problem["loss_fn"](x0)
+    plan.close()
+
+
+def test_update_entry_point_matches_reduce_then_axpy(dq, oracle):
+    """dq_unpack_dequant_reduce_update against the oracle's average followed by its update, every
+    width, ragged layout; pads of x stay untouched; g_hat output optional."""
+    seg_len, grads = wl.ragged_mix(M=5)
+    plan = dq.Plan(seg_len)
+    dp = plan.padded_elems
+    g_dev = grads.cuda()
+    norms_dev = torch.empty((5, plan.n_seg), dtype=torch.float32, device="cuda")
+    ws = torch.empty(plan.workspace_bytes(5), dtype=torch.uint8, device="cuda")
+    dq.norm(plan, g_dev, norms_dev, ws)
+    norms = norms_dev.cpu().numpy()
+    rng = np.random.default_rng(1)
+    x_init = rng.standard_normal(dp).astype(np.float32)
+    valid = np.zeros(dp, dtype=bool)
+    starts, _ = wl.seg_starts(seg_len)
+    for st, n in zip(starts, seg_len):
+        valid[st:st + n] = True
+    for b in range(1, 9):
+        packed = torch.zeros((5, plan.packed_bytes(b)), dtype=torch.uint8, device="cuda")
+        dq.quantize_pack(plan, g_dev, norms_dev, b, SEED, b, packed)
+        x = torch.from_numpy(x_init.copy()).cuda()
+        ghat = torch.full((dp,), float("nan"), dtype=torch.float32, device="cuda")
+        eta = 0.37
+        dq.unpack_dequant_reduce_update(plan, packed, norms_dev, b, eta, x, ghat if b % 2 else None)
+        torch.cuda.synchronize()
+        want_g = oracle.unpack_dequant_reduce(seg_len, packed.cpu().numpy(), norms, b)
+        want_x = oracle.update(x_init.copy(), want_g, np.float32(eta))
+        got_x = x.cpu().numpy()
+        assert np.array_equal(got_x[~valid], x_init[~valid])
+        scale = np.abs(want_g).max()
+        assert np.all(np.abs(got_x - want_x) <= 2.0 ** -23 * np.abs(want_x) + eta * 1e-6 * scale)
+        if b % 2:
+            np.testing.assert_allclose(ghat.cpu().numpy(), want_g, rtol=0, atol=1e-6 * scale)
+    plan.close()

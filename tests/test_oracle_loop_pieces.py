@@ -1,0 +1,132 @@
+"""Pins for the pieces of Algorithm 1 around the quantizer: cost accounting (Eq. (7)) against the
+paper's Table 2, the alpha estimate (Eq. (24)), the model update."""
+import os
+
+import numpy as np
+import pytest
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "table2_comm_cost.txt")
+W, ITERS = 8, {"AG-News": 1000, "CIFAR-10": 6000, "CIFAR-100": 6000}
+RESNET18_CIFAR10_PARAMS = 11_173_962  # the 62 tensors of workloads.resnet18_cifar10_segments()
+
+
+def _table2():
+    rows = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, bits, *vals = line.split()
+            rows[name] = (int(bits), [float(v) for v in vals])
+    return rows
+
+
+def _impls(oracle):
+    impls = [oracle.comm_cost_bits]
+    import paper_2107_14575_amd as dq
+    if os.path.exists(dq.library_path()):
+        impls.append(dq.comm_cost_bits)
+    return impls
+
+
+def test_fixed_width_rows_of_table2_follow_eq7(oracle):
+    """Eq. (7) with a fixed width: cost = W*T*d*b_paper bits, so every fixed-width row is the SGD
+    row times b_paper/32 (to the table's two decimals; the B_pre bits of the norm are far below
+    that).  Uses the printed SGD cost to get d, so no model size has to be assumed."""
+    rows = _table2()
+    sgd = rows["VanillaSGD"][1]
+    for cost_fn in _impls(oracle):
+        for col, (task, T) in enumerate(ITERS.items()):
+            d = round(sgd[col] * 2 ** 30 * 8 / (W * T * 32))          # elements implied by the SGD row
+            assert abs(cost_fn(W, d, 31, 0, 32) * T / 8 / 2 ** 30 - sgd[col]) < 0.005
+            for name, (b_paper, vals) in rows.items():
+                if name == "VanillaSGD":
+                    continue
+                gib = cost_fn(W, d, b_paper - 1, 1, 32) * T / 8 / 2 ** 30
+                assert abs(gib - vals[col]) < 0.006, (name, task, gib, vals[col])
+
+
+def test_cifar10_sgd_row_is_resnet18_exactly(oracle):
+    """1998.06 'GB' = 11,173,962 parameters x 32 bits x 8 workers x 6000 iterations / 2^30 bytes:
+    the unit is GiB and the model is the 10-class ResNet-18 whose tensors the workloads use."""
+    for cost_fn in _impls(oracle):
+        gib = cost_fn(W, RESNET18_CIFAR10_PARAMS, 31, 0, 32) * 6000 / 8 / 2 ** 30
+        assert abs(gib - 1998.06) < 0.005
+    from paper_2107_14575_amd import workloads as wl
+    assert sum(wl.resnet18_cifar10_segments()) == RESNET18_CIFAR10_PARAMS
+
+
+def test_cost_counts_sign_bit_and_every_norm(oracle):
+    for cost_fn in _impls(oracle):
+        assert cost_fn(1, 128, 4, 1, 32) == 128 * 5 + 32
+        assert cost_fn(3, 1000, 1, 62, 64) == 3 * (1000 * 2 + 62 * 64)
+        with pytest.raises(Exception):
+            cost_fn(0, 10, 4, 1, 32)
+
+
+def test_alpha_est_inverts_a_geometric_loss(oracle):
+    """Eq. (24) recovers alpha when F(x_t) = alpha^t F(x_0) (the first term of Theorem 1)."""
+    impls = [oracle.alpha_est]
+    import paper_2107_14575_amd as dq
+    if os.path.exists(dq.library_path()):
+        impls.append(dq.alpha_est)
+    for fn in impls:
+        for alpha in (0.5, 0.9, 0.994, 0.999):
+            for t in (1, 7, 100, 5000):
+                if alpha ** t > 1e-250:
+                    assert abs(fn(3.7 * alpha ** t, 3.7, t) - alpha) < 1e-12
+        assert fn(2.0, 2.0, 5) == 1.0
+        with pytest.raises(Exception):
+            fn(1.0, 2.0, 0)
+        with pytest.raises(Exception):
+            fn(0.0, 2.0, 3)
+
+
+def test_update_is_a_gradient_step(oracle):
+    x = np.array([1.0, -2.0, 0.5, 0.0], dtype=np.float32)
+    g = np.array([0.5, 0.25, -1.0, 0.0], dtype=np.float32)
+    oracle.update(x, g, 2.0)                                   # powers of two: exact
+    assert np.array_equal(x, np.array([0.0, -2.5, 2.5, 0.0], dtype=np.float32))
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(1000).astype(np.float32)
+    g = rng.standard_normal(1000).astype(np.float32)
+    want = (x.astype(np.float64) - 0.1 * g.astype(np.float64))
+    got = oracle.update(x.copy(), g, np.float32(0.1))
+    assert np.all(np.abs(got - want) <= 1e-7 * (np.abs(want) + np.abs(g)))
+
+
+def test_one_step_of_the_loop_obeys_theorem3_isotropic_case(oracle):
+    """Theorem 3 with H = lambda*I (Eq. (22)): E[F(x_{t+1}) - F*] = beta (F(x_t) - F*) +
+    (lambda eta^2 / 2) Tr Sigma(x_t), beta = (1 - eta*lambda)^2, where for noiseless workers
+    Sigma is the quantization covariance of the average, Tr Sigma = (1/W^2) sum_i (N_i/s)^2 sum_j
+    p_j (1 - p_j) (Appendix A).  One step of quantize -> average -> update through the oracle,
+    averaged over many seeds, must reproduce it: pins the 1/W, the sign of the update and eta."""
+    from tests import pyref
+    rng = np.random.default_rng(3)
+    d, W, b, lam, eta = 64, 4, 3, 0.7, 0.9
+    s = (1 << b) - 1
+    x_star = rng.standard_normal(d).astype(np.float32)
+    x_t = (x_star + rng.standard_normal(d).astype(np.float32)).astype(np.float32)
+    g = (lam * (x_t.astype(np.float64) - x_star)).astype(np.float32)        # every worker's gradient
+    grads = np.zeros((W, 128), dtype=np.float32)
+    grads[:, :d] = g
+    norms = oracle.norm([d], grads)
+    N = float(norms[0, 0])
+    p = np.array([float(pyref.scaled_magnitude(v, norms[0, 0], b)[2]) for v in g])
+    tr_sigma = (N / s) ** 2 * np.sum(p * (1 - p)) / W                        # W equal workers: W/W^2
+    F = lambda x: 0.5 * lam * np.sum((x.astype(np.float64) - x_star) ** 2)
+    beta = (1 - eta * lam) ** 2
+    want = beta * F(x_t) + 0.5 * lam * eta ** 2 * tr_sigma
+    R = 6000
+    vals = np.empty(R)
+    for r in range(R):
+        packed = oracle.quantize_pack([d], grads, norms, b, 99, r)
+        ghat = oracle.unpack_dequant_reduce([d], packed, norms, b)
+        x = np.zeros(128, dtype=np.float32)
+        x[:d] = x_t
+        oracle.update(x, ghat, np.float32(eta))
+        vals[r] = F(x[:d])
+    se = vals.std() / np.sqrt(R)
+    assert abs(vals.mean() - want) <= 5 * se + 1e-6 * want
+    # and the quantization term is what separates it from the noiseless contraction
+    assert vals.mean() > beta * F(x_t) + 0.5 * 0.5 * lam * eta ** 2 * tr_sigma
