@@ -161,6 +161,62 @@ int dqo_select_bits(const float *norms /* [M][n_seg] */, int32_t M, int32_t n_se
 }
 
 /* ------------------------------------------------------------------------------------------- */
+/* The p = infinity choice of the norm in Eq. (5): N = max_j |g_j| per worker and segment.        */
+/* A NaN element never becomes the maximum (every comparison with it is false).                  */
+/* ------------------------------------------------------------------------------------------- */
+int dqo_norm_linf(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+                  int32_t M, float *norms /* [M][n_seg] */)
+{
+    if (!seg_len || !grads || !norms || n_seg < 1 || M < 1) return DQO_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < M; ++i) {
+        const float *g = grads + (int64_t)i * worker_stride;
+        int64_t start = 0;
+        for (int32_t l = 0; l < n_seg; ++l) {
+            float m = 0.0f;
+            for (int64_t j = 0; j < seg_len[l]; ++j) {
+                float a = fabsf(g[start + j]);
+                if (a > m) m = a;
+            }
+            norms[(int64_t)i * n_seg + l] = m;
+            start += padded_len(seg_len[l]);
+        }
+    }
+    return DQO_OK;
+}
+
+/* The bit rule, Eq. (17), for p = infinity.  A worker's whole-gradient norm is the largest of    */
+/* its segment norms, so G2 = (1/M) sum_i max_l N_{i,l}^2; with one scale per segment the         */
+/* variance bound of Lemma 1 is sum_l d_l N_l^2 / (4 s^2) <= d max_l N_l^2 / (4 s^2), so the      */
+/* constraint of Eq. (16) still holds with this G-bar.  The rest is as for p = 2.                 */
+int dqo_select_bits_linf(const float *norms /* [M][n_seg] */, int32_t M, int32_t n_seg, int64_t t,
+                         int64_t T, double eps_hat_q, double alpha, int b_min, int b_max,
+                         int *b_out, double *gbar_out)
+{
+    if (!norms || !b_out || M < 1 || n_seg < 1 || T < 1 || t < 0 || t >= T) return DQO_ERR_INVALID_ARG;
+    if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQO_ERR_INVALID_ARG;
+    if (b_min < 1 || b_max > 8 || b_min > b_max) return DQO_ERR_INVALID_ARG;
+    double sum = 0.0;
+    for (int32_t i = 0; i < M; ++i) {
+        double top = 0.0;
+        for (int32_t l = 0; l < n_seg; ++l) {
+            double n = (double)norms[(int64_t)i * n_seg + l];
+            if (n > top) top = n;
+        }
+        sum += top * top;
+    }
+    double gbar = sqrt(sum / (double)M);
+    double s_star = sqrt((double)T / eps_hat_q) * pow(alpha, (double)(T - 1 - t) / 2.0) * gbar;
+    int b = b_max;
+    for (int cand = b_min; cand <= b_max; ++cand) {
+        double levels = (double)((1 << cand) - 1);
+        if (levels >= s_star) { b = cand; break; }
+    }
+    *b_out = b;
+    if (gbar_out) *gbar_out = gbar;
+    return DQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
 /* O3: sign and stochastic level of every element (Eq. (5)-(6)).                                  */
 /* sign[i][P], level[i][P] are one byte per padded element; pads get 0/0.                         */
 /* ------------------------------------------------------------------------------------------- */

@@ -50,6 +50,10 @@ def lib():
         L.dqo_packed_bytes.argtypes = [i64p, C.c_int32, C.c_int]
         L.dqo_packed_bytes.restype = C.c_int64
         L.dqo_norm.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, f32p]
+        L.dqo_norm_linf.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, f32p]
+        L.dqo_select_bits_linf.argtypes = [f32p, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_double,
+                                           C.c_double, C.c_int, C.c_int, C.POINTER(C.c_int),
+                                           C.POINTER(C.c_double)]
         L.dqo_select_bits.argtypes = [f32p, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                       C.c_double, C.c_double, C.c_int, C.c_int,
                                       C.POINTER(C.c_int), C.POINTER(C.c_double)]
@@ -152,6 +156,27 @@ def select_bits(norms, t, T, eps_hat_q, alpha, b_min, b_max):
     gbar = C.c_double(0.0)
     _check(lib().dqo_select_bits(_p(n, C.c_float), n.shape[0], n.shape[1], t, T, eps_hat_q,
                                  alpha, b_min, b_max, C.byref(b), C.byref(gbar)), "select_bits")
+    return int(b.value), float(gbar.value)
+
+
+def norm_linf(seg_len, grads):
+    s = _segs(seg_len)
+    g = _grads2d(grads, padded_elems(s))
+    M = g.shape[0]
+    out = np.zeros((M, s.size), dtype=np.float32)
+    _check(lib().dqo_norm_linf(_p(s, C.c_int64), s.size, _p(g, C.c_float), g.shape[1], M,
+                               _p(out, C.c_float)), "norm_linf")
+    return out
+
+
+def select_bits_linf(norms, t, T, eps_hat_q, alpha, b_min, b_max):
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32))
+    if n.ndim != 2:
+        raise ValueError("norms must be [M][n_seg]")
+    b = C.c_int(0)
+    gbar = C.c_double(0.0)
+    _check(lib().dqo_select_bits_linf(_p(n, C.c_float), n.shape[0], n.shape[1], t, T, eps_hat_q,
+                                      alpha, b_min, b_max, C.byref(b), C.byref(gbar)), "select_bits_linf")
     return int(b.value), float(gbar.value)
 
 
