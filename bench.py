@@ -182,6 +182,18 @@ def main() -> None:
     t_upd = u0.elapsed_time(u1) / 5
     del x_model
 
+    # the max-norm variant of the norm pass (p = infinity in Eq. (5)), timed on its own
+    norms_inf = torch.empty_like(norms_dev)
+    dq.norm_linf(plan, grads, norms_inf, ws)
+    torch.cuda.synchronize()
+    u0, u1 = ev(), ev()
+    u0.record()
+    for _ in range(5):
+        dq.norm_linf(plan, grads, norms_inf, ws)
+    u1.record()
+    torch.cuda.synchronize()
+    t_ninf = u0.elapsed_time(u1) / 5
+
     if args.copy_probe:
         probe = torch.empty_like(out)
         probe.copy_(out)
@@ -240,6 +252,7 @@ def main() -> None:
             "dq_unpack_dequant_reduce": dict(rl(r_bytes, t_red), fp32_in_GBps=round(in_bytes / t_red / 1e6, 1)),
             "dq_norm": rl(n_bytes, t_norm),
             "dq_unpack_dequant_reduce_update": rl(dp * (M * (b_last + 1) / 8 + 8), t_upd),
+            "dq_norm_linf": rl(n_bytes, t_ninf),
         },
     }
     # what a kernel with no arithmetic reaches for the same read/write mixes (large workloads only:

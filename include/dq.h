@@ -79,6 +79,12 @@ int dq_plan_has_device(const dq_plan_t* plan);                     /* 1 if the t
 int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
             float* norms_dev, void* workspace_dev, void* hip_stream);
 
+/* The same with p = infinity in Eq. (5): N[i][l] = max_j |g_j| over tensor l of worker i (0 for
+ * an empty tensor; NaN elements are skipped).  With it no ratio |g_j|/N exceeds 1 and b = 1 is
+ * the ternary scheme of the related work.  Arguments as dq_norm; the result is exact. */
+int dq_norm_linf(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
+                 float* norms_dev, void* workspace_dev, void* hip_stream);
+
 /* The bit rule, Eq. (17), in level-bit convention.  Pure host code, no GPU work.
  *   Gbar^2 = (1/M) sum_i sum_l N[i][l]^2        (mean square of the workers' gradient norms, Lemma 1)
  *   s*     = sqrt(T/eps_hat_q) * alpha^((T-1-t)/2) * Gbar
@@ -89,6 +95,14 @@ int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride
 int dq_select_bits(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
                    double eps_hat_q, double alpha, int b_min, int b_max, int* b_out,
                    double* gbar_out);
+
+/* Eq. (17) for norms from dq_norm_linf: a worker's whole-gradient max norm is the largest of its
+ * tensor norms, so Gbar^2 = (1/M) sum_i max_l N[i][l]^2 (with one scale per tensor the variance
+ * bound of Lemma 1 is sum_l d_l N_l^2/(4 s^2) <= d max_l N_l^2/(4 s^2), so the constraint of
+ * Eq. (16) is kept).  Otherwise identical to dq_select_bits. */
+int dq_select_bits_linf(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
+                        double eps_hat_q, double alpha, int b_min, int b_max, int* b_out,
+                        double* gbar_out);
 
 /* EWU quantizer of Eq. (5)-(6) fused with the packing of the message whose size Eq. (7) counts.
  * For worker w = worker_base + i, element P of tensor l with norm N = norms_dev[i][l]:

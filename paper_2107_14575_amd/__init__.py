@@ -11,11 +11,14 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     norm,
+    norm_linf,
     probe_stream,
     quantize_pack,
     select_bits,
+    select_bits_linf,
     unpack_dequant_reduce,
 )
 
-__all__ = ["DQError", "alpha_est", "comm_cost_bits", "unpack_dequant_reduce_update", "Plan", "library_path", "load_library", "norm", "probe_stream", "quantize_pack",
-           "select_bits", "unpack_dequant_reduce"]
+__all__ = ["DQError", "Plan", "alpha_est", "comm_cost_bits", "library_path", "load_library", "norm", "norm_linf",
+           "probe_stream", "quantize_pack", "select_bits", "select_bits_linf", "unpack_dequant_reduce",
+           "unpack_dequant_reduce_update"]

@@ -18,7 +18,7 @@ MAX_WORKERS = 64
 EXPORTS = (
     "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems",
     "dq_plan_segment_start", "dq_packed_bytes", "dq_workspace_bytes", "dq_plan_has_device",
-    "dq_norm", "dq_select_bits", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
+    "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
     "dq_unpack_dequant_reduce_update", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
 )
 
@@ -65,9 +65,13 @@ def load_library():
     L.dq_plan_has_device.restype = C.c_int
     L.dq_norm.argtypes = [vp, vp, i64, C.c_int, vp, vp, vp]
     L.dq_norm.restype = C.c_int
+    L.dq_norm_linf.argtypes = [vp, vp, i64, C.c_int, vp, vp, vp]
+    L.dq_norm_linf.restype = C.c_int
     L.dq_select_bits.argtypes = [f32p, C.c_int, C.c_int, i64, i64, C.c_double, C.c_double,
                                  C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_double)]
     L.dq_select_bits.restype = C.c_int
+    L.dq_select_bits_linf.argtypes = L.dq_select_bits.argtypes
+    L.dq_select_bits_linf.restype = C.c_int
     L.dq_quantize_pack.argtypes = [vp, vp, i64, C.c_int, vp, C.c_int, C.c_uint64, C.c_uint32,
                                    C.c_uint32, vp, i64, vp]
     L.dq_quantize_pack.restype = C.c_int
@@ -159,17 +163,34 @@ def norm(plan: Plan, grads, norms_out, workspace, stream=None) -> None:
                                              _stream_handle(stream)))
 
 
-def select_bits(norms_host, t: int, T: int, eps_hat_q: float, alpha: float, b_min: int, b_max: int):
-    """norms_host: host float32 array [M][n_seg] -> (b, Gbar)."""
+def norm_linf(plan: Plan, grads, norms_out, workspace, stream=None) -> None:
+    """As norm, with the max norm (p = infinity)."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    _check("dq_norm_linf", load_library().dq_norm_linf(plan.handle, grads.data_ptr(), stride, M,
+                                                       norms_out.data_ptr(), workspace.data_ptr(),
+                                                       _stream_handle(stream)))
+
+
+def _select_bits(name, norms_host, t, T, eps_hat_q, alpha, b_min, b_max):
     n = np.ascontiguousarray(np.asarray(norms_host, dtype=np.float32))
     if n.ndim != 2:
         raise ValueError("norms must be [M][n_seg]")
     b = C.c_int(0)
     gbar = C.c_double(0.0)
-    _check("dq_select_bits",
-           load_library().dq_select_bits(n.ctypes.data_as(C.POINTER(C.c_float)), n.shape[0], n.shape[1],
-                                         t, T, eps_hat_q, alpha, b_min, b_max, C.byref(b), C.byref(gbar)))
+    fn = getattr(load_library(), name)
+    _check(name, fn(n.ctypes.data_as(C.POINTER(C.c_float)), n.shape[0], n.shape[1],
+                    t, T, eps_hat_q, alpha, b_min, b_max, C.byref(b), C.byref(gbar)))
     return int(b.value), float(gbar.value)
+
+
+def select_bits(norms_host, t: int, T: int, eps_hat_q: float, alpha: float, b_min: int, b_max: int):
+    """norms_host: host float32 array [M][n_seg] -> (b, Gbar)."""
+    return _select_bits("dq_select_bits", norms_host, t, T, eps_hat_q, alpha, b_min, b_max)
+
+
+def select_bits_linf(norms_host, t: int, T: int, eps_hat_q: float, alpha: float, b_min: int, b_max: int):
+    """select_bits for norms from norm_linf."""
+    return _select_bits("dq_select_bits_linf", norms_host, t, T, eps_hat_q, alpha, b_min, b_max)
 
 
 def quantize_pack(plan: Plan, grads, norms, b: int, seed: int, step: int, packed_out,

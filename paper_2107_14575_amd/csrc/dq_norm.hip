@@ -1,10 +1,13 @@
-// dq_norm: l2 norm per (worker, segment) -- the ||g|| of Eq. (5) with p = 2.
+// dq_norm / dq_norm_linf: l2 or max norm per (worker, segment) -- the ||g||_p of Eq. (5) with
+// p = 2 or p = infinity.
 //
 // Two passes, both deterministic.  Pass 1: one workgroup per (norm item, worker) sums the squares
 // of up to 4096 valid elements in binary64 (squares of binary32 values are exact there): per-lane
 // partial, wavefront shuffle tree, then the four wave sums through LDS in wave order.  Pass 2: one
 // workgroup per (segment, worker) adds that segment's item partials in a fixed order and takes
 // the square root.  HBM traffic: 4 bytes read per element, plus 8 bytes per 4096 elements.
+// The max norm takes the same two passes with binary32 maxima in place of the binary64 sums (a
+// maximum does not depend on the order; a NaN element never wins a comparison).
 #include "dq_internal.h"
 
 namespace {
@@ -16,10 +19,27 @@ __device__ __forceinline__ double wave_sum(double v)
     return v; // lane 0 holds the sum
 }
 
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float o = __shfl_down(v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v; // lane 0 holds the maximum
+}
+
+__device__ __forceinline__ float larger(float m, float x)
+{
+    const float a = fabsf(x);
+    return a > m ? a : m;
+}
+
+template <bool LINF>
 __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ grads,
                                                       int64_t worker_stride,
                                                       const dq_norm_item* __restrict__ items,
-                                                      int32_t n_items, double* __restrict__ partial)
+                                                      int32_t n_items, void* __restrict__ partial_out)
 {
     __shared__ double wave_part[4];
     const int item_id = blockIdx.x;
@@ -36,6 +56,29 @@ __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ 
         // item's valid range never leaves the worker's buffer
         v[k] = e < item.count ? *reinterpret_cast<const float4*>(g + e) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    if constexpr (LINF) {
+        float m = 0.f;
+#pragma unroll
+        for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
+            const int e = (k * 256 + tid) * 4;
+            m = larger(m, e + 0 < item.count ? v[k].x : 0.f);
+            m = larger(m, e + 1 < item.count ? v[k].y : 0.f);
+            m = larger(m, e + 2 < item.count ? v[k].z : 0.f);
+            m = larger(m, e + 3 < item.count ? v[k].w : 0.f);
+        }
+        m = wave_max(m);
+        float* wave_m = reinterpret_cast<float*>(wave_part);
+        if ((tid & 63) == 0) wave_m[tid >> 6] = m;
+        __syncthreads();
+        if (tid == 0) {
+            float top = wave_m[0];
+#pragma unroll
+            for (int k = 1; k < 4; ++k) top = wave_m[k] > top ? wave_m[k] : top;
+            static_cast<float*>(partial_out)[static_cast<int64_t>(w) * n_items + item_id] = top;
+        }
+        return;
+    }
+    double* partial = static_cast<double*>(partial_out);
     double acc = 0.0;
 #pragma unroll
     for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
@@ -91,10 +134,58 @@ __global__ __launch_bounds__(FINISH_THREADS) void k_norm_finish(const double* __
     }
 }
 
+__global__ __launch_bounds__(FINISH_THREADS) void k_norm_linf_finish(const float* __restrict__ partial, int32_t n_items,
+                                                                     const int32_t* __restrict__ seg_item_begin,
+                                                                     int32_t n_seg, float* __restrict__ norms)
+{
+    __shared__ float wave_m[FINISH_THREADS / 64];
+    const int seg = blockIdx.x;
+    const int w = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int begin = seg_item_begin[seg], end = seg_item_begin[seg + 1];
+    const float* p = partial + static_cast<int64_t>(w) * n_items;
+    float m = 0.f;
+    int i = begin + tid;
+    for (; i + 7 * FINISH_THREADS < end; i += 8 * FINISH_THREADS) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = p[i + k * FINISH_THREADS];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) m = v[k] > m ? v[k] : m;
+    }
+    for (; i < end; i += FINISH_THREADS) m = p[i] > m ? p[i] : m;
+    m = wave_max(m);
+    if ((tid & 63) == 0) wave_m[tid >> 6] = m;
+    __syncthreads();
+    if (tid == 0) {
+        float top = 0.f;
+#pragma unroll
+        for (int k = 0; k < FINISH_THREADS / 64; ++k) top = wave_m[k] > top ? wave_m[k] : top;
+        norms[static_cast<int64_t>(w) * n_seg + seg] = top;
+    }
+}
+
+int norm_entry(bool linf, const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
+               float* norms_dev, void* workspace_dev, void* hip_stream);
+
 } // namespace
 
 extern "C" int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
                        int M, float* norms_dev, void* workspace_dev, void* hip_stream)
+{
+    return norm_entry(false, plan, grads_dev, worker_stride_elems, M, norms_dev, workspace_dev, hip_stream);
+}
+
+extern "C" int dq_norm_linf(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                            int M, float* norms_dev, void* workspace_dev, void* hip_stream)
+{
+    return norm_entry(true, plan, grads_dev, worker_stride_elems, M, norms_dev, workspace_dev, hip_stream);
+}
+
+namespace {
+
+int norm_entry(bool linf, const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
+               float* norms_dev, void* workspace_dev, void* hip_stream)
 {
     if (!plan || !grads_dev || !norms_dev || !workspace_dev) return DQ_ERR_INVALID_ARG;
     if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
@@ -104,12 +195,23 @@ extern "C" int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t wo
     const int rc = dq_plan_check_device(plan);
     if (rc != DQ_OK) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    double* partial = static_cast<double*>(workspace_dev);
-    if (plan->n_items > 0) {
-        hipLaunchKernelGGL(k_norm_partial, dim3(plan->n_items, M), dim3(256), 0, stream, grads_dev,
-                           worker_stride_elems, plan->d_items, plan->n_items, partial);
+    const dim3 grid_items(plan->n_items, M), grid_segs(plan->n_seg, M);
+    if (linf) {
+        if (plan->n_items > 0)
+            hipLaunchKernelGGL(k_norm_partial<true>, grid_items, dim3(256), 0, stream, grads_dev,
+                               worker_stride_elems, plan->d_items, plan->n_items, workspace_dev);
+        hipLaunchKernelGGL(k_norm_linf_finish, grid_segs, dim3(FINISH_THREADS), 0, stream,
+                           static_cast<const float*>(workspace_dev), plan->n_items, plan->d_seg_item_begin,
+                           plan->n_seg, norms_dev);
+    } else {
+        if (plan->n_items > 0)
+            hipLaunchKernelGGL(k_norm_partial<false>, grid_items, dim3(256), 0, stream, grads_dev,
+                               worker_stride_elems, plan->d_items, plan->n_items, workspace_dev);
+        hipLaunchKernelGGL(k_norm_finish, grid_segs, dim3(FINISH_THREADS), 0, stream,
+                           static_cast<const double*>(workspace_dev), plan->n_items, plan->d_seg_item_begin,
+                           plan->n_seg, norms_dev);
     }
-    hipLaunchKernelGGL(k_norm_finish, dim3(plan->n_seg, M), dim3(FINISH_THREADS), 0, stream, partial, plan->n_items,
-                       plan->d_seg_item_begin, plan->n_seg, norms_dev);
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
 }
+
+} // namespace

@@ -184,19 +184,27 @@ int dq_plan_check_device(const dq_plan* plan)
 }
 
 // Eq. (17) with b = b_paper - 1, rounded up: the smallest b whose 2^b - 1 levels reach s*.
-extern "C" int dq_select_bits(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
-                              double eps_hat_q, double alpha, int b_min, int b_max, int* b_out,
-                              double* gbar_out)
+// G-bar^2 is the mean over workers of the squared whole-gradient norm: the sum of the squared
+// segment norms for p = 2, the square of the largest segment norm for p = infinity.
+static int select_bits(bool linf, const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
+                       double eps_hat_q, double alpha, int b_min, int b_max, int* b_out, double* gbar_out)
 {
     if (!norms_host || !b_out || M < 1 || n_seg < 1) return DQ_ERR_INVALID_ARG;
     if (T < 1 || t < 0 || t >= T) return DQ_ERR_INVALID_ARG;
     if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQ_ERR_INVALID_ARG;
     if (b_min < 1 || b_max > 8 || b_min > b_max) return DQ_ERR_INVALID_ARG;
     double sum_sq = 0.0;
-    const int64_t count = static_cast<int64_t>(M) * n_seg;
-    for (int64_t k = 0; k < count; ++k) {
-        const double n = static_cast<double>(norms_host[k]);
-        sum_sq += n * n;
+    for (int i = 0; i < M; ++i) {
+        const float* row = norms_host + static_cast<int64_t>(i) * n_seg;
+        double worker_sq = 0.0;
+        for (int l = 0; l < n_seg; ++l) {
+            const double sq = static_cast<double>(row[l]) * static_cast<double>(row[l]);
+            if (linf)
+                worker_sq = sq > worker_sq ? sq : worker_sq;
+            else
+                worker_sq += sq;
+        }
+        sum_sq += worker_sq;
     }
     const double gbar = sqrt(sum_sq / static_cast<double>(M));
     const double weight = pow(alpha, static_cast<double>(T - 1 - t) / 2.0);
@@ -211,6 +219,20 @@ extern "C" int dq_select_bits(const float* norms_host, int M, int n_seg, int64_t
     *b_out = b;
     if (gbar_out) *gbar_out = gbar;
     return DQ_OK;
+}
+
+extern "C" int dq_select_bits(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
+                              double eps_hat_q, double alpha, int b_min, int b_max, int* b_out,
+                              double* gbar_out)
+{
+    return select_bits(false, norms_host, M, n_seg, t, T, eps_hat_q, alpha, b_min, b_max, b_out, gbar_out);
+}
+
+extern "C" int dq_select_bits_linf(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
+                                   double eps_hat_q, double alpha, int b_min, int b_max, int* b_out,
+                                   double* gbar_out)
+{
+    return select_bits(true, norms_host, M, n_seg, t, T, eps_hat_q, alpha, b_min, b_max, b_out, gbar_out);
 }
 
 // Eq. (24): alpha_est = (F(x_t) / F(x_0))^(1/t).

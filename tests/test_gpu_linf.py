@@ -1,0 +1,79 @@
+"""GPU parity for the max-norm variant (p = infinity in Eq. (5)): dq_norm_linf bit for bit against
+the oracle, then the unchanged quantize+pack and reduce passes fed with those norms."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2107_14575_amd import workloads as wl
+from tests.test_gpu_parity import SEED, _one_step, dq, gpu_norm  # noqa: F401  (dq is a fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("b", [1, 2, 4, 7, 8])
+def test_ragged_layout(dq, oracle, b):
+    seg_len, grads = wl.ragged_mix(M=3)
+    _one_step(dq, oracle, seg_len, grads, b, step=20 + b, worker_base=2, linf=True)
+
+
+@pytest.mark.parametrize("D", [1, 127, 4096, 4097, 4096 * 1500 + 77, 4096 * 8200 + 77])
+def test_item_boundaries(dq, oracle, D):
+    """one item, a ragged item, more items than the finishing workgroup has lanes, and more than
+    one pass of its eight-deep loop"""
+    if D > 4097:
+        seg_len, grads = wl.flat_student_t(D=D, M=1, config=21)
+    else:
+        seg_len, grads = wl.flat_gaussian(D=D, M=2, config=21)
+    _one_step(dq, oracle, seg_len, grads, 3, step=1, linf=True)
+
+
+def test_transformer_layout_heavy_tails(dq, oracle):
+    seg_len, grads = wl.transformer_like(M=2)
+    _one_step(dq, oracle, seg_len, grads, 2, step=4, linf=True)
+
+
+def test_many_tiny_tensors_and_poisoned_pads(dq, oracle):
+    rng = np.random.default_rng(5)
+    seg_len = [int(x) for x in rng.choice([0, 1, 2, 64, 128, 129, 300], size=300)]
+    starts, dp = wl.seg_starts(seg_len)
+    g = torch.full((3, dp), float("inf"), dtype=torch.float32)     # pads must not reach the maximum
+    gen = torch.Generator().manual_seed(34)
+    for st, n in zip(starts, seg_len):
+        g[:, st:st + n] = torch.randn((3, n), generator=gen) * 1e-2
+    _one_step(dq, oracle, seg_len, g, 1, step=3, linf=True)
+
+
+def test_where_the_maximum_sits_and_special_values(dq, oracle):
+    """the maximum in every lane position of an item, negative, subnormal, all-zero, and a NaN
+    element next to it (skipped by the comparison)"""
+    seg_len = [4096 * 3 + 5, 9, 4096]
+    starts, dp = wl.seg_starts(seg_len)
+    plan = dq.Plan(seg_len)
+    gen = torch.Generator().manual_seed(35)
+    base = torch.randn((1, dp), generator=gen) * 1e-3
+    positions = [0, 1, 2, 3, 63, 64, 255 * 4 + 3, 1024, 4095, 4096, 4096 * 3 + 4]
+    g = base.repeat(len(positions) + 3, 1)
+    for i, pos in enumerate(positions):
+        g[i, pos] = -7.5 if i % 2 else 7.25
+        g[i, starts[1] + (i % 9)] = float("nan")
+    k = len(positions)
+    g[k] = 0.0
+    g[k + 1] = 0.0
+    g[k + 1, 5] = 1e-42
+    g[k + 1, starts[2] + 4095] = -3e-45
+    g[k + 2, starts[2]:starts[2] + 4096] = float("nan")             # nothing but NaN: the norm is 0
+    got = gpu_norm(dq, plan, g.cuda(), linf=True).cpu().numpy()
+    want = oracle.norm_linf(seg_len, g.numpy())
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert got[0, 0] == 7.25 and got[1, 0] == 7.5 and got[k, 0] == 0 and got[k + 2, 2] == 0
+    assert got[k + 1, 0] == np.float32(1e-42) and got[k + 1, 2] == np.float32(3e-45)
+    plan.close()
+
+
+def test_bit_rule_follows_the_gpu_norms(dq, oracle):
+    seg_len, grads = wl.resnet18_like(M=4)
+    plan = dq.Plan(seg_len)
+    norms = gpu_norm(dq, plan, grads.cuda(), linf=True).cpu().numpy()
+    for t in (0, 50, 99):
+        assert dq.select_bits_linf(norms, t, 100, 1e-3, 0.97, 1, 8) == oracle.select_bits_linf(norms, t, 100, 1e-3, 0.97, 1, 8)
+    plan.close()

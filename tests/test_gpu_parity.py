@@ -28,11 +28,11 @@ def _valid_mask(seg_len):
     return valid
 
 
-def gpu_norm(dq, plan, grads_dev):
+def gpu_norm(dq, plan, grads_dev, linf=False):
     M = grads_dev.shape[0]
-    norms = torch.empty((M, plan.n_seg), dtype=torch.float32, device="cuda")
+    norms = torch.full((M, plan.n_seg), float("nan"), dtype=torch.float32, device="cuda")
     ws = torch.empty(plan.workspace_bytes(M), dtype=torch.uint8, device="cuda")
-    dq.norm(plan, grads_dev, norms, ws)
+    (dq.norm_linf if linf else dq.norm)(plan, grads_dev, norms, ws)
     torch.cuda.synchronize()
     return norms
 
@@ -70,7 +70,7 @@ def _check_average(got, want, sign, level, norms, seg_len, b):
     assert np.array_equal(got[~valid].view(np.uint32), np.zeros((~valid).sum(), dtype=np.uint32))
 
 
-def _one_step(dq, oracle, seg_len, grads, b, step, worker_base=0, check_norm=True):
+def _one_step(dq, oracle, seg_len, grads, b, step, worker_base=0, check_norm=True, linf=False):
     """norm -> quantize+pack -> reduce on the GPU and in the oracle; the oracle is fed the GPU's
     norms for the later stages (the norm is an input of the quantizer, and may differ in the
     last place between two correct implementations)."""
@@ -78,9 +78,11 @@ def _one_step(dq, oracle, seg_len, grads, b, step, worker_base=0, check_norm=Tru
     assert plan.has_device
     g_host = np.ascontiguousarray(grads.numpy())
     g_dev = grads.cuda()
-    norms_dev = gpu_norm(dq, plan, g_dev)
+    norms_dev = gpu_norm(dq, plan, g_dev, linf)
     norms = norms_dev.cpu().numpy()
-    if check_norm:
+    if linf:
+        assert np.array_equal(norms.view(np.uint32), oracle.norm_linf(seg_len, g_host).view(np.uint32))
+    elif check_norm:
         want = oracle.norm(seg_len, g_host)
         assert np.all(np.abs(norms.astype(np.float64) - want.astype(np.float64)) <= np.spacing(want))
     packed_dev = gpu_quantize_pack(dq, plan, g_dev, norms_dev, b, step, worker_base, slack=48)

@@ -64,6 +64,10 @@ def test_select_bits_bit_exact_against_the_oracle(dq, oracle):
         want = oracle.select_bits(norms, t, T, eps, alpha, b_min, b_max)
         assert got[0] == want[0]
         assert abs(got[1] - want[1]) <= 1e-15 * want[1]
+        got = dq.select_bits_linf(norms, t, T, eps, alpha, b_min, b_max)
+        want = oracle.select_bits_linf(norms, t, T, eps, alpha, b_min, b_max)
+        assert got[0] == want[0]
+        assert abs(got[1] - want[1]) <= 1e-15 * want[1]
 
 
 def test_select_bits_rejects_bad_arguments(dq):
