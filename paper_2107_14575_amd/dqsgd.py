@@ -13,6 +13,8 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
   * lagged=False: b_t is computed from iteration t's own norms before quantizing (needs the norms
     on the host before the quantize pass).
   * alpha: a number, or "estimate" to use Eq. (24) with the caller's loss at the update points.
+  * p: 2 or "inf", the norm of Eq. (5) (the paper leaves p open): ``dq_norm``/``dq_select_bits`` or
+    ``dq_norm_linf``/``dq_select_bits_linf``.
 """
 from __future__ import annotations
 
@@ -37,10 +39,13 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         M: int, T: int, eta: float, eps_hat_q: float, alpha: Union[float, str], b0: int,
         b_min: int = 1, b_max: int = 8, tau: int = 1, lagged: bool = True, seed: int = 0,
         loss_fn: Optional[Callable[["torch.Tensor"], float]] = None, B_pre: int = 32,
-        on_step: Optional[Callable] = None) -> DQSGDResult:
+        on_step: Optional[Callable] = None, p: Union[int, str] = 2) -> DQSGDResult:
     """grad_fn(t, x, grads_out) fills grads_out[M][D'] (float32, CUDA, padded layout) with the M
     workers' stochastic gradients at x.  on_step(t, b_t, grads, norms_host, packed) is called after
     the quantize pass of every iteration (tests use it to feed the same bytes to the oracle)."""
+    if p not in (2, "inf"):
+        raise ValueError('p must be 2 or "inf"')
+    norm_fn, rule = (_b.norm, _b.select_bits) if p == 2 else (_b.norm_linf, _b.select_bits_linf)
     dp, n_seg = plan.padded_elems, plan.n_seg
     dev = x0.device
     x = x0.clone()
@@ -60,11 +65,11 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
 
     for t in range(T):
         grad_fn(t, x, grads)
-        _b.norm(plan, grads, norms, ws)
+        norm_fn(plan, grads, norms, ws)
         norms_host.copy_(norms, non_blocking=True)
         if not lagged:
             torch.cuda.current_stream().synchronize()
-            b, gb = _b.select_bits(norms_host.numpy(), t, T, eps_hat_q, cur_alpha, b_min, b_max)
+            b, gb = rule(norms_host.numpy(), t, T, eps_hat_q, cur_alpha, b_min, b_max)
         pk = packed[:, :plan.packed_bytes(b)]
         _b.quantize_pack(plan, grads, norms, b, seed, t, pk)
         if on_step is not None:
@@ -75,12 +80,12 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         res.cost_bits += _b.comm_cost_bits(M, d_true, b, n_seg, B_pre)
         if lagged:
             torch.cuda.current_stream().synchronize()
-            gb = _b.select_bits(norms_host.numpy(), t, T, eps_hat_q, 1.0, b_min, b_max)[1]
+            gb = rule(norms_host.numpy(), t, T, eps_hat_q, 1.0, b_min, b_max)[1]
             if t + 1 < T and (t + 1) % tau == 0:
                 if estimate:
                     cur_alpha = min(1.0, _b.alpha_est(loss_fn(x), F0, t + 1))
                     res.alphas.append(cur_alpha)
-                b, _ = _b.select_bits(norms_host.numpy(), t + 1, T, eps_hat_q, cur_alpha, b_min, b_max)
+                b, _ = rule(norms_host.numpy(), t + 1, T, eps_hat_q, cur_alpha, b_min, b_max)
         res.gbar.append(gb)
     torch.cuda.synchronize()
     return res
