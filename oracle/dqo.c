@@ -228,19 +228,28 @@ static int norm_is_usable(float N)
 /* Range form: only padded indices p_begin <= P < p_end (both multiples of 128) are computed.
  * grads points at element p_begin of worker 0 and worker i's slice starts worker_stride later;
  * sign/level are [M][p_end - p_begin].  The Philox counter uses the absolute index P. */
-int dqo_quantize_range(const int64_t *seg_len, int32_t n_seg, const float *grads,
-                       int64_t worker_stride, int32_t M, const float *norms /* [M][n_seg] */, int b,
-                       uint64_t seed, uint32_t step, uint32_t worker_base, int64_t p_begin,
-                       int64_t p_end, uint8_t *sign, uint8_t *level)
+static int widths_ok(const int32_t *b_seg, int32_t n_seg)
+{
+    if (!b_seg) return 0;
+    for (int32_t l = 0; l < n_seg; ++l)
+        if (b_seg[l] < 1 || b_seg[l] > 8) return 0;
+    return 1;
+}
+
+/* b_seg == NULL: every tensor uses b level bits; otherwise tensor l uses b_seg[l] (the
+ * per-tensor widths further down) and b is ignored. */
+static int quantize_range(const int64_t *seg_len, int32_t n_seg, const float *grads,
+                          int64_t worker_stride, int32_t M, const float *norms /* [M][n_seg] */, int b,
+                          const int32_t *b_seg, uint64_t seed, uint32_t step, uint32_t worker_base,
+                          int64_t p_begin, int64_t p_end, uint8_t *sign, uint8_t *level)
 {
     if (!seg_len || !grads || !norms || !sign || !level) return DQO_ERR_INVALID_ARG;
-    if (n_seg < 1 || M < 1 || b < 1 || b > 8) return DQO_ERR_INVALID_ARG;
+    if (n_seg < 1 || M < 1) return DQO_ERR_INVALID_ARG;
+    if (b_seg ? !widths_ok(b_seg, n_seg) : (b < 1 || b > 8)) return DQO_ERR_INVALID_ARG;
     int64_t dp = dqo_padded_elems(seg_len, n_seg);
     if (dp < 0 || p_begin < 0 || p_end > dp || p_begin > p_end) return DQO_ERR_INVALID_ARG;
     if (p_begin % DQO_GRANULE || p_end % DQO_GRANULE) return DQO_ERR_INVALID_ARG;
     const int64_t span = p_end - p_begin;
-    const uint32_t s_int = (1u << b) - 1u;
-    const float s = (float)s_int;
     const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
 
 #pragma omp parallel for schedule(static)
@@ -252,6 +261,7 @@ int dqo_quantize_range(const int64_t *seg_len, int32_t n_seg, const float *grads
         memset(lv, 0, (size_t)span);
         int64_t start = 0;
         for (int32_t l = 0; l < n_seg; ++l) {
+            const float s = (float)((1u << (b_seg ? b_seg[l] : b)) - 1u); /* quantization levels */
             const float N = norms[(int64_t)i * n_seg + l];
             const int usable = norm_is_usable(N);
             const float scale = usable ? s / N : 0.0f; /* one binary32 division per segment */
@@ -280,6 +290,15 @@ int dqo_quantize_range(const int64_t *seg_len, int32_t n_seg, const float *grads
         }
     }
     return DQO_OK;
+}
+
+int dqo_quantize_range(const int64_t *seg_len, int32_t n_seg, const float *grads,
+                       int64_t worker_stride, int32_t M, const float *norms /* [M][n_seg] */, int b,
+                       uint64_t seed, uint32_t step, uint32_t worker_base, int64_t p_begin,
+                       int64_t p_end, uint8_t *sign, uint8_t *level)
+{
+    return quantize_range(seg_len, n_seg, grads, worker_stride, M, norms, b, NULL, seed, step,
+                          worker_base, p_begin, p_end, sign, level);
 }
 
 int dqo_quantize(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
@@ -351,21 +370,22 @@ int dqo_unpack(const uint8_t *packed, int64_t dp, int b, uint8_t *sign, uint8_t 
 /* ------------------------------------------------------------------------------------------- */
 /* Range form: codes are [M][p_end - p_begin] for padded indices p_begin <= P < p_end (multiples
  * of 128); out has p_end - p_begin entries. */
-int dqo_dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign,
-                             const uint8_t *level, int32_t M, const float *norms /* [M][n_seg] */,
-                             int b, int64_t p_begin, int64_t p_end, float *out)
+static int dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign,
+                                const uint8_t *level, int32_t M, const float *norms /* [M][n_seg] */,
+                                int b, const int32_t *b_seg, int64_t p_begin, int64_t p_end, float *out)
 {
     if (!seg_len || !sign || !level || !norms || !out) return DQO_ERR_INVALID_ARG;
-    if (n_seg < 1 || M < 1 || b < 1 || b > 8) return DQO_ERR_INVALID_ARG;
+    if (n_seg < 1 || M < 1) return DQO_ERR_INVALID_ARG;
+    if (b_seg ? !widths_ok(b_seg, n_seg) : (b < 1 || b > 8)) return DQO_ERR_INVALID_ARG;
     int64_t dp = dqo_padded_elems(seg_len, n_seg);
     if (dp < 0 || p_begin < 0 || p_end > dp || p_begin > p_end) return DQO_ERR_INVALID_ARG;
     if (p_begin % DQO_GRANULE || p_end % DQO_GRANULE) return DQO_ERR_INVALID_ARG;
     const int64_t span = p_end - p_begin;
-    const float s = (float)((1u << b) - 1u);
     for (int64_t q = 0; q < span; ++q) out[q] = 0.0f;
     int64_t start = 0;
     for (int32_t l = 0; l < n_seg; ++l) {
         const int64_t len = seg_len[l];
+        const float s = (float)((1u << (b_seg ? b_seg[l] : b)) - 1u);
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < len; ++j) {
             const int64_t P = start + j;
@@ -384,6 +404,13 @@ int dqo_dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uint8_
         start += padded_len(len);
     }
     return DQO_OK;
+}
+
+int dqo_dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign,
+                             const uint8_t *level, int32_t M, const float *norms /* [M][n_seg] */,
+                             int b, int64_t p_begin, int64_t p_end, float *out)
+{
+    return dequant_reduce_range(seg_len, n_seg, sign, level, M, norms, b, NULL, p_begin, p_end, out);
 }
 
 int dqo_dequant_reduce(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign /* [M][D'] */,
@@ -434,6 +461,189 @@ int dqo_unpack_dequant_reduce(const int64_t *seg_len, int32_t n_seg, const uint8
         dqo_unpack(packed + (int64_t)i * packed_stride, dp, b, sign + (int64_t)i * dp,
                    level + (int64_t)i * dp);
     return dqo_dequant_reduce(seg_len, n_seg, sign, level, M, norms, b, out);
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* One bit-width per tensor.                                                                      */
+/*                                                                                                */
+/* The paper's problem (the program before Eq. (17), solved in its appendix "Proof of Eq. (17)")  */
+/* has one b_t per iteration.  With one scale and one level count s_l = 2^(b_l) - 1 per tensor,   */
+/* Lemma 1's bound on the quantization variance of an iteration becomes                           */
+/*     sum_l d_l Nbar_l^2 / (4 s_l^2),     Nbar_l^2 = (1/M) sum_i N_{i,l}^2,                      */
+/* in place of d Gbar^2/(4 s^2), so the constraint reads                                          */
+/*     sum_t alpha^(T-1-t) sum_l (d_l/d) Nbar_{t,l}^2 / s_{t,l}^2 = eps_hat                       */
+/* and the cost is sum_t sum_l d_l b_{t,l}.  The same Lagrangian steps (stationarity in b_{t,l},  */
+/* 2^(b-1) ~ s as in the appendix) give s_{t,l} proportional to alpha^((T-1-t)/2) Nbar_{t,l}      */
+/* -- d_l cancels -- and the constraint fixes the factor at sqrt(T/eps_hat):                      */
+/*     s*_{t,l} = sqrt(T/eps_hat) * alpha^((T-1-t)/2) * Nbar_{t,l},                               */
+/* Eq. (17) with the tensor's own root-mean-square norm in place of Gbar_t.  Integer rounding and */
+/* clamping as for the single width; an all-zero tensor gets b_min.                               */
+/* ------------------------------------------------------------------------------------------- */
+int dqo_select_bits_per_tensor(const float *norms /* [M][n_seg] */, int32_t M, int32_t n_seg,
+                               int64_t t, int64_t T, double eps_hat_q, double alpha, int b_min,
+                               int b_max, int32_t *b_out /* [n_seg] */,
+                               double *nbar_out /* [n_seg] or NULL */)
+{
+    if (!norms || !b_out || M < 1 || n_seg < 1 || T < 1 || t < 0 || t >= T) return DQO_ERR_INVALID_ARG;
+    if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQO_ERR_INVALID_ARG;
+    if (b_min < 1 || b_max > 8 || b_min > b_max) return DQO_ERR_INVALID_ARG;
+    const double factor = sqrt((double)T / eps_hat_q) * pow(alpha, (double)(T - 1 - t) / 2.0);
+    for (int32_t l = 0; l < n_seg; ++l) {
+        double sum = 0.0;
+        for (int32_t i = 0; i < M; ++i) {
+            double n = (double)norms[(int64_t)i * n_seg + l];
+            sum += n * n;
+        }
+        double nbar = sqrt(sum / (double)M);
+        double s_star = factor * nbar;
+        int b = b_max;
+        for (int cand = b_min; cand <= b_max; ++cand) {
+            double levels = (double)((1 << cand) - 1);
+            if (levels >= s_star) { b = cand; break; }
+        }
+        b_out[l] = b;
+        if (nbar_out) nbar_out[l] = nbar;
+    }
+    return DQO_OK;
+}
+
+/* message bytes with per-tensor widths: D'/8 sign bytes, then tensor l's pad_l * b_l / 8 level bytes */
+int64_t dqo_packed_bytes_v(const int64_t *seg_len, int32_t n_seg, const int32_t *b_seg)
+{
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0 || !widths_ok(b_seg, n_seg)) return -1;
+    int64_t bytes = dp / 8;
+    for (int32_t l = 0; l < n_seg; ++l) bytes += padded_len(seg_len[l]) * b_seg[l] / 8;
+    return bytes;
+}
+
+/* Codes with per-tensor widths: tensor l is quantized as by dqo_quantize with b = b_l (the      */
+/* element's random number does not depend on b).  Range form as dqo_quantize_range.              */
+int dqo_quantize_v_range(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+                         int32_t M, const float *norms, const int32_t *b_seg, uint64_t seed, uint32_t step,
+                         uint32_t worker_base, int64_t p_begin, int64_t p_end, uint8_t *sign, uint8_t *level)
+{
+    if (!b_seg) return DQO_ERR_INVALID_ARG;
+    return quantize_range(seg_len, n_seg, grads, worker_stride, M, norms, 0, b_seg, seed, step,
+                          worker_base, p_begin, p_end, sign, level);
+}
+
+int dqo_quantize_v(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+                   int32_t M, const float *norms, const int32_t *b_seg, uint64_t seed, uint32_t step,
+                   uint32_t worker_base, uint8_t *sign /* [M][D'] */, uint8_t *level /* [M][D'] */)
+{
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    return dqo_quantize_v_range(seg_len, n_seg, grads, worker_stride, M, norms, b_seg, seed, step,
+                                worker_base, 0, dp, sign, level);
+}
+
+/* The message with per-tensor widths.  Sign plane as before.  Level plane: the tensors' level   */
+/* fields follow one another, tensor l taking pad_l * b_l bits (a whole number of 16-byte pieces), */
+/* its element j at bits [j*b_l, j*b_l + b_l) of that stretch, least significant bit first.  With */
+/* all widths equal this is the layout of dqo_pack.                                               */
+int dqo_pack_v(const uint8_t *sign, const uint8_t *level, const int64_t *seg_len, int32_t n_seg,
+               const int32_t *b_seg, uint8_t *packed)
+{
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    int64_t bytes = dqo_packed_bytes_v(seg_len, n_seg, b_seg);
+    if (!sign || !level || !packed || dp < 0 || bytes < 0) return DQO_ERR_INVALID_ARG;
+    memset(packed, 0, (size_t)bytes);
+    uint8_t *level_plane = packed + dp / 8;
+    int64_t start = 0, bit0 = 0;
+    for (int32_t l = 0; l < n_seg; ++l) {
+        const int64_t pad = padded_len(seg_len[l]);
+        for (int64_t j = 0; j < pad; ++j) {
+            put_bits(packed, start + j, 1, sign[start + j]);
+            put_bits(level_plane, bit0 + j * b_seg[l], b_seg[l], level[start + j]);
+        }
+        start += pad;
+        bit0 += pad * b_seg[l];
+    }
+    return DQO_OK;
+}
+
+int dqo_unpack_v(const uint8_t *packed, const int64_t *seg_len, int32_t n_seg, const int32_t *b_seg,
+                 uint8_t *sign, uint8_t *level)
+{
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (!sign || !level || !packed || dp < 0 || !widths_ok(b_seg, n_seg)) return DQO_ERR_INVALID_ARG;
+    const uint8_t *level_plane = packed + dp / 8;
+    int64_t start = 0, bit0 = 0;
+    for (int32_t l = 0; l < n_seg; ++l) {
+        const int64_t pad = padded_len(seg_len[l]);
+        for (int64_t j = 0; j < pad; ++j) {
+            sign[start + j] = (uint8_t)get_bits(packed, start + j, 1);
+            level[start + j] = (uint8_t)get_bits(level_plane, bit0 + j * b_seg[l], b_seg[l]);
+        }
+        start += pad;
+        bit0 += pad * b_seg[l];
+    }
+    return DQO_OK;
+}
+
+/* Average with per-tensor widths: tensor l dequantizes with unit N_{i,l} / (2^(b_l) - 1).       */
+int dqo_dequant_reduce_v_range(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign, const uint8_t *level,
+                               int32_t M, const float *norms, const int32_t *b_seg, int64_t p_begin,
+                               int64_t p_end, float *out)
+{
+    if (!b_seg) return DQO_ERR_INVALID_ARG;
+    return dequant_reduce_range(seg_len, n_seg, sign, level, M, norms, 0, b_seg, p_begin, p_end, out);
+}
+
+int dqo_dequant_reduce_v(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign, const uint8_t *level,
+                         int32_t M, const float *norms, const int32_t *b_seg, float *out /* [D'] */)
+{
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    return dqo_dequant_reduce_v_range(seg_len, n_seg, sign, level, M, norms, b_seg, 0, dp, out);
+}
+
+/* whole passes on messages with per-tensor widths; scratch holds 2*M*D' bytes */
+int dqo_quantize_pack_v(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+                        int32_t M, const float *norms, const int32_t *b_seg, uint64_t seed, uint32_t step,
+                        uint32_t worker_base, uint8_t *packed, int64_t packed_stride, uint8_t *scratch)
+{
+    if (!packed || !scratch) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    int64_t bytes = dqo_packed_bytes_v(seg_len, n_seg, b_seg);
+    if (dp < 0 || bytes < 0 || packed_stride < bytes) return DQO_ERR_INVALID_ARG;
+    uint8_t *sign = scratch, *level = scratch + (int64_t)M * dp;
+    int rc = dqo_quantize_v(seg_len, n_seg, grads, worker_stride, M, norms, b_seg, seed, step, worker_base,
+                            sign, level);
+    for (int32_t i = 0; rc == DQO_OK && i < M; ++i)
+        rc = dqo_pack_v(sign + (int64_t)i * dp, level + (int64_t)i * dp, seg_len, n_seg, b_seg,
+                        packed + (int64_t)i * packed_stride);
+    return rc;
+}
+
+int dqo_unpack_dequant_reduce_v(const int64_t *seg_len, int32_t n_seg, const uint8_t *packed,
+                                int64_t packed_stride, int32_t M, const float *norms, const int32_t *b_seg,
+                                float *out, uint8_t *scratch)
+{
+    if (!packed || !scratch || M < 1) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    uint8_t *sign = scratch, *level = scratch + (int64_t)M * dp;
+    int rc = DQO_OK;
+    for (int32_t i = 0; rc == DQO_OK && i < M; ++i)
+        rc = dqo_unpack_v(packed + (int64_t)i * packed_stride, seg_len, n_seg, b_seg, sign + (int64_t)i * dp,
+                          level + (int64_t)i * dp);
+    if (rc != DQO_OK) return rc;
+    return dqo_dequant_reduce_v(seg_len, n_seg, sign, level, M, norms, b_seg, out);
+}
+
+/* Eq. (7) with per-tensor widths, one iteration: W [ sum_l d_l (b_l + 1) + n_seg B_pre ] bits. */
+int64_t dqo_comm_cost_bits_per_tensor(int W, const int64_t *seg_len, const int32_t *b_seg, int32_t n_seg,
+                                      int B_pre)
+{
+    if (W < 1 || !seg_len || n_seg < 1 || B_pre < 0 || !widths_ok(b_seg, n_seg)) return -1;
+    int64_t bits = 0;
+    for (int32_t l = 0; l < n_seg; ++l) {
+        if (seg_len[l] < 0) return -1;
+        bits += seg_len[l] * (int64_t)(b_seg[l] + 1) + B_pre;
+    }
+    return (int64_t)W * bits;
 }
 
 /* ------------------------------------------------------------------------------------------- */

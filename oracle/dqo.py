@@ -72,6 +72,26 @@ def lib():
                                         C.c_int64, u8p]
         L.dqo_unpack_dequant_reduce.argtypes = [i64p, C.c_int32, u8p, C.c_int64, C.c_int32, f32p,
                                                 C.c_int, f32p, u8p]
+        i32p = C.POINTER(C.c_int32)
+        L.dqo_select_bits_per_tensor.argtypes = [f32p, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_double,
+                                                 C.c_double, C.c_int, C.c_int, i32p, C.POINTER(C.c_double)]
+        L.dqo_packed_bytes_v.argtypes = [i64p, C.c_int32, i32p]
+        L.dqo_packed_bytes_v.restype = C.c_int64
+        L.dqo_quantize_v.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, f32p, i32p, C.c_uint64,
+                                     C.c_uint32, C.c_uint32, u8p, u8p]
+        L.dqo_quantize_v_range.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, f32p, i32p, C.c_uint64,
+                                           C.c_uint32, C.c_uint32, C.c_int64, C.c_int64, u8p, u8p]
+        L.dqo_pack_v.argtypes = [u8p, u8p, i64p, C.c_int32, i32p, u8p]
+        L.dqo_unpack_v.argtypes = [u8p, i64p, C.c_int32, i32p, u8p, u8p]
+        L.dqo_dequant_reduce_v.argtypes = [i64p, C.c_int32, u8p, u8p, C.c_int32, f32p, i32p, f32p]
+        L.dqo_dequant_reduce_v_range.argtypes = [i64p, C.c_int32, u8p, u8p, C.c_int32, f32p, i32p, C.c_int64,
+                                                 C.c_int64, f32p]
+        L.dqo_quantize_pack_v.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, f32p, i32p, C.c_uint64,
+                                          C.c_uint32, C.c_uint32, u8p, C.c_int64, u8p]
+        L.dqo_unpack_dequant_reduce_v.argtypes = [i64p, C.c_int32, u8p, C.c_int64, C.c_int32, f32p, i32p,
+                                                  f32p, u8p]
+        L.dqo_comm_cost_bits_per_tensor.argtypes = [C.c_int, i64p, i32p, C.c_int32, C.c_int]
+        L.dqo_comm_cost_bits_per_tensor.restype = C.c_int64
         L.dqo_update.argtypes = [f32p, f32p, C.c_int64, C.c_float]
         L.dqo_alpha_est.argtypes = [C.c_double, C.c_double, C.c_int64]
         L.dqo_alpha_est.restype = C.c_double
@@ -317,6 +337,166 @@ def alpha_est(F_t, F_0, t):
 
 def comm_cost_bits(W, d, b, n_norms=1, B_pre=32):
     v = int(lib().dqo_comm_cost_bits(W, d, b, n_norms, B_pre))
+    if v < 0:
+        raise ValueError("bad argument")
+    return v
+
+
+# ------------------------------------------------------------------ one bit-width per tensor
+def _widths(b_seg, n_seg):
+    b = np.ascontiguousarray(np.asarray(b_seg, dtype=np.int32).reshape(-1))
+    if b.size != n_seg:
+        raise ValueError("one width per tensor")
+    return b
+
+
+def select_bits_per_tensor(norms, t, T, eps_hat_q, alpha, b_min, b_max):
+    """-> (b[n_seg] int32, Nbar[n_seg] float64)."""
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32))
+    if n.ndim != 2:
+        raise ValueError("norms must be [M][n_seg]")
+    b = np.zeros(n.shape[1], dtype=np.int32)
+    nbar = np.zeros(n.shape[1], dtype=np.float64)
+    _check(lib().dqo_select_bits_per_tensor(_p(n, C.c_float), n.shape[0], n.shape[1], t, T, eps_hat_q, alpha,
+                                            b_min, b_max, _p(b, C.c_int32), _p(nbar, C.c_double)),
+           "select_bits_per_tensor")
+    return b, nbar
+
+
+def packed_bytes_v(seg_len, b_seg) -> int:
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    return int(lib().dqo_packed_bytes_v(_p(s, C.c_int64), s.size, _p(b, C.c_int32)))
+
+
+def quantize_v(seg_len, grads, norms, b_seg, seed, step, worker_base=0):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    dp = padded_elems(s)
+    g = _grads2d(grads, dp)
+    M = g.shape[0]
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    sign = np.zeros((M, dp), dtype=np.uint8)
+    level = np.zeros((M, dp), dtype=np.uint8)
+    _check(lib().dqo_quantize_v(_p(s, C.c_int64), s.size, _p(g, C.c_float), g.shape[1], M, _p(n, C.c_float),
+                                _p(b, C.c_int32), seed, step, worker_base, _p(sign, C.c_uint8),
+                                _p(level, C.c_uint8)), "quantize_v")
+    return sign, level
+
+
+def quantize_v_range(seg_len, grads_slice, norms, b_seg, seed, step, p_begin, p_end, worker_base=0):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    span = int(p_end - p_begin)
+    g = _grads2d(grads_slice, span)
+    M = g.shape[0]
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    sign = np.zeros((M, span), dtype=np.uint8)
+    level = np.zeros((M, span), dtype=np.uint8)
+    _check(lib().dqo_quantize_v_range(_p(s, C.c_int64), s.size, _p(g, C.c_float), g.shape[1], M,
+                                      _p(n, C.c_float), _p(b, C.c_int32), seed, step, worker_base, p_begin,
+                                      p_end, _p(sign, C.c_uint8), _p(level, C.c_uint8)), "quantize_v_range")
+    return sign, level
+
+
+def pack_v(sign, level, seg_len, b_seg):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    sg = np.ascontiguousarray(np.asarray(sign, dtype=np.uint8).reshape(-1))
+    lv = np.ascontiguousarray(np.asarray(level, dtype=np.uint8).reshape(-1))
+    if sg.size != padded_elems(s) or lv.size != sg.size:
+        raise ValueError("codes must have D' entries")
+    out = np.zeros(packed_bytes_v(s, b), dtype=np.uint8)
+    _check(lib().dqo_pack_v(_p(sg, C.c_uint8), _p(lv, C.c_uint8), _p(s, C.c_int64), s.size, _p(b, C.c_int32),
+                            _p(out, C.c_uint8)), "pack_v")
+    return out
+
+
+def unpack_v(packed, seg_len, b_seg):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    pk = np.ascontiguousarray(np.asarray(packed, dtype=np.uint8).reshape(-1))
+    if pk.size < packed_bytes_v(s, b):
+        raise ValueError("message too short")
+    dp = padded_elems(s)
+    sign = np.zeros(dp, dtype=np.uint8)
+    level = np.zeros(dp, dtype=np.uint8)
+    _check(lib().dqo_unpack_v(_p(pk, C.c_uint8), _p(s, C.c_int64), s.size, _p(b, C.c_int32),
+                              _p(sign, C.c_uint8), _p(level, C.c_uint8)), "unpack_v")
+    return sign, level
+
+
+def dequant_reduce_v(seg_len, sign, level, norms, b_seg):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    dp = padded_elems(s)
+    sg = np.ascontiguousarray(np.asarray(sign, dtype=np.uint8))
+    lv = np.ascontiguousarray(np.asarray(level, dtype=np.uint8))
+    M = sg.shape[0]
+    if sg.shape != (M, dp) or lv.shape != (M, dp):
+        raise ValueError("codes must be [M][D']")
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    out = np.zeros(dp, dtype=np.float32)
+    _check(lib().dqo_dequant_reduce_v(_p(s, C.c_int64), s.size, _p(sg, C.c_uint8), _p(lv, C.c_uint8), M,
+                                      _p(n, C.c_float), _p(b, C.c_int32), _p(out, C.c_float)),
+           "dequant_reduce_v")
+    return out
+
+
+def dequant_reduce_v_range(seg_len, sign, level, norms, b_seg, p_begin, p_end):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    span = int(p_end - p_begin)
+    sg = np.ascontiguousarray(np.asarray(sign, dtype=np.uint8))
+    lv = np.ascontiguousarray(np.asarray(level, dtype=np.uint8))
+    M = sg.shape[0]
+    if sg.shape != (M, span) or lv.shape != (M, span):
+        raise ValueError("codes must be [M][p_end - p_begin]")
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    out = np.zeros(span, dtype=np.float32)
+    _check(lib().dqo_dequant_reduce_v_range(_p(s, C.c_int64), s.size, _p(sg, C.c_uint8), _p(lv, C.c_uint8), M,
+                                            _p(n, C.c_float), _p(b, C.c_int32), p_begin, p_end,
+                                            _p(out, C.c_float)), "dequant_reduce_v_range")
+    return out
+
+
+def quantize_pack_v(seg_len, grads, norms, b_seg, seed, step, worker_base=0):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    dp = padded_elems(s)
+    g = _grads2d(grads, dp)
+    M = g.shape[0]
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    stride = packed_bytes_v(s, b)
+    packed = np.zeros((M, stride), dtype=np.uint8)
+    scratch = np.zeros(2 * M * dp, dtype=np.uint8)
+    _check(lib().dqo_quantize_pack_v(_p(s, C.c_int64), s.size, _p(g, C.c_float), g.shape[1], M,
+                                     _p(n, C.c_float), _p(b, C.c_int32), seed, step, worker_base,
+                                     _p(packed, C.c_uint8), stride, _p(scratch, C.c_uint8)), "quantize_pack_v")
+    return packed
+
+
+def unpack_dequant_reduce_v(seg_len, packed, norms, b_seg):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    dp = padded_elems(s)
+    pk = np.asarray(packed)
+    if pk.dtype != np.uint8 or pk.ndim != 2 or not pk.flags.c_contiguous:
+        raise ValueError("packed must be a C-contiguous uint8 [M][stride] array")
+    M = pk.shape[0]
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    out = np.zeros(dp, dtype=np.float32)
+    scratch = np.zeros(2 * M * dp, dtype=np.uint8)
+    _check(lib().dqo_unpack_dequant_reduce_v(_p(s, C.c_int64), s.size, _p(pk, C.c_uint8), pk.shape[1], M,
+                                             _p(n, C.c_float), _p(b, C.c_int32), _p(out, C.c_float),
+                                             _p(scratch, C.c_uint8)), "unpack_dequant_reduce_v")
+    return out
+
+
+def comm_cost_bits_per_tensor(W, seg_len, b_seg, B_pre=32):
+    s = _segs(seg_len)
+    b = _widths(b_seg, s.size)
+    v = int(lib().dqo_comm_cost_bits_per_tensor(W, _p(s, C.c_int64), _p(b, C.c_int32), s.size, B_pre))
     if v < 0:
         raise ValueError("bad argument")
     return v
