@@ -29,7 +29,8 @@
  * MEMORY    Pointers named *_dev are device pointers on the plan's GPU, 16-byte aligned, owned by
  *           the caller and borrowed until the enqueued work has finished.  Pointers named *_host
  *           are host pointers, read or written before the call returns.  The library allocates
- *           only the plan's tables (dq_plan_create / dq_plan_destroy).
+ *           only the plan's tables (dq_plan_create / dq_plan_destroy) and the per-tensor width
+ *           tables (dq_widths_create / dq_widths_destroy).
  * STREAMS   Device entry points enqueue on `hip_stream` (a hipStream_t passed as void*; NULL is
  *           the default stream) and return without synchronising.
  * ERRORS    Every int-returning function returns DQ_OK (0) or a negative dq_status; nothing
@@ -133,6 +134,62 @@ int dq_unpack_dequant_reduce(const dq_plan_t* plan, const uint8_t* packed_dev,
 int dq_unpack_dequant_reduce_update(const dq_plan_t* plan, const uint8_t* packed_dev,
                                     int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
                                     int b, float eta, float* x_dev, float* ghat_dev, void* hip_stream);
+
+/* ---- one bit-width per tensor -------------------------------------------------------------
+ * The single b of Algorithm 1 generalised to one b_l per tensor, all workers sharing it.
+ *   message  [sign plane | level plane] as before; in the level plane the tensors' fields follow
+ *            one another, tensor l taking 128*ceil(len_l/128) * b_l bits (a whole number of 16-byte
+ *            pieces), its element j at bits [j*b_l, j*b_l + b_l) of that stretch.  With all b_l
+ *            equal this is the single-width message.
+ */
+
+/* The bit rule per tensor.  Carrying the Lagrangian argument behind Eq. (17) (appendix "Proof of
+ * Eq. (17)") through with one level count per tensor -- variance bound sum_l d_l Nbar_l^2/(4 s_l^2)
+ * in place of Lemma 1's d Gbar^2/(4 s^2), cost sum_l d_l b_l -- gives
+ *     s*_l = sqrt(T/eps_hat_q) * alpha^((T-1-t)/2) * Nbar_l,   Nbar_l^2 = (1/M) sum_i N[i][l]^2,
+ * i.e. Eq. (17) with the tensor's own root-mean-square norm; b_l = smallest integer in
+ * [b_min, b_max] with 2^b_l - 1 >= s*_l, else b_max.  No tensor gets more bits than dq_select_bits
+ * gives the whole gradient.  Host code; arguments as dq_select_bits.
+ *   b_out_host [n_seg] int32, written;  nbar_out_host [n_seg] double or NULL. */
+int dq_select_bits_per_tensor(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
+                              double eps_hat_q, double alpha, int b_min, int b_max,
+                              int32_t* b_out_host, double* nbar_out_host);
+
+/* Message size per worker for the widths b_host[n_seg] (each 1..8): D'/8 + sum_l pad_l*b_l/8.
+ * Host code, needs no GPU.  -1 on a bad argument. */
+int64_t dq_packed_bytes_v(const dq_plan_t* plan, const int32_t* b_host);
+
+/* Eq. (7) with per-tensor widths, one iteration: W * sum_l (len_l*(b_l + 1) + B_pre) bits.  Host
+ * code.  -1 on a bad argument. */
+int64_t dq_comm_cost_bits_per_tensor(int W, const int64_t* seg_len_host, const int32_t* b_host,
+                                     int32_t n_seg, int B_pre);
+
+/* The widths as the kernels read them: a small table on the plan's GPU (24 bytes per tensor) that
+ * dq_widths_set refills.  The plan must outlive it. */
+typedef struct dq_widths dq_widths_t;
+int dq_widths_create(const dq_plan_t* plan, dq_widths_t** widths_out); /* allocates; DQ_ERR_HIP without a GPU */
+void dq_widths_destroy(dq_widths_t* widths);
+/* Enqueues the upload of b_host[n_seg] (each 1..8; read before the call returns) on hip_stream.
+ * Work that uses `widths` must be ordered after it, and work enqueued earlier with the previous
+ * widths before it (same stream, or events).  Blocks only if the previous upload of this object
+ * has not finished yet. */
+int dq_widths_set(dq_widths_t* widths, const int32_t* b_host, void* hip_stream);
+int64_t dq_widths_packed_bytes(const dq_widths_t* widths); /* for the widths last set; -1 before */
+
+/* dq_quantize_pack, dq_unpack_dequant_reduce and dq_unpack_dequant_reduce_update with the widths
+ * of `widths` (created from `plan`, set at least once) in place of b.  Same arithmetic per element
+ * with s = 2^(b_l) - 1 for tensor l; packed_worker_stride_bytes >= dq_widths_packed_bytes. */
+int dq_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
+                       int64_t worker_stride_elems, int M, const float* norms_dev, uint64_t seed,
+                       uint32_t step, uint32_t worker_base, uint8_t* packed_dev,
+                       int64_t packed_worker_stride_bytes, void* hip_stream);
+int dq_unpack_dequant_reduce_v(const dq_plan_t* plan, const dq_widths_t* widths, const uint8_t* packed_dev,
+                               int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
+                               float* out_dev, void* hip_stream);
+int dq_unpack_dequant_reduce_update_v(const dq_plan_t* plan, const dq_widths_t* widths,
+                                      const uint8_t* packed_dev, int64_t packed_worker_stride_bytes, int M,
+                                      const float* norms_dev, float eta, float* x_dev, float* ghat_dev,
+                                      void* hip_stream);
 
 /* Eq. (24), the practical estimate of the convergence factor: alpha_est = (F(x_t)/F(x_0))^(1/t).
  * Host code.  Returns -1 unless t >= 1, F_t > 0 and F_0 > 0. */

@@ -8,6 +8,13 @@ from .binding import (  # noqa: F401
     comm_cost_bits,
     unpack_dequant_reduce_update,
     Plan,
+    Widths,
+    comm_cost_bits_per_tensor,
+    packed_bytes_v,
+    quantize_pack_v,
+    select_bits_per_tensor,
+    unpack_dequant_reduce_update_v,
+    unpack_dequant_reduce_v,
     library_path,
     load_library,
     norm,
@@ -19,6 +26,7 @@ from .binding import (  # noqa: F401
     unpack_dequant_reduce,
 )
 
-__all__ = ["DQError", "Plan", "alpha_est", "comm_cost_bits", "library_path", "load_library", "norm", "norm_linf",
+__all__ = ["DQError", "Plan", "Widths", "comm_cost_bits_per_tensor", "packed_bytes_v", "quantize_pack_v",
+           "select_bits_per_tensor", "unpack_dequant_reduce_update_v", "unpack_dequant_reduce_v", "alpha_est", "comm_cost_bits", "library_path", "load_library", "norm", "norm_linf",
            "probe_stream", "quantize_pack", "select_bits", "select_bits_linf", "unpack_dequant_reduce",
            "unpack_dequant_reduce_update"]

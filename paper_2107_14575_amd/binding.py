@@ -19,7 +19,10 @@ EXPORTS = (
     "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems",
     "dq_plan_segment_start", "dq_packed_bytes", "dq_workspace_bytes", "dq_plan_has_device",
     "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
-    "dq_unpack_dequant_reduce_update", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
+    "dq_unpack_dequant_reduce_update", "dq_select_bits_per_tensor", "dq_packed_bytes_v",
+    "dq_comm_cost_bits_per_tensor", "dq_widths_create", "dq_widths_destroy", "dq_widths_set",
+    "dq_widths_packed_bytes", "dq_quantize_pack_v", "dq_unpack_dequant_reduce_v",
+    "dq_unpack_dequant_reduce_update_v", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
 )
 
 
@@ -79,6 +82,28 @@ def load_library():
     L.dq_unpack_dequant_reduce.restype = C.c_int
     L.dq_unpack_dequant_reduce_update.argtypes = [vp, vp, i64, C.c_int, vp, C.c_int, C.c_float, vp, vp, vp]
     L.dq_unpack_dequant_reduce_update.restype = C.c_int
+    i32p = C.POINTER(C.c_int32)
+    L.dq_select_bits_per_tensor.argtypes = [f32p, C.c_int, C.c_int, i64, i64, C.c_double, C.c_double,
+                                            C.c_int, C.c_int, i32p, C.POINTER(C.c_double)]
+    L.dq_select_bits_per_tensor.restype = C.c_int
+    L.dq_packed_bytes_v.argtypes = [vp, i32p]
+    L.dq_packed_bytes_v.restype = i64
+    L.dq_comm_cost_bits_per_tensor.argtypes = [C.c_int, C.POINTER(C.c_int64), i32p, i32, C.c_int]
+    L.dq_comm_cost_bits_per_tensor.restype = i64
+    L.dq_widths_create.argtypes = [vp, C.POINTER(vp)]
+    L.dq_widths_create.restype = C.c_int
+    L.dq_widths_destroy.argtypes = [vp]
+    L.dq_widths_destroy.restype = None
+    L.dq_widths_set.argtypes = [vp, i32p, vp]
+    L.dq_widths_set.restype = C.c_int
+    L.dq_widths_packed_bytes.argtypes = [vp]
+    L.dq_widths_packed_bytes.restype = i64
+    L.dq_quantize_pack_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, C.c_uint64, C.c_uint32, C.c_uint32, vp, i64, vp]
+    L.dq_quantize_pack_v.restype = C.c_int
+    L.dq_unpack_dequant_reduce_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, vp, vp]
+    L.dq_unpack_dequant_reduce_v.restype = C.c_int
+    L.dq_unpack_dequant_reduce_update_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, C.c_float, vp, vp, vp]
+    L.dq_unpack_dequant_reduce_update_v.restype = C.c_int
     L.dq_alpha_est.argtypes = [C.c_double, C.c_double, i64]
     L.dq_alpha_est.restype = C.c_double
     L.dq_comm_cost_bits.argtypes = [C.c_int, i64, C.c_int, i32, C.c_int]
@@ -243,3 +268,106 @@ def comm_cost_bits(W: int, d: int, b: int, n_norms: int = 1, B_pre: int = 32) ->
     if v < 0:
         raise DQError("dq_comm_cost_bits", -1, "invalid argument")
     return v
+
+
+# ------------------------------------------------------------------ one bit-width per tensor
+def _widths_array(b_seg, n_seg):
+    b = np.ascontiguousarray(np.asarray(b_seg, dtype=np.int32).reshape(-1))
+    if b.size != n_seg:
+        raise ValueError("one width per tensor")
+    return b
+
+
+def select_bits_per_tensor(norms_host, t: int, T: int, eps_hat_q: float, alpha: float, b_min: int, b_max: int):
+    """norms_host [M][n_seg] -> (b[n_seg] int32, Nbar[n_seg] float64)."""
+    n = np.ascontiguousarray(np.asarray(norms_host, dtype=np.float32))
+    if n.ndim != 2:
+        raise ValueError("norms must be [M][n_seg]")
+    b = np.zeros(n.shape[1], dtype=np.int32)
+    nbar = np.zeros(n.shape[1], dtype=np.float64)
+    _check("dq_select_bits_per_tensor",
+           load_library().dq_select_bits_per_tensor(n.ctypes.data_as(C.POINTER(C.c_float)), n.shape[0], n.shape[1],
+                                                    t, T, eps_hat_q, alpha, b_min, b_max,
+                                                    b.ctypes.data_as(C.POINTER(C.c_int32)),
+                                                    nbar.ctypes.data_as(C.POINTER(C.c_double))))
+    return b, nbar
+
+
+def packed_bytes_v(plan: Plan, b_seg) -> int:
+    b = _widths_array(b_seg, plan.n_seg)
+    return int(load_library().dq_packed_bytes_v(plan.handle, b.ctypes.data_as(C.POINTER(C.c_int32))))
+
+
+def comm_cost_bits_per_tensor(W: int, seg_len, b_seg, B_pre: int = 32) -> int:
+    lens = np.ascontiguousarray(np.asarray(seg_len, dtype=np.int64).reshape(-1))
+    b = _widths_array(b_seg, lens.size)
+    v = int(load_library().dq_comm_cost_bits_per_tensor(W, lens.ctypes.data_as(C.POINTER(C.c_int64)),
+                                                        b.ctypes.data_as(C.POINTER(C.c_int32)), lens.size, B_pre))
+    if v < 0:
+        raise ValueError("comm_cost_bits_per_tensor: bad argument")
+    return v
+
+
+class Widths:
+    """Per-tensor level bit-widths of a plan, as a table on the plan's GPU."""
+
+    def __init__(self, plan: Plan, b_seg=None, stream=None):
+        handle = C.c_void_p()
+        _check("dq_widths_create", load_library().dq_widths_create(plan.handle, C.byref(handle)))
+        self._h = handle
+        self.plan = plan
+        if b_seg is not None:
+            self.set(b_seg, stream)
+
+    def set(self, b_seg, stream=None) -> None:
+        b = _widths_array(b_seg, self.plan.n_seg)
+        _check("dq_widths_set", load_library().dq_widths_set(self.handle, b.ctypes.data_as(C.POINTER(C.c_int32)),
+                                                             _stream_handle(stream)))
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("widths are closed")
+        return self._h
+
+    @property
+    def packed_bytes(self) -> int:
+        return int(load_library().dq_widths_packed_bytes(self.handle))
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            load_library().dq_widths_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def quantize_pack_v(plan: Plan, widths: Widths, grads, norms, seed: int, step: int, packed_out,
+                    worker_base: int = 0, stream=None) -> None:
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    _check("dq_quantize_pack_v",
+           load_library().dq_quantize_pack_v(plan.handle, widths.handle, grads.data_ptr(), stride, M,
+                                             norms.data_ptr(), seed, step, worker_base, packed_out.data_ptr(),
+                                             int(packed_out.stride(0)), _stream_handle(stream)))
+
+
+def unpack_dequant_reduce_v(plan: Plan, widths: Widths, packed, norms, out, stream=None) -> None:
+    M = int(packed.shape[0])
+    _check("dq_unpack_dequant_reduce_v",
+           load_library().dq_unpack_dequant_reduce_v(plan.handle, widths.handle, packed.data_ptr(),
+                                                     int(packed.stride(0)), M, norms.data_ptr(), out.data_ptr(),
+                                                     _stream_handle(stream)))
+
+
+def unpack_dequant_reduce_update_v(plan: Plan, widths: Widths, packed, norms, eta: float, x, ghat=None,
+                                   stream=None) -> None:
+    M = int(packed.shape[0])
+    _check("dq_unpack_dequant_reduce_update_v",
+           load_library().dq_unpack_dequant_reduce_update_v(plan.handle, widths.handle, packed.data_ptr(),
+                                                            int(packed.stride(0)), M, norms.data_ptr(), eta,
+                                                            x.data_ptr(), ghat.data_ptr() if ghat is not None else None,
+                                                            _stream_handle(stream)))

@@ -22,6 +22,7 @@ struct dq_plan {
     int64_t* seg_start;   // host [n_seg + 1]
     int32_t n_items;      // norm work items
     int device;           // HIP device the tables live on, -1 if none
+    int32_t n_cseg;       // number of non-empty segments
     // device tables.  Kernels address segments through a compact index c that counts only the
     // non-empty ones, so consecutive granules differ by at most one in c.
     int32_t* d_granule_cseg;       // [D'/128]  compact segment index of each 128-element granule
@@ -29,6 +30,24 @@ struct dq_plan {
     int64_t* d_cseg_valid_end;     // [n_nonempty] P_l + len_l: first padded index past the data
     dq_norm_item* d_items;         // [n_items]
     int32_t* d_seg_item_begin;     // [n_seg + 1] items of segment l are [begin[l], begin[l+1])
+};
+
+// Per-tensor bit-widths (dq_widths_*): one entry per non-empty segment, indexed like the plan's
+// compact tables.
+struct dq_cseg_width {
+    int64_t level_start; // byte offset of the segment's level fields inside the level plane (multiple of 16)
+    int64_t seg_start;   // P_l
+    int32_t b;           // level bits of the segment, 1..8
+    int32_t reserved;
+};
+
+struct dq_widths {
+    const dq_plan* plan;
+    dq_cseg_width* d_table;  // device [plan->n_cseg]
+    dq_cseg_width* h_stage;  // pinned host staging of the same size
+    hipEvent_t uploaded;     // recorded after the last upload; the staging is reused only after it
+    int64_t packed_bytes;    // message size for the widths last set, -1 before the first set
+    int32_t* b_host;         // [n_seg] widths last set
 };
 
 static inline bool dq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

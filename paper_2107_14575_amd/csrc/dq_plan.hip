@@ -130,6 +130,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
         return DQ_ERR_ALLOC;
     }
     p->device = dev;
+    p->n_cseg = static_cast<int32_t>(cseg_seg.size());
     *plan_out = p;
     return DQ_OK;
 }

@@ -67,6 +67,97 @@ __device__ __forceinline__ void for_each_level(const uint32_t (&wd)[B], F&& f)
     }
 }
 
+// The M workers' contributions to a lane's 32 elements: acc[k] += sgn * level * unit, workers in
+// ascending order.  sign_ptr / level_ptr address worker 0's sign dword and B level dwords of the
+// lane; unit_ptr[w] is worker w's N/s for the lane's segment.
+template <int B>
+__device__ __forceinline__ void accumulate_lane(const uint8_t* __restrict__ sign_ptr,
+                                                const uint8_t* __restrict__ level_ptr, int64_t packed_stride,
+                                                int M, const float* unit_ptr, float (&acc)[UR_PER_LANE])
+{
+    // one worker's sign dword and B level dwords of this lane
+    auto load_worker = [&](int w, uint32_t& sg, uint32_t (&wd)[B]) {
+        sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
+        const uint32_t* lp = reinterpret_cast<const uint32_t*>(level_ptr + static_cast<int64_t>(w) * packed_stride);
+        if constexpr (B % 4 == 0) {
+#pragma unroll
+            for (int q = 0; q < B / 4; ++q) {
+                const uint4 t = reinterpret_cast<const uint4*>(lp)[q];
+                wd[4 * q] = t.x; wd[4 * q + 1] = t.y; wd[4 * q + 2] = t.z; wd[4 * q + 3] = t.w;
+            }
+        } else if constexpr (B % 2 == 0) {
+#pragma unroll
+            for (int q = 0; q < B / 2; ++q) {
+                const uint2 t = reinterpret_cast<const uint2*>(lp)[q];
+                wd[2 * q] = t.x; wd[2 * q + 1] = t.y;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < B; ++q) wd[q] = lp[q];
+        }
+    };
+    auto accumulate = [&](uint32_t sg, const uint32_t (&wd)[B], float unit) {
+        for_each_level<B>(wd, [&](int k, float lv) {
+            // sign bit of element k on top of the unit, whose own sign bit is always clear
+            const float su = __uint_as_float(__float_as_uint(unit) | ((sg << (31 - k)) & 0x80000000u));
+            acc[k] = __builtin_fmaf(lv, su, acc[k]);
+        });
+    };
+    // workers four at a time, so that four messages' loads are in flight together
+    constexpr int GROUP = 4;
+    int w = 0;
+    for (; w + GROUP <= M; w += GROUP) {
+        uint32_t sg[GROUP], wd[GROUP][B];
+#pragma unroll
+        for (int i = 0; i < GROUP; ++i) load_worker(w + i, sg[i], wd[i]);
+#pragma unroll
+        for (int i = 0; i < GROUP; ++i) accumulate(sg[i], wd[i], unit_ptr[w + i]);
+    }
+    for (; w < M; ++w) {
+        uint32_t sg, wd[B];
+        load_worker(w, sg, wd);
+        accumulate(sg, wd, unit_ptr[w]);
+    }
+}
+
+// Scales a lane's sums by 1/M (zero beyond the tensor's end), transposes the workgroup's tile
+// through LDS and writes it out, with the model update when x is given.
+__device__ __forceinline__ void finish_tile(float (&acc)[UR_PER_LANE], bool active, int64_t n_valid, float inv_M,
+                                            float4* lds_out, int tid, int64_t tile0, int64_t tile_end,
+                                            float* __restrict__ out, float* __restrict__ x, float eta)
+{
+    if (active) {
+        const int nv = n_valid >= UR_PER_LANE ? UR_PER_LANE : (n_valid > 0 ? static_cast<int>(n_valid) : 0);
+#pragma unroll
+        for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = k < nv ? acc[k] * inv_M : 0.0f;
+    }
+    // lane t of wave v holds elements [v*2048 + 32t, +32): slot (t, q) -> t*8 + (q ^ (t & 7))
+    const int wave = tid >> 6, lane = tid & 63;
+    float4* wave_out = lds_out + wave * 512;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        wave_out[lane * 8 + (q ^ (lane & 7))] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        // store j of the wave covers its elements [256j, 256j + 256); this lane takes 4 of them
+        const int src_lane = 8 * j + (lane >> 3), q = lane & 7;
+        const float4 v = wave_out[src_lane * 8 + (q ^ (src_lane & 7))];
+        const int64_t P = tile0 + wave * 2048 + 256 * j + 4 * lane;
+        if (P < tile_end) {
+            if (out) *reinterpret_cast<float4*>(out + P) = v;
+            if (x) { // model update of Algorithm 1: x <- x - eta * g_hat (pads: g_hat is +0, x unchanged)
+                float4 xv = *reinterpret_cast<const float4*>(x + P);
+                xv.x = __builtin_fmaf(-eta, v.x, xv.x);
+                xv.y = __builtin_fmaf(-eta, v.y, xv.y);
+                xv.z = __builtin_fmaf(-eta, v.z, xv.z);
+                xv.w = __builtin_fmaf(-eta, v.w, xv.w);
+                *reinterpret_cast<float4*>(x + P) = xv;
+            }
+        }
+    }
+}
+
 template <int B>
 __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
     const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
@@ -106,83 +197,74 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
 #pragma unroll
     for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = 0.0f;
 
+    if (active)
+        accumulate_lane<B>(packed + (P0 >> 3), packed + (padded_elems >> 3) + (P0 >> 3) * B, packed_stride, M,
+                           lds_unit + local * M, acc);
+    finish_tile(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
+}
+
+// Per-tensor widths: each lane takes its segment's b and the place of its level dwords from the
+// widths table and runs the accumulation specialised for that b.  A lane's 32 elements lie in one
+// 128-element granule, hence in one segment; lanes of a wave differ in b only where a wave
+// straddles two tensors.
+__global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_v(
+    const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
+    int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths, int64_t padded_elems,
+    float inv_M, float* __restrict__ out, float* __restrict__ x, float eta)
+{
+    extern __shared__ __align__(16) uint8_t lds_raw[];
+    float4* lds_out = reinterpret_cast<float4*>(lds_raw);
+    float* lds_unit = reinterpret_cast<float*>(lds_raw + UR_TILE * sizeof(float));
+
+    const int tid = threadIdx.x;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * UR_TILE;
+    const int64_t tile_end = tile0 + UR_TILE < padded_elems ? tile0 + UR_TILE : padded_elems;
+    const int64_t P0 = tile0 + tid * UR_PER_LANE;
+    const bool active = P0 < tile_end;
+
+    const int32_t seg_first = granule_cseg[tile0 >> 7];
+    const int32_t seg_last = granule_cseg[(tile_end - 1) >> 7];
+    const int n_local = seg_last - seg_first + 1;
+    for (int i = tid; i < n_local * M; i += UR_THREADS) {
+        const int local = i / M, w = i - local * M;
+        const float S = static_cast<float>((1 << widths[seg_first + local].b) - 1);
+        const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + local]];
+        lds_unit[i] = N >= DQ_MIN_NORM ? N / S : 0.0f;
+    }
+    int local = 0, b = 0;
+    int64_t n_valid = 0, level_off = 0;
+    if (active) {
+        const int32_t c = granule_cseg[P0 >> 7];
+        const dq_cseg_width e = widths[c];
+        local = c - seg_first;
+        n_valid = cseg_valid_end[c] - P0;
+        b = e.b;
+        level_off = e.level_start + ((P0 - e.seg_start) >> 3) * e.b; // 4*b bytes per lane: dword aligned
+    }
+    __syncthreads();
+
+    float acc[UR_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = 0.0f;
+
     if (active) {
         const uint8_t* sign_ptr = packed + (P0 >> 3);
-        const uint8_t* level_ptr = packed + (padded_elems >> 3) + (P0 >> 3) * B;
+        const uint8_t* level_ptr = packed + (padded_elems >> 3) + level_off;
         const float* unit_ptr = lds_unit + local * M;
-        // one worker's sign dword and B level dwords of this lane
-        auto load_worker = [&](int w, uint32_t& sg, uint32_t (&wd)[B]) {
-            sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
-            const uint32_t* lp = reinterpret_cast<const uint32_t*>(level_ptr + static_cast<int64_t>(w) * packed_stride);
-            if constexpr (B % 4 == 0) {
-#pragma unroll
-                for (int q = 0; q < B / 4; ++q) {
-                    const uint4 t = reinterpret_cast<const uint4*>(lp)[q];
-                    wd[4 * q] = t.x; wd[4 * q + 1] = t.y; wd[4 * q + 2] = t.z; wd[4 * q + 3] = t.w;
-                }
-            } else if constexpr (B % 2 == 0) {
-#pragma unroll
-                for (int q = 0; q < B / 2; ++q) {
-                    const uint2 t = reinterpret_cast<const uint2*>(lp)[q];
-                    wd[2 * q] = t.x; wd[2 * q + 1] = t.y;
-                }
-            } else {
-#pragma unroll
-                for (int q = 0; q < B; ++q) wd[q] = lp[q];
-            }
-        };
-        auto accumulate = [&](uint32_t sg, const uint32_t (&wd)[B], float unit) {
-            for_each_level<B>(wd, [&](int k, float lv) {
-                // sign bit of element k on top of the unit, whose own sign bit is always clear
-                const float su = __uint_as_float(__float_as_uint(unit) | ((sg << (31 - k)) & 0x80000000u));
-                acc[k] = __builtin_fmaf(lv, su, acc[k]);
-            });
-        };
-        // workers four at a time, so that four messages' loads are in flight together
-        constexpr int GROUP = 4;
-        int w = 0;
-        for (; w + GROUP <= M; w += GROUP) {
-            uint32_t sg[GROUP], wd[GROUP][B];
-#pragma unroll
-            for (int i = 0; i < GROUP; ++i) load_worker(w + i, sg[i], wd[i]);
-#pragma unroll
-            for (int i = 0; i < GROUP; ++i) accumulate(sg[i], wd[i], unit_ptr[w + i]);
-        }
-        for (; w < M; ++w) {
-            uint32_t sg, wd[B];
-            load_worker(w, sg, wd);
-            accumulate(sg, wd, unit_ptr[w]);
-        }
-        const int nv = n_valid >= UR_PER_LANE ? UR_PER_LANE : (n_valid > 0 ? static_cast<int>(n_valid) : 0);
-#pragma unroll
-        for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = k < nv ? acc[k] * inv_M : 0.0f;
-    }
-
-    // lane t of wave v holds elements [v*2048 + 32t, +32): slot (t, q) -> t*8 + (q ^ (t & 7))
-    const int wave = tid >> 6, lane = tid & 63;
-    float4* wave_out = lds_out + wave * 512;
-#pragma unroll
-    for (int q = 0; q < 8; ++q)
-        wave_out[lane * 8 + (q ^ (lane & 7))] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        // store j of the wave covers its elements [256j, 256j + 256); this lane takes 4 of them
-        const int src_lane = 8 * j + (lane >> 3), q = lane & 7;
-        const float4 v = wave_out[src_lane * 8 + (q ^ (src_lane & 7))];
-        const int64_t P = tile0 + wave * 2048 + 256 * j + 4 * lane;
-        if (P < tile_end) {
-            if (out) *reinterpret_cast<float4*>(out + P) = v;
-            if (x) { // model update of Algorithm 1: x <- x - eta * g_hat (pads: g_hat is +0, x unchanged)
-                float4 xv = *reinterpret_cast<const float4*>(x + P);
-                xv.x = __builtin_fmaf(-eta, v.x, xv.x);
-                xv.y = __builtin_fmaf(-eta, v.y, xv.y);
-                xv.z = __builtin_fmaf(-eta, v.z, xv.z);
-                xv.w = __builtin_fmaf(-eta, v.w, xv.w);
-                *reinterpret_cast<float4*>(x + P) = xv;
-            }
+        switch (b) {
+        case 1: accumulate_lane<1>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        case 2: accumulate_lane<2>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        case 3: accumulate_lane<3>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        case 4: accumulate_lane<4>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        case 5: accumulate_lane<5>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        case 6: accumulate_lane<6>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        case 7: accumulate_lane<7>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        case 8: accumulate_lane<8>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        default: break; // the host only uploads widths in 1..8
         }
     }
+    finish_tile(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
 }
 
 template <int B>
@@ -225,7 +307,52 @@ int reduce_entry(const dq_plan_t* plan, const uint8_t* packed_dev, int64_t packe
     }
 }
 
+int reduce_entry_v(const dq_plan_t* plan, const dq_widths_t* widths, const uint8_t* packed_dev,
+                   int64_t packed_worker_stride_bytes, int M, const float* norms_dev, float* out_dev, float* x_dev,
+                   float eta, void* hip_stream)
+{
+    if (!plan || !widths || !packed_dev || !norms_dev || (!out_dev && !x_dev)) return DQ_ERR_INVALID_ARG;
+    if (widths->plan != plan || widths->packed_bytes < 0) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < widths->packed_bytes || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(packed_dev) || !dq_aligned16(out_dev) || !dq_aligned16(x_dev) ||
+        (reinterpret_cast<uintptr_t>(norms_dev) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    if (x_dev && !(eta == eta)) return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    if (plan->padded_elems == 0) return DQ_OK;
+    const int64_t n_tiles = (plan->padded_elems + UR_TILE - 1) / UR_TILE;
+    if (n_tiles > INT32_MAX) return DQ_ERR_INVALID_ARG;
+    const size_t lds_bytes = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(float);
+    hipLaunchKernelGGL(k_unpack_dequant_reduce_v, dim3(static_cast<unsigned>(n_tiles)), dim3(UR_THREADS), lds_bytes,
+                       static_cast<hipStream_t>(hip_stream), packed_dev, packed_worker_stride_bytes, M, norms_dev,
+                       plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table,
+                       plan->padded_elems, 1.0f / static_cast<float>(M), out_dev, x_dev, eta);
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
 } // namespace
+
+extern "C" int dq_unpack_dequant_reduce_v(const dq_plan_t* plan, const dq_widths_t* widths,
+                                          const uint8_t* packed_dev, int64_t packed_worker_stride_bytes, int M,
+                                          const float* norms_dev, float* out_dev, void* hip_stream)
+{
+    if (!out_dev) return DQ_ERR_INVALID_ARG;
+    return reduce_entry_v(plan, widths, packed_dev, packed_worker_stride_bytes, M, norms_dev, out_dev, nullptr,
+                          0.0f, hip_stream);
+}
+
+extern "C" int dq_unpack_dequant_reduce_update_v(const dq_plan_t* plan, const dq_widths_t* widths,
+                                                 const uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                                                 int M, const float* norms_dev, float eta, float* x_dev,
+                                                 float* ghat_dev, void* hip_stream)
+{
+    if (!x_dev) return DQ_ERR_INVALID_ARG;
+    return reduce_entry_v(plan, widths, packed_dev, packed_worker_stride_bytes, M, norms_dev, ghat_dev, x_dev, eta,
+                          hip_stream);
+}
 
 extern "C" int dq_unpack_dequant_reduce(const dq_plan_t* plan, const uint8_t* packed_dev,
                                         int64_t packed_worker_stride_bytes, int M, const float* norms_dev,

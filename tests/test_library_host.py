@@ -132,3 +132,28 @@ def test_workload_shapes():
     assert np.isnan(gn[:, ~valid]).all() and np.isfinite(gn[:, valid]).all()
     seg2, g2 = wl.ragged_mix(M=2)
     assert np.array_equal(g2.numpy()[:, valid], gn[:, valid])
+
+
+def test_per_tensor_host_functions_against_the_oracle(dq, oracle):
+    rng = np.random.default_rng(7)
+    for _ in range(300):
+        M, n_seg = int(rng.integers(1, 9)), int(rng.integers(1, 12))
+        norms = (10 ** rng.uniform(-6, 1, size=(M, n_seg))).astype(np.float32)
+        norms[:, rng.integers(0, n_seg)] = 0
+        T = int(rng.integers(1, 500))
+        t = int(rng.integers(0, T))
+        eps, alpha = float(10 ** rng.uniform(-8, 2)), float(rng.uniform(0.5, 1.0))
+        b_min = int(rng.integers(1, 9))
+        b_max = int(rng.integers(b_min, 9))
+        got_b, got_n = dq.select_bits_per_tensor(norms, t, T, eps, alpha, b_min, b_max)
+        want_b, want_n = oracle.select_bits_per_tensor(norms, t, T, eps, alpha, b_min, b_max)
+        assert np.array_equal(got_b, want_b)
+        assert np.allclose(got_n, want_n, rtol=1e-15, atol=0)
+        seg = [int(x) for x in rng.integers(0, 5000, size=n_seg)]
+        plan = dq.Plan(seg)
+        assert dq.packed_bytes_v(plan, got_b) == oracle.packed_bytes_v(seg, got_b)
+        assert dq.comm_cost_bits_per_tensor(M, seg, got_b, 32) == oracle.comm_cost_bits_per_tensor(M, seg, got_b, 32)
+        assert dq.packed_bytes_v(plan, [9] * n_seg) == -1
+        plan.close()
+    with pytest.raises(dq.DQError):
+        dq.select_bits_per_tensor(np.ones((2, 2), dtype=np.float32), 5, 5, 0.1, 0.9, 1, 8)
