@@ -13,6 +13,9 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
   * lagged=False: b_t is computed from iteration t's own norms before quantizing (needs the norms
     on the host before the quantize pass).
   * alpha: a number, or "estimate" to use Eq. (24) with the caller's loss at the update points.
+  * per_tensor=True: one bit-width per tensor from ``dq_select_bits_per_tensor`` (b0, b_t in the
+    result and on_step's b are then arrays of n_seg widths), messages in the per-tensor layout,
+    through the ``*_v`` entry points.
   * p: 2 or "inf", the norm of Eq. (5) (the paper leaves p open): ``dq_norm``/``dq_select_bits`` or
     ``dq_norm_linf``/``dq_select_bits_linf``.
 """
@@ -39,7 +42,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         M: int, T: int, eta: float, eps_hat_q: float, alpha: Union[float, str], b0: int,
         b_min: int = 1, b_max: int = 8, tau: int = 1, lagged: bool = True, seed: int = 0,
         loss_fn: Optional[Callable[["torch.Tensor"], float]] = None, B_pre: int = 32,
-        on_step: Optional[Callable] = None, p: Union[int, str] = 2) -> DQSGDResult:
+        on_step: Optional[Callable] = None, p: Union[int, str] = 2, per_tensor: bool = False) -> DQSGDResult:
     """grad_fn(t, x, grads_out) fills grads_out[M][D'] (float32, CUDA, padded layout) with the M
     workers' stochastic gradients at x.  on_step(t, b_t, grads, norms_host, packed) is called after
     the quantize pass of every iteration (tests use it to feed the same bytes to the oracle)."""
@@ -47,6 +50,9 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         raise ValueError('p must be 2 or "inf"')
     norm_fn, rule = (_b.norm, _b.select_bits) if p == 2 else (_b.norm_linf, _b.select_bits_linf)
     dp, n_seg = plan.padded_elems, plan.n_seg
+    if per_tensor:
+        return _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged,
+                               seed, B_pre, on_step, norm_fn)
     dev = x0.device
     x = x0.clone()
     grads = torch.zeros((M, dp), dtype=torch.float32, device=dev)
@@ -88,4 +94,46 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
                 b, _ = rule(norms_host.numpy(), t + 1, T, eps_hat_q, cur_alpha, b_min, b_max)
         res.gbar.append(gb)
     torch.cuda.synchronize()
+    return res
+
+
+def _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged, seed, B_pre,
+                    on_step, norm_fn) -> DQSGDResult:
+    import numpy as np
+    if alpha == "estimate":
+        raise ValueError('alpha="estimate" is not available with per_tensor')
+    dp, n_seg = plan.padded_elems, plan.n_seg
+    dev = x0.device
+    x = x0.clone()
+    grads = torch.zeros((M, dp), dtype=torch.float32, device=dev)
+    norms = torch.empty((M, n_seg), dtype=torch.float32, device=dev)
+    norms_host = torch.empty((M, n_seg), dtype=torch.float32).pin_memory()
+    ws = torch.empty(plan.workspace_bytes(M), dtype=torch.uint8, device=dev)
+    packed = torch.zeros((M, _b.packed_bytes_v(plan, [b_max] * n_seg)), dtype=torch.uint8, device=dev)
+    b = np.broadcast_to(np.asarray(b0, dtype=np.int32), (n_seg,)).copy()
+    table = _b.Widths(plan, b)
+    res = DQSGDResult(x=x)
+    for t in range(T):
+        grad_fn(t, x, grads)
+        norm_fn(plan, grads, norms, ws)
+        norms_host.copy_(norms, non_blocking=True)
+        if not lagged:
+            torch.cuda.current_stream().synchronize()
+            b, _ = _b.select_bits_per_tensor(norms_host.numpy(), t, T, eps_hat_q, float(alpha), b_min, b_max)
+            table.set(b)
+        pk = packed[:, :table.packed_bytes]
+        _b.quantize_pack_v(plan, table, grads, norms, seed, t, pk)
+        if on_step is not None:
+            torch.cuda.current_stream().synchronize()
+            on_step(t, b.copy(), grads, norms_host.numpy(), pk)
+        _b.unpack_dequant_reduce_update_v(plan, table, pk, norms, eta, x)
+        res.bits.append(b.copy())
+        res.cost_bits += _b.comm_cost_bits_per_tensor(M, plan.seg_len, b, B_pre)
+        torch.cuda.current_stream().synchronize()
+        res.gbar.append(float(np.sqrt((norms_host.numpy().astype(np.float64) ** 2).sum() / M)))
+        if lagged and t + 1 < T and (t + 1) % tau == 0:
+            b, _ = _b.select_bits_per_tensor(norms_host.numpy(), t + 1, T, eps_hat_q, float(alpha), b_min, b_max)
+            table.set(b)
+    torch.cuda.synchronize()
+    table.close()
     return res

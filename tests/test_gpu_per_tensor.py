@@ -216,3 +216,53 @@ def test_argument_checks(dq):
     table.close()
     other.close()
     plan.close()
+
+
+def test_algorithm1_loop_with_per_tensor_widths(dq, oracle):
+    """Algorithm 1 with one width per tensor on a least-squares problem whose two tensors have very
+    different gradient norms: widths, bitstreams, model and cost follow the oracle loop; the
+    low-norm tensor is sent with fewer bits than the single-width rule would use."""
+    from paper_2107_14575_amd import dqsgd
+    seg_len = [700, 300, 77]
+    plan = dq.Plan(seg_len)
+    starts, dp = wl.seg_starts(seg_len)
+    M, T, eta, alpha, tau, eps_hat = 4, 40, 0.2, 0.9, 5, 0.02
+    gen = torch.Generator().manual_seed(57)
+    target = torch.zeros(dp)
+    for (st, n), scale in zip(zip(starts, seg_len), (1.0, 0.01, 0.1)):
+        target[st:st + n] = torch.randn(n, generator=gen) * scale
+    noise_scale = torch.zeros(dp)
+    for (st, n), scale in zip(zip(starts, seg_len), (0.05, 0.0005, 0.005)):
+        noise_scale[st:st + n] = scale
+    noise = (torch.randn((T, M, dp), generator=gen) * noise_scale).cuda()
+    target = target.cuda()
+
+    def grad_fn(t, x, grads):
+        grads.copy_((x - target).unsqueeze(0) + noise[t])
+
+    x_or = np.zeros(dp, dtype=np.float32)
+    state = dict(b=np.full(3, 2, dtype=np.int32), bits=[], cost=0, single=[])
+
+    def on_step(t, b, grads, norms, packed):
+        g_host = np.ascontiguousarray(grads.cpu().numpy())
+        assert np.array_equal(b, state["b"]), f"widths differ at t={t}"
+        want = oracle.quantize_pack_v(seg_len, g_host, norms, b, SEED, t)
+        assert np.array_equal(packed.cpu().numpy(), want), f"bitstream differs at t={t}"
+        oracle.update(x_or, oracle.unpack_dequant_reduce_v(seg_len, want, norms, b), eta)
+        state["bits"].append(b.copy())
+        state["cost"] += oracle.comm_cost_bits_per_tensor(M, seg_len, b, 32)
+        if t + 1 < T and (t + 1) % tau == 0:
+            state["b"], _ = oracle.select_bits_per_tensor(norms, t + 1, T, eps_hat, alpha, 1, 8)
+            state["single"].append(oracle.select_bits(norms, t + 1, T, eps_hat, alpha, 1, 8)[0])
+
+    x0 = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    res = dqsgd.run(plan, x0, grad_fn, M, T, eta, eps_hat, alpha, b0=2, b_min=1, b_max=8, tau=tau, lagged=True,
+                    seed=SEED, on_step=on_step, per_tensor=True)
+    assert all(np.array_equal(a, c) for a, c in zip(res.bits, state["bits"])) and res.cost_bits == state["cost"]
+    widths = np.array(res.bits)
+    assert len(np.unique(widths)) >= 3 and np.any(widths[:, 0] > widths[:, 1])
+    assert all(np.all(state["bits"][tau * (k + 1)] <= s) for k, s in enumerate(state["single"]))
+    x_gpu = res.x.cpu().numpy()
+    assert np.abs(x_gpu - x_or).max() <= T * (2.0 ** -23 * np.abs(x_or).max() + eta * 1e-6 * 4.0)
+    assert float((res.x - target).norm()) < 0.1 * float(target.norm())
+    plan.close()
