@@ -647,6 +647,68 @@ int64_t dqo_comm_cost_bits_per_tensor(int W, const int64_t *seg_len, const int32
 }
 
 /* ------------------------------------------------------------------------------------------- */
+/* Sign-only messages: the 1-bit-per-element baseline of the paper's Table 2 ("SignSGD", cost     */
+/* W*T*d bits -- Eq. (7) with b_paper = 1 and no norm).  A worker sends the sign plane alone.     */
+/* The paper does not say what the server does with it; the two rules in use are both here:       */
+/*   mean:      out_P = (1/M) sum_i c_{i,l} * sgn_{i,P}, with a per-worker, per-tensor scale c    */
+/*              that travels beside the message (1 when scales == NULL);                          */
+/*   majority:  out_P = sgn( sum_i sgn_{i,P} ) in {-1, 0, +1} (0 on a tie).                       */
+/* sgn is -1 when the IEEE sign bit is set, else +1 (so +0.0 votes +1, as in the quantizer).      */
+/* ------------------------------------------------------------------------------------------- */
+int dqo_sign_pack(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+                  int32_t M, uint8_t *packed, int64_t packed_stride)
+{
+    if (!seg_len || !grads || !packed || n_seg < 1 || M < 1) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0 || packed_stride < dp / 8) return DQO_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < M; ++i) {
+        uint8_t *msg = packed + (int64_t)i * packed_stride;
+        const float *g = grads + (int64_t)i * worker_stride;
+        memset(msg, 0, (size_t)(dp / 8));
+        int64_t start = 0;
+        for (int32_t l = 0; l < n_seg; ++l) {
+            for (int64_t j = 0; j < seg_len[l]; ++j) {
+                uint32_t bits;
+                memcpy(&bits, &g[start + j], 4);
+                put_bits(msg, start + j, 1, bits >> 31);
+            }
+            start += padded_len(seg_len[l]);
+        }
+    }
+    return DQO_OK;
+}
+
+int dqo_sign_reduce(const int64_t *seg_len, int32_t n_seg, const uint8_t *packed, int64_t packed_stride,
+                    int32_t M, const float *scales /* [M][n_seg] or NULL */, int majority,
+                    float *out /* [D'] */)
+{
+    if (!seg_len || !packed || !out || n_seg < 1 || M < 1) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0 || packed_stride < dp / 8) return DQO_ERR_INVALID_ARG;
+    for (int64_t q = 0; q < dp; ++q) out[q] = 0.0f;
+    int64_t start = 0;
+    for (int32_t l = 0; l < n_seg; ++l) {
+        for (int64_t j = 0; j < seg_len[l]; ++j) {
+            const int64_t P = start + j;
+            double acc = 0.0;
+            int votes = 0;
+            for (int32_t i = 0; i < M; ++i) {
+                const int neg = (int)get_bits(packed + (int64_t)i * packed_stride, P, 1);
+                const double c = scales ? (double)scales[(int64_t)i * n_seg + l] : 1.0;
+                acc += neg ? -c : c;
+                votes += neg ? -1 : 1;
+            }
+            if (majority)
+                out[P] = votes > 0 ? 1.0f : (votes < 0 ? -1.0f : 0.0f);
+            else
+                out[P] = (float)(acc / (double)M);
+        }
+        start += padded_len(seg_len[l]);
+    }
+    return DQO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
 /* Server update of Algorithm 1: x_{t+1} = x_t - eta * g_hat_t (also Eq. (2)).  The product and   */
 /* the difference are formed in binary64 and rounded once to binary32.                            */
 /* ------------------------------------------------------------------------------------------- */

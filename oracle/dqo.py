@@ -92,6 +92,8 @@ def lib():
                                                   f32p, u8p]
         L.dqo_comm_cost_bits_per_tensor.argtypes = [C.c_int, i64p, i32p, C.c_int32, C.c_int]
         L.dqo_comm_cost_bits_per_tensor.restype = C.c_int64
+        L.dqo_sign_pack.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, u8p, C.c_int64]
+        L.dqo_sign_reduce.argtypes = [i64p, C.c_int32, u8p, C.c_int64, C.c_int32, f32p, C.c_int, f32p]
         L.dqo_update.argtypes = [f32p, f32p, C.c_int64, C.c_float]
         L.dqo_alpha_est.argtypes = [C.c_double, C.c_double, C.c_int64]
         L.dqo_alpha_est.restype = C.c_double
@@ -500,3 +502,33 @@ def comm_cost_bits_per_tensor(W, seg_len, b_seg, B_pre=32):
     if v < 0:
         raise ValueError("bad argument")
     return v
+
+
+# ------------------------------------------------------------------------- sign-only messages
+def sign_pack(seg_len, grads):
+    """-> packed[M][D'/8] uint8: every worker's sign plane."""
+    s = _segs(seg_len)
+    dp = padded_elems(s)
+    g = _grads2d(grads, dp)
+    M = g.shape[0]
+    packed = np.zeros((M, dp // 8), dtype=np.uint8)
+    _check(lib().dqo_sign_pack(_p(s, C.c_int64), s.size, _p(g, C.c_float), g.shape[1], M,
+                               _p(packed, C.c_uint8), dp // 8), "sign_pack")
+    return packed
+
+
+def sign_reduce(seg_len, packed, scales=None, majority=False):
+    s = _segs(seg_len)
+    dp = padded_elems(s)
+    pk = np.asarray(packed)
+    if pk.dtype != np.uint8 or pk.ndim != 2 or not pk.flags.c_contiguous:
+        raise ValueError("packed must be a C-contiguous uint8 [M][stride] array")
+    M = pk.shape[0]
+    sc = None
+    if scales is not None:
+        sc = np.ascontiguousarray(np.asarray(scales, dtype=np.float32)).reshape(M, s.size)
+    out = np.zeros(dp, dtype=np.float32)
+    _check(lib().dqo_sign_reduce(_p(s, C.c_int64), s.size, _p(pk, C.c_uint8), pk.shape[1], M,
+                                 _p(sc, C.c_float) if sc is not None else None, 1 if majority else 0,
+                                 _p(out, C.c_float)), "sign_reduce")
+    return out
