@@ -191,6 +191,28 @@ int dq_unpack_dequant_reduce_update_v(const dq_plan_t* plan, const dq_widths_t* 
                                       const float* norms_dev, float eta, float* x_dev, float* ghat_dev,
                                       void* hip_stream);
 
+/* ---- sign-only messages ---------------------------------------------------------------------
+ * The one-bit-per-element baseline of the paper's Table 2 ("SignSGD": W*T*d bits, i.e. Eq. (7)
+ * with b_paper = 1 and no norm; dq_comm_cost_bits with b = 0, n_norms = 0).  A worker's message is
+ * the sign plane alone, D'/8 bytes in the layout above.  The paper does not say how the server
+ * combines such messages; both rules in use are offered.
+ */
+
+/* packed_dev [M] sign planes, worker i at packed_dev + i*packed_worker_stride_bytes (>= D'/8,
+ * multiple of 16), written in full; bit P set when the IEEE sign bit of g_P is set, pad bits 0. */
+int dq_sign_pack(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
+                 uint8_t* packed_dev, int64_t packed_worker_stride_bytes, void* hip_stream);
+
+/* out_P = (1/M) sum_i c[i][l] * sgn_{i,P}, sgn = -1 where the bit is set, else +1; binary32 sum
+ * over i ascending, then times 1/M.  scales_dev [M][n_seg] float (a scale per worker and tensor
+ * that travelled beside the message, e.g. mean |g|) or NULL for c = 1.  Pads +0.0f. */
+int dq_sign_reduce(const dq_plan_t* plan, const uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                   int M, const float* scales_dev, float* out_dev, void* hip_stream);
+
+/* Majority vote: out_P = sgn(sum_i sgn_{i,P}) in {-1, 0, +1}, 0 on a tie.  Exact. */
+int dq_sign_majority(const dq_plan_t* plan, const uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                     int M, float* out_dev, void* hip_stream);
+
 /* Eq. (24), the practical estimate of the convergence factor: alpha_est = (F(x_t)/F(x_0))^(1/t).
  * Host code.  Returns -1 unless t >= 1, F_t > 0 and F_0 > 0. */
 double dq_alpha_est(double F_t, double F_0, int64_t t);

@@ -22,7 +22,7 @@ EXPORTS = (
     "dq_unpack_dequant_reduce_update", "dq_select_bits_per_tensor", "dq_packed_bytes_v",
     "dq_comm_cost_bits_per_tensor", "dq_widths_create", "dq_widths_destroy", "dq_widths_set",
     "dq_widths_packed_bytes", "dq_quantize_pack_v", "dq_unpack_dequant_reduce_v",
-    "dq_unpack_dequant_reduce_update_v", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
+    "dq_unpack_dequant_reduce_update_v", "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
 )
 
 
@@ -104,6 +104,12 @@ def load_library():
     L.dq_unpack_dequant_reduce_v.restype = C.c_int
     L.dq_unpack_dequant_reduce_update_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, C.c_float, vp, vp, vp]
     L.dq_unpack_dequant_reduce_update_v.restype = C.c_int
+    L.dq_sign_pack.argtypes = [vp, vp, i64, C.c_int, vp, i64, vp]
+    L.dq_sign_pack.restype = C.c_int
+    L.dq_sign_reduce.argtypes = [vp, vp, i64, C.c_int, vp, vp, vp]
+    L.dq_sign_reduce.restype = C.c_int
+    L.dq_sign_majority.argtypes = [vp, vp, i64, C.c_int, vp, vp]
+    L.dq_sign_majority.restype = C.c_int
     L.dq_alpha_est.argtypes = [C.c_double, C.c_double, i64]
     L.dq_alpha_est.restype = C.c_double
     L.dq_comm_cost_bits.argtypes = [C.c_int, i64, C.c_int, i32, C.c_int]
@@ -371,3 +377,26 @@ def unpack_dequant_reduce_update_v(plan: Plan, widths: Widths, packed, norms, et
                                                             int(packed.stride(0)), M, norms.data_ptr(), eta,
                                                             x.data_ptr(), ghat.data_ptr() if ghat is not None else None,
                                                             _stream_handle(stream)))
+
+
+# ------------------------------------------------------------------------- sign-only messages
+def sign_pack(plan: Plan, grads, packed_out, stream=None) -> None:
+    """packed_out: uint8 CUDA [M][>= D'/8]: every worker's sign plane."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    _check("dq_sign_pack", load_library().dq_sign_pack(plan.handle, grads.data_ptr(), stride, M,
+                                                       packed_out.data_ptr(), int(packed_out.stride(0)),
+                                                       _stream_handle(stream)))
+
+
+def sign_reduce(plan: Plan, packed, out, scales=None, stream=None) -> None:
+    M = int(packed.shape[0])
+    _check("dq_sign_reduce", load_library().dq_sign_reduce(plan.handle, packed.data_ptr(), int(packed.stride(0)), M,
+                                                           scales.data_ptr() if scales is not None else None,
+                                                           out.data_ptr(), _stream_handle(stream)))
+
+
+def sign_majority(plan: Plan, packed, out, stream=None) -> None:
+    M = int(packed.shape[0])
+    _check("dq_sign_majority", load_library().dq_sign_majority(plan.handle, packed.data_ptr(),
+                                                               int(packed.stride(0)), M, out.data_ptr(),
+                                                               _stream_handle(stream)))

@@ -288,6 +288,59 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_v(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Sign-only messages (the one-bit baseline of the paper's Table 2): the sign plane alone.  Same
+// work split with four tiles per workgroup; no random numbers, no norms.
+// HBM traffic per element: 4 bytes read, 1/8 byte written.
+// ---------------------------------------------------------------------------------------------
+constexpr int SP_TILES = 4;
+
+__global__ __launch_bounds__(QP_THREADS) void k_sign_pack(const float* __restrict__ grads, int64_t worker_stride,
+                                                          const int32_t* __restrict__ granule_cseg,
+                                                          const int64_t* __restrict__ cseg_valid_end,
+                                                          int64_t padded_elems, uint8_t* __restrict__ packed,
+                                                          int64_t packed_stride)
+{
+    constexpr int CHUNK = QP_TILE * SP_TILES;
+    __shared__ __align__(16) uint8_t lds_sign[SP_TILES * QP_THREADS];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t w = blockIdx.y;
+    const int64_t chunk0 = static_cast<int64_t>(blockIdx.x) * CHUNK;
+    const uint32_t n_elems = static_cast<uint32_t>(padded_elems - chunk0 < CHUNK ? padded_elems - chunk0 : CHUNK);
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride + chunk0;
+    const int32_t* gseg = granule_cseg + (chunk0 >> 7);
+
+    float4 x[SP_TILES][2];
+    int64_t valid_end[SP_TILES];
+#pragma unroll
+    for (int it = 0; it < SP_TILES; ++it) {
+        uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        e = e < n_elems ? e : n_elems - QP_PER_LANE; // clamped: always in bounds, result unused
+        x[it][0] = *reinterpret_cast<const float4*>(g + e);
+        x[it][1] = *reinterpret_cast<const float4*>(g + e + 4);
+        valid_end[it] = cseg_valid_end[gseg[e >> 7]];
+    }
+#pragma unroll
+    for (int it = 0; it < SP_TILES; ++it) {
+        const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        if (e < n_elems) {
+            const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
+                                 x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
+            uint32_t sign = 0;
+#pragma unroll
+            for (int k = 7; k >= 0; --k) sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31);
+            const int64_t n_valid = valid_end[it] - (chunk0 + e);
+            if (n_valid < QP_PER_LANE) sign &= (1u << (n_valid > 0 ? static_cast<int>(n_valid) : 0)) - 1u;
+            lds_sign[it * QP_THREADS + tid] = static_cast<uint8_t>(sign);
+        }
+    }
+    __syncthreads();
+    uint4* dst = reinterpret_cast<uint4*>(packed + static_cast<int64_t>(w) * packed_stride + (chunk0 >> 3));
+    const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
+    for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+}
+
 template <int B>
 int launch(const dq_plan* plan, const float* grads, int64_t worker_stride, int M, const float* norms,
            uint64_t seed, uint32_t step, uint32_t worker_base, uint8_t* packed, int64_t packed_stride,
@@ -359,5 +412,26 @@ extern "C" int dq_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widt
                        plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table,
                        plan->padded_elems, static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), step,
                        worker_base, packed_dev, packed_worker_stride_bytes);
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
+extern "C" int dq_sign_pack(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
+                            uint8_t* packed_dev, int64_t packed_worker_stride_bytes, void* hip_stream)
+{
+    if (!plan || !grads_dev || !packed_dev) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
+    if (worker_stride_elems < plan->padded_elems || (worker_stride_elems & 3)) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < plan->padded_elems / 8 || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(grads_dev) || !dq_aligned16(packed_dev)) return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    if (plan->padded_elems == 0) return DQ_OK;
+    constexpr int CHUNK = QP_TILE * SP_TILES;
+    const int64_t n_chunks = (plan->padded_elems + CHUNK - 1) / CHUNK;
+    if (n_chunks > INT32_MAX) return DQ_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_sign_pack, dim3(static_cast<unsigned>(n_chunks), M), dim3(QP_THREADS), 0,
+                       static_cast<hipStream_t>(hip_stream), grads_dev, worker_stride_elems, plan->d_granule_cseg,
+                       plan->d_cseg_valid_end, plan->padded_elems, packed_dev, packed_worker_stride_bytes);
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
 }

@@ -267,6 +267,79 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_v(
     finish_tile(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
 }
 
+// Sign-only messages (the one-bit baseline of the paper's Table 2).  MAJORITY: out = sgn of the
+// sum of the workers' signs (exact small integers in binary32).  Otherwise the mean of
+// scale * sgn, summed over workers ascending like the quantized average; scales == nullptr means 1.
+// HBM traffic per output element: M/8 bytes read, 4 bytes written.
+template <bool MAJORITY>
+__global__ __launch_bounds__(UR_THREADS) void k_sign_reduce(
+    const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ scales,
+    int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, float inv_M, float* __restrict__ out)
+{
+    extern __shared__ __align__(16) uint8_t lds_raw[];
+    float4* lds_out = reinterpret_cast<float4*>(lds_raw);
+    float* lds_unit = reinterpret_cast<float*>(lds_raw + UR_TILE * sizeof(float)); // [local seg][M]
+
+    const int tid = threadIdx.x;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * UR_TILE;
+    const int64_t tile_end = tile0 + UR_TILE < padded_elems ? tile0 + UR_TILE : padded_elems;
+    const int64_t P0 = tile0 + tid * UR_PER_LANE;
+    const bool active = P0 < tile_end;
+
+    const int32_t seg_first = granule_cseg[tile0 >> 7];
+    const int32_t seg_last = granule_cseg[(tile_end - 1) >> 7];
+    const int n_local = seg_last - seg_first + 1;
+    for (int i = tid; i < n_local * M; i += UR_THREADS) {
+        const int local = i / M, w = i - local * M;
+        lds_unit[i] = (MAJORITY || !scales) ? 1.0f
+                                            : scales[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + local]];
+    }
+    int local = 0;
+    int64_t n_valid = 0;
+    if (active) {
+        const int32_t c = granule_cseg[P0 >> 7];
+        local = c - seg_first;
+        n_valid = cseg_valid_end[c] - P0;
+    }
+    __syncthreads();
+
+    float acc[UR_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = 0.0f;
+    if (active) {
+        const uint8_t* sign_ptr = packed + (P0 >> 3);
+        const float* unit_ptr = lds_unit + local * M;
+        constexpr int GROUP = 8;
+        int w = 0;
+        for (; w + GROUP <= M; w += GROUP) {
+            uint32_t sg[GROUP];
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i)
+                sg[i] = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w + i) * packed_stride);
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i) {
+                const uint32_t unit = __float_as_uint(unit_ptr[w + i]);
+#pragma unroll
+                for (int k = 0; k < UR_PER_LANE; ++k) // flip the scale's sign where the element's bit is set
+                    acc[k] += __uint_as_float(unit ^ ((sg[i] << (31 - k)) & 0x80000000u));
+            }
+        }
+        for (; w < M; ++w) {
+            const uint32_t sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
+            const uint32_t unit = __float_as_uint(unit_ptr[w]);
+#pragma unroll
+            for (int k = 0; k < UR_PER_LANE; ++k)
+                acc[k] += __uint_as_float(unit ^ ((sg << (31 - k)) & 0x80000000u));
+        }
+        if constexpr (MAJORITY) {
+#pragma unroll
+            for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = acc[k] > 0.0f ? 1.0f : (acc[k] < 0.0f ? -1.0f : 0.0f);
+        }
+    }
+    finish_tile(acc, active, n_valid, MAJORITY ? 1.0f : inv_M, lds_out, tid, tile0, tile_end, out, nullptr, 0.0f);
+}
+
 template <int B>
 int launch(const dq_plan* plan, const uint8_t* packed, int64_t packed_stride, int M, const float* norms,
            float* out, float* x, float eta, hipStream_t stream)
@@ -333,7 +406,49 @@ int reduce_entry_v(const dq_plan_t* plan, const dq_widths_t* widths, const uint8
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
 }
 
+int sign_reduce_entry(bool majority, const dq_plan_t* plan, const uint8_t* packed_dev,
+                      int64_t packed_worker_stride_bytes, int M, const float* scales_dev, float* out_dev,
+                      void* hip_stream)
+{
+    if (!plan || !packed_dev || !out_dev) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < plan->padded_elems / 8 || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(packed_dev) || !dq_aligned16(out_dev) || (reinterpret_cast<uintptr_t>(scales_dev) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    if (plan->padded_elems == 0) return DQ_OK;
+    const int64_t n_tiles = (plan->padded_elems + UR_TILE - 1) / UR_TILE;
+    if (n_tiles > INT32_MAX) return DQ_ERR_INVALID_ARG;
+    const size_t lds_bytes = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(float);
+    const dim3 grid(static_cast<unsigned>(n_tiles)), block(UR_THREADS);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const float inv_M = 1.0f / static_cast<float>(M);
+    if (majority)
+        hipLaunchKernelGGL(k_sign_reduce<true>, grid, block, lds_bytes, stream, packed_dev, packed_worker_stride_bytes,
+                           M, scales_dev, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg,
+                           plan->d_cseg_valid_end, plan->padded_elems, inv_M, out_dev);
+    else
+        hipLaunchKernelGGL(k_sign_reduce<false>, grid, block, lds_bytes, stream, packed_dev, packed_worker_stride_bytes,
+                           M, scales_dev, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg,
+                           plan->d_cseg_valid_end, plan->padded_elems, inv_M, out_dev);
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
 } // namespace
+
+extern "C" int dq_sign_reduce(const dq_plan_t* plan, const uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                              int M, const float* scales_dev, float* out_dev, void* hip_stream)
+{
+    return sign_reduce_entry(false, plan, packed_dev, packed_worker_stride_bytes, M, scales_dev, out_dev, hip_stream);
+}
+
+extern "C" int dq_sign_majority(const dq_plan_t* plan, const uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                                int M, float* out_dev, void* hip_stream)
+{
+    return sign_reduce_entry(true, plan, packed_dev, packed_worker_stride_bytes, M, nullptr, out_dev, hip_stream);
+}
 
 extern "C" int dq_unpack_dequant_reduce_v(const dq_plan_t* plan, const dq_widths_t* widths,
                                           const uint8_t* packed_dev, int64_t packed_worker_stride_bytes, int M,
