@@ -167,32 +167,43 @@ def main() -> None:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    # the reduce pass fused with the model update of Algorithm 1 (x <- x - eta*g_hat), timed on its own
-    x_model = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    def timed_loop(fn, reps: int = 5) -> float:
+        """ms per call, after one untimed call, with events on the stream the kernels run on"""
+        fn()
+        torch.cuda.synchronize()
+        u0, u1 = ev(), ev()
+        u0.record()
+        for _ in range(reps):
+            fn()
+        u1.record()
+        torch.cuda.synchronize()
+        return u0.elapsed_time(u1) / reps
+
+    # the other entry points on the same data, each timed on its own (not part of `value`)
     b_last = marks[-1][0]
     pk_last = packed[:, :plan.packed_bytes(b_last)]
-    dq.unpack_dequant_reduce_update(plan, pk_last, norms_dev, b_last, 1e-3, x_model)
-    torch.cuda.synchronize()
-    u0, u1 = ev(), ev()
-    u0.record()
-    for _ in range(5):
-        dq.unpack_dequant_reduce_update(plan, pk_last, norms_dev, b_last, 1e-3, x_model)
-    u1.record()
-    torch.cuda.synchronize()
-    t_upd = u0.elapsed_time(u1) / 5
+    # reduce fused with the model update of Algorithm 1 (x <- x - eta*g_hat)
+    x_model = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    t_upd = timed_loop(lambda: dq.unpack_dequant_reduce_update(plan, pk_last, norms_dev, b_last, 1e-3, x_model))
     del x_model
-
-    # the max-norm variant of the norm pass (p = infinity in Eq. (5)), timed on its own
+    # max-norm variant of the norm pass (p = infinity in Eq. (5))
     norms_inf = torch.empty_like(norms_dev)
-    dq.norm_linf(plan, grads, norms_inf, ws)
+    t_ninf = timed_loop(lambda: dq.norm_linf(plan, grads, norms_inf, ws))
+    # per-tensor-width kernels at the same widths (every tensor b_last)
+    table = dq.Widths(plan, [b_last] * n_seg)
+    t_qv = timed_loop(lambda: dq.quantize_pack_v(plan, table, grads, norms_dev, wl.QUANT_SEED, T, pk_last))
+    t_rv = timed_loop(lambda: dq.unpack_dequant_reduce_v(plan, table, pk_last, norms_dev, out))
+    table.close()
+    # sign-only baseline (one bit per element)
+    sign_msgs = packed[:, :dp // 8]
+    t_sp = timed_loop(lambda: dq.sign_pack(plan, grads, sign_msgs))
+    t_sr = timed_loop(lambda: dq.sign_reduce(plan, sign_msgs, out))
+    t_sm = timed_loop(lambda: dq.sign_majority(plan, sign_msgs, out))
+    t_ss = timed_loop(lambda: dq.sign_reduce(plan, sign_msgs, out, scales=norms_dev))
+    # leave packed/out as the last step left them for anything that follows
+    dq.quantize_pack(plan, grads, norms_dev, b_last, wl.QUANT_SEED, T - 1, pk_last)
+    dq.unpack_dequant_reduce(plan, pk_last, norms_dev, b_last, out)
     torch.cuda.synchronize()
-    u0, u1 = ev(), ev()
-    u0.record()
-    for _ in range(5):
-        dq.norm_linf(plan, grads, norms_inf, ws)
-    u1.record()
-    torch.cuda.synchronize()
-    t_ninf = u0.elapsed_time(u1) / 5
 
     if args.copy_probe:
         probe = torch.empty_like(out)
@@ -253,6 +264,12 @@ def main() -> None:
             "dq_norm": rl(n_bytes, t_norm),
             "dq_unpack_dequant_reduce_update": rl(dp * (M * (b_last + 1) / 8 + 8), t_upd),
             "dq_norm_linf": rl(n_bytes, t_ninf),
+            "dq_quantize_pack_v": rl(M * dp * (4 + (b_last + 1) / 8), t_qv),
+            "dq_unpack_dequant_reduce_v": rl(dp * (M * (b_last + 1) / 8 + 4), t_rv),
+            "dq_sign_pack": rl(M * dp * (4 + 1 / 8), t_sp),
+            "dq_sign_reduce": rl(dp * (M / 8 + 4), t_sr),
+            "dq_sign_majority": rl(dp * (M / 8 + 4), t_sm),
+            "dq_sign_reduce_scaled": rl(dp * (M / 8 + 4), t_ss),
         },
     }
     # what a kernel with no arithmetic reaches for the same read/write mixes (large workloads only:

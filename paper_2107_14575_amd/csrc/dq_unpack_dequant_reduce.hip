@@ -121,7 +121,9 @@ __device__ __forceinline__ void accumulate_lane(const uint8_t* __restrict__ sign
 }
 
 // Scales a lane's sums by 1/M (zero beyond the tensor's end), transposes the workgroup's tile
-// through LDS and writes it out, with the model update when x is given.
+// through LDS and writes it out; with UPDATE it also applies the model update to x (and then
+// `out` may be null).
+template <bool UPDATE>
 __device__ __forceinline__ void finish_tile(float (&acc)[UR_PER_LANE], bool active, int64_t n_valid, float inv_M,
                                             float4* lds_out, int tid, int64_t tile0, int64_t tile_end,
                                             float* __restrict__ out, float* __restrict__ x, float eta)
@@ -145,8 +147,8 @@ __device__ __forceinline__ void finish_tile(float (&acc)[UR_PER_LANE], bool acti
         const float4 v = wave_out[src_lane * 8 + (q ^ (src_lane & 7))];
         const int64_t P = tile0 + wave * 2048 + 256 * j + 4 * lane;
         if (P < tile_end) {
-            if (out) *reinterpret_cast<float4*>(out + P) = v;
-            if (x) { // model update of Algorithm 1: x <- x - eta * g_hat (pads: g_hat is +0, x unchanged)
+            if (!UPDATE || out) *reinterpret_cast<float4*>(out + P) = v;
+            if constexpr (UPDATE) { // model update of Algorithm 1: x <- x - eta * g_hat (pads: g_hat is +0, x unchanged)
                 float4 xv = *reinterpret_cast<const float4*>(x + P);
                 xv.x = __builtin_fmaf(-eta, v.x, xv.x);
                 xv.y = __builtin_fmaf(-eta, v.y, xv.y);
@@ -158,7 +160,7 @@ __device__ __forceinline__ void finish_tile(float (&acc)[UR_PER_LANE], bool acti
     }
 }
 
-template <int B>
+template <int B, bool UPDATE>
 __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
     const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
     int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
@@ -200,13 +202,14 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
     if (active)
         accumulate_lane<B>(packed + (P0 >> 3), packed + (padded_elems >> 3) + (P0 >> 3) * B, packed_stride, M,
                            lds_unit + local * M, acc);
-    finish_tile(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
+    finish_tile<UPDATE>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
 }
 
 // Per-tensor widths: each lane takes its segment's b and the place of its level dwords from the
 // widths table and runs the accumulation specialised for that b.  A lane's 32 elements lie in one
 // 128-element granule, hence in one segment; lanes of a wave differ in b only where a wave
 // straddles two tensors.
+template <bool UPDATE>
 __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_v(
     const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
     int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
@@ -264,15 +267,13 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_v(
         default: break; // the host only uploads widths in 1..8
         }
     }
-    finish_tile(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
+    finish_tile<UPDATE>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
 }
 
-// Sign-only messages (the one-bit baseline of the paper's Table 2).  MAJORITY: out = sgn of the
-// sum of the workers' signs (exact small integers in binary32).  Otherwise the mean of
-// scale * sgn, summed over workers ascending like the quantized average; scales == nullptr means 1.
+// Sign-only messages (the one-bit baseline of the paper's Table 2): the mean of scale * sgn,
+// summed over workers ascending like the quantized average.
 // HBM traffic per output element: M/8 bytes read, 4 bytes written.
-template <bool MAJORITY>
-__global__ __launch_bounds__(UR_THREADS) void k_sign_reduce(
+__global__ __launch_bounds__(UR_THREADS) void k_sign_reduce_scaled(
     const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ scales,
     int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
     const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, float inv_M, float* __restrict__ out)
@@ -292,8 +293,7 @@ __global__ __launch_bounds__(UR_THREADS) void k_sign_reduce(
     const int n_local = seg_last - seg_first + 1;
     for (int i = tid; i < n_local * M; i += UR_THREADS) {
         const int local = i / M, w = i - local * M;
-        lds_unit[i] = (MAJORITY || !scales) ? 1.0f
-                                            : scales[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + local]];
+        lds_unit[i] = scales[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + local]];
     }
     int local = 0;
     int64_t n_valid = 0;
@@ -332,12 +332,72 @@ __global__ __launch_bounds__(UR_THREADS) void k_sign_reduce(
             for (int k = 0; k < UR_PER_LANE; ++k)
                 acc[k] += __uint_as_float(unit ^ ((sg << (31 - k)) & 0x80000000u));
         }
-        if constexpr (MAJORITY) {
+    }
+    finish_tile<false>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, nullptr, 0.0f);
+}
+
+// Sign-only messages without scales: per element only the number of workers whose bit is set
+// matters.  A lane keeps that count for its 32 elements bit-sliced in PLANES dwords (bit k of
+// plane j = bit j of element k's count, PLANES >= bit length of M) and adds each worker's sign
+// dword with a ripple of half adders -- two bit operations per plane for 32 elements at once.
+// MAJORITY: out = sgn(M - 2*count) in {-1, 0, +1}; otherwise out = (M - 2*count) / M.
+template <int PLANES, bool MAJORITY>
+__global__ __launch_bounds__(UR_THREADS) void k_sign_reduce_count(
+    const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const int32_t* __restrict__ granule_cseg,
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, float inv_M, float* __restrict__ out)
+{
+    extern __shared__ __align__(16) uint8_t lds_raw[];
+    float4* lds_out = reinterpret_cast<float4*>(lds_raw);
+
+    const int tid = threadIdx.x;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * UR_TILE;
+    const int64_t tile_end = tile0 + UR_TILE < padded_elems ? tile0 + UR_TILE : padded_elems;
+    const int64_t P0 = tile0 + tid * UR_PER_LANE;
+    const bool active = P0 < tile_end;
+
+    float acc[UR_PER_LANE];
 #pragma unroll
-            for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = acc[k] > 0.0f ? 1.0f : (acc[k] < 0.0f ? -1.0f : 0.0f);
+    for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = 0.0f;
+    int64_t n_valid = 0;
+    if (active) {
+        n_valid = cseg_valid_end[granule_cseg[P0 >> 7]] - P0;
+        const uint8_t* sign_ptr = packed + (P0 >> 3);
+        uint32_t plane[PLANES];
+#pragma unroll
+        for (int j = 0; j < PLANES; ++j) plane[j] = 0u;
+        auto add = [&](uint32_t carry) {
+#pragma unroll
+            for (int j = 0; j < PLANES; ++j) {
+                const uint32_t t = plane[j] & carry;
+                plane[j] ^= carry;
+                carry = t;
+            }
+        };
+        constexpr int GROUP = 8;
+        int w = 0;
+        for (; w + GROUP <= M; w += GROUP) {
+            uint32_t sg[GROUP];
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i)
+                sg[i] = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w + i) * packed_stride);
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i) add(sg[i]);
+        }
+        for (; w < M; ++w)
+            add(*reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride));
+#pragma unroll
+        for (int k = 0; k < UR_PER_LANE; ++k) {
+            uint32_t count = 0;
+#pragma unroll
+            for (int j = 0; j < PLANES; ++j) count |= __builtin_amdgcn_ubfe(plane[j], k, 1) << j;
+            const int votes = M - 2 * static_cast<int>(count);
+            if constexpr (MAJORITY)
+                acc[k] = votes > 0 ? 1.0f : (votes < 0 ? -1.0f : 0.0f);
+            else
+                acc[k] = static_cast<float>(votes);
         }
     }
-    finish_tile(acc, active, n_valid, MAJORITY ? 1.0f : inv_M, lds_out, tid, tile0, tile_end, out, nullptr, 0.0f);
+    finish_tile<false>(acc, active, n_valid, MAJORITY ? 1.0f : inv_M, lds_out, tid, tile0, tile_end, out, nullptr, 0.0f);
 }
 
 template <int B>
@@ -347,9 +407,16 @@ int launch(const dq_plan* plan, const uint8_t* packed, int64_t packed_stride, in
     const int64_t n_tiles = (plan->padded_elems + UR_TILE - 1) / UR_TILE;
     if (n_tiles > INT32_MAX) return DQ_ERR_INVALID_ARG;
     const size_t lds_bytes = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(float);
-    hipLaunchKernelGGL((k_unpack_dequant_reduce<B>), dim3(static_cast<unsigned>(n_tiles)), dim3(UR_THREADS), lds_bytes,
-                       stream, packed, packed_stride, M, norms, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg,
-                       plan->d_cseg_valid_end, plan->padded_elems, 1.0f / static_cast<float>(M), out, x, eta);
+    const dim3 grid(static_cast<unsigned>(n_tiles)), block(UR_THREADS);
+    const float inv_M = 1.0f / static_cast<float>(M);
+    if (x)
+        hipLaunchKernelGGL((k_unpack_dequant_reduce<B, true>), grid, block, lds_bytes, stream, packed, packed_stride, M,
+                           norms, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end,
+                           plan->padded_elems, inv_M, out, x, eta);
+    else
+        hipLaunchKernelGGL((k_unpack_dequant_reduce<B, false>), grid, block, lds_bytes, stream, packed, packed_stride, M,
+                           norms, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end,
+                           plan->padded_elems, inv_M, out, x, eta);
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
 }
 
@@ -399,10 +466,19 @@ int reduce_entry_v(const dq_plan_t* plan, const dq_widths_t* widths, const uint8
     const int64_t n_tiles = (plan->padded_elems + UR_TILE - 1) / UR_TILE;
     if (n_tiles > INT32_MAX) return DQ_ERR_INVALID_ARG;
     const size_t lds_bytes = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(float);
-    hipLaunchKernelGGL(k_unpack_dequant_reduce_v, dim3(static_cast<unsigned>(n_tiles)), dim3(UR_THREADS), lds_bytes,
-                       static_cast<hipStream_t>(hip_stream), packed_dev, packed_worker_stride_bytes, M, norms_dev,
-                       plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table,
-                       plan->padded_elems, 1.0f / static_cast<float>(M), out_dev, x_dev, eta);
+    const dim3 grid(static_cast<unsigned>(n_tiles)), block(UR_THREADS);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const float inv_M = 1.0f / static_cast<float>(M);
+    if (x_dev)
+        hipLaunchKernelGGL(k_unpack_dequant_reduce_v<true>, grid, block, lds_bytes, stream, packed_dev,
+                           packed_worker_stride_bytes, M, norms_dev, plan->n_seg, plan->d_granule_cseg,
+                           plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table, plan->padded_elems, inv_M,
+                           out_dev, x_dev, eta);
+    else
+        hipLaunchKernelGGL(k_unpack_dequant_reduce_v<false>, grid, block, lds_bytes, stream, packed_dev,
+                           packed_worker_stride_bytes, M, norms_dev, plan->n_seg, plan->d_granule_cseg,
+                           plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table, plan->padded_elems, inv_M,
+                           out_dev, x_dev, eta);
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
 }
 
@@ -421,18 +497,30 @@ int sign_reduce_entry(bool majority, const dq_plan_t* plan, const uint8_t* packe
     if (plan->padded_elems == 0) return DQ_OK;
     const int64_t n_tiles = (plan->padded_elems + UR_TILE - 1) / UR_TILE;
     if (n_tiles > INT32_MAX) return DQ_ERR_INVALID_ARG;
-    const size_t lds_bytes = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(float);
     const dim3 grid(static_cast<unsigned>(n_tiles)), block(UR_THREADS);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const float inv_M = 1.0f / static_cast<float>(M);
-    if (majority)
-        hipLaunchKernelGGL(k_sign_reduce<true>, grid, block, lds_bytes, stream, packed_dev, packed_worker_stride_bytes,
-                           M, scales_dev, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg,
-                           plan->d_cseg_valid_end, plan->padded_elems, inv_M, out_dev);
-    else
-        hipLaunchKernelGGL(k_sign_reduce<false>, grid, block, lds_bytes, stream, packed_dev, packed_worker_stride_bytes,
-                           M, scales_dev, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg,
-                           plan->d_cseg_valid_end, plan->padded_elems, inv_M, out_dev);
+    const size_t tile_bytes = UR_TILE * sizeof(float);
+    if (!majority && scales_dev) {
+        const size_t lds_bytes = tile_bytes + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(float);
+        hipLaunchKernelGGL(k_sign_reduce_scaled, grid, block, lds_bytes, stream, packed_dev,
+                           packed_worker_stride_bytes, M, scales_dev, plan->n_seg, plan->d_granule_cseg,
+                           plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, inv_M, out_dev);
+        return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+    }
+    // planes for the bit-sliced count: the bit length of M, rounded up to 3, 5 or 7 (M <= 64)
+#define DQ_LAUNCH_COUNT(PLANES, MAJ)                                                                              \
+    hipLaunchKernelGGL((k_sign_reduce_count<PLANES, MAJ>), grid, block, tile_bytes, stream, packed_dev,          \
+                       packed_worker_stride_bytes, M, plan->d_granule_cseg, plan->d_cseg_valid_end,              \
+                       plan->padded_elems, inv_M, out_dev)
+    if (M < 8) {
+        if (majority) DQ_LAUNCH_COUNT(3, true); else DQ_LAUNCH_COUNT(3, false);
+    } else if (M < 32) {
+        if (majority) DQ_LAUNCH_COUNT(5, true); else DQ_LAUNCH_COUNT(5, false);
+    } else {
+        if (majority) DQ_LAUNCH_COUNT(7, true); else DQ_LAUNCH_COUNT(7, false);
+    }
+#undef DQ_LAUNCH_COUNT
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
 }
 
