@@ -611,10 +611,12 @@ int dqo_quantize_pack_v(const int64_t *seg_len, int32_t n_seg, const float *grad
     uint8_t *sign = scratch, *level = scratch + (int64_t)M * dp;
     int rc = dqo_quantize_v(seg_len, n_seg, grads, worker_stride, M, norms, b_seg, seed, step, worker_base,
                             sign, level);
-    for (int32_t i = 0; rc == DQO_OK && i < M; ++i)
-        rc = dqo_pack_v(sign + (int64_t)i * dp, level + (int64_t)i * dp, seg_len, n_seg, b_seg,
-                        packed + (int64_t)i * packed_stride);
-    return rc;
+    if (rc != DQO_OK) return rc;
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < M; ++i)
+        dqo_pack_v(sign + (int64_t)i * dp, level + (int64_t)i * dp, seg_len, n_seg, b_seg,
+                   packed + (int64_t)i * packed_stride);
+    return DQO_OK;
 }
 
 int dqo_unpack_dequant_reduce_v(const int64_t *seg_len, int32_t n_seg, const uint8_t *packed,
@@ -625,11 +627,11 @@ int dqo_unpack_dequant_reduce_v(const int64_t *seg_len, int32_t n_seg, const uin
     int64_t dp = dqo_padded_elems(seg_len, n_seg);
     if (dp < 0) return DQO_ERR_INVALID_ARG;
     uint8_t *sign = scratch, *level = scratch + (int64_t)M * dp;
-    int rc = DQO_OK;
-    for (int32_t i = 0; rc == DQO_OK && i < M; ++i)
-        rc = dqo_unpack_v(packed + (int64_t)i * packed_stride, seg_len, n_seg, b_seg, sign + (int64_t)i * dp,
-                          level + (int64_t)i * dp);
-    if (rc != DQO_OK) return rc;
+    if (!widths_ok(b_seg, n_seg)) return DQO_ERR_INVALID_ARG;
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < M; ++i)
+        dqo_unpack_v(packed + (int64_t)i * packed_stride, seg_len, n_seg, b_seg, sign + (int64_t)i * dp,
+                     level + (int64_t)i * dp);
     return dqo_dequant_reduce_v(seg_len, n_seg, sign, level, M, norms, b_seg, out);
 }
 

@@ -160,3 +160,116 @@ def test_config5_large_flat_gradient_sampled(dq, oracle):
         got_sign = np.unpackbits(pk[3, :n // 8].cpu().numpy(), bitorder="little")
         assert np.array_equal(got_sign, np.signbit(g[3, :n].cpu().numpy()).astype(np.uint8))
     plan.close()
+
+
+def test_config3_per_tensor_widths_from_the_rule(dq, oracle):
+    """config 3 at full size (M = 16) with one width per tensor chosen by the per-tensor rule:
+    bitstreams and the average against the oracle in full."""
+    M, T, t, alpha = 16, 100, 80, 0.97
+    seg_len, g = wl.transformer_like(M=M, device="cuda")
+    plan = dq.Plan(seg_len)
+    norms_dev, ws, _, out = _buffers(plan, M, b_max=1)
+    dq.norm(plan, g, norms_dev, ws)
+    torch.cuda.synchronize()
+    norms = norms_dev.cpu().numpy()
+    gbar = float(np.sqrt((norms.astype(np.float64) ** 2).sum() / M))
+    eps_hat = T * alpha ** (T - 1 - t) * (gbar / 200.0) ** 2
+    widths, _ = dq.select_bits_per_tensor(norms, t, T, eps_hat, alpha, 1, 8)
+    assert np.array_equal(widths, oracle.select_bits_per_tensor(norms, t, T, eps_hat, alpha, 1, 8)[0])
+    assert len(set(widths.tolist())) >= 3
+    table = dq.Widths(plan, widths)
+    pk = torch.zeros((M, table.packed_bytes), dtype=torch.uint8, device="cuda")
+    dq.quantize_pack_v(plan, table, g, norms_dev, SEED, t, pk)
+    dq.unpack_dequant_reduce_v(plan, table, pk, norms_dev, out)
+    torch.cuda.synchronize()
+    g_host = np.ascontiguousarray(g.cpu().numpy())
+    want_pk = oracle.quantize_pack_v(seg_len, g_host, norms, widths, SEED, t)
+    assert np.array_equal(pk.cpu().numpy(), want_pk)
+    want_out = oracle.unpack_dequant_reduce_v(seg_len, want_pk, norms, widths)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - want_out)
+    assert err.max() <= 1e-6 * np.abs(want_out).max()
+    table.close()
+    plan.close()
+
+
+def test_config5_other_entry_points_sampled(dq, oracle):
+    """The other entry points at D = 2^28, M = 16: max norm, per-tensor-width kernels at equal
+    widths (must reproduce the single-width kernels' bytes), the fused model update, and the
+    sign-only messages and server rules on sampled ranges plus device-side properties."""
+    D, M, b, step = 1 << 28, 16, 4, 3
+    seg_len, g = wl.flat_student_t(D=D, M=M, device="cuda")
+    plan = dq.Plan(seg_len)
+    norms_dev, ws, packed, out = _buffers(plan, M, b_max=b)
+
+    # max norm: exact, against torch's own reduction for every worker and the oracle for two
+    ninf = torch.empty_like(norms_dev)
+    dq.norm_linf(plan, g, ninf, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ninf[:, 0], g.abs().amax(dim=1))
+    for i in (0, M - 1):
+        want = oracle.norm_linf(seg_len, np.ascontiguousarray(g[i:i + 1].cpu().numpy()))
+        assert float(ninf[i, 0]) == float(want[0, 0])
+
+    # per-tensor-width kernels with equal widths = the single-width kernels, byte for byte
+    dq.norm(plan, g, norms_dev, ws)
+    dq.quantize_pack(plan, g, norms_dev, b, SEED, step, packed)
+    dq.unpack_dequant_reduce(plan, packed, norms_dev, b, out)
+    table = dq.Widths(plan, [b])
+    packed_v = torch.zeros_like(packed)
+    out_v = torch.empty_like(out)
+    dq.quantize_pack_v(plan, table, g, norms_dev, SEED, step, packed_v)
+    dq.unpack_dequant_reduce_v(plan, table, packed_v, norms_dev, out_v)
+    torch.cuda.synchronize()
+    assert torch.equal(packed, packed_v)
+    assert torch.equal(out.view(torch.int32), out_v.view(torch.int32))
+    del packed_v
+
+    # fused update: x - eta*g_hat with one rounding, against torch on the device
+    eta = 0.125
+    x = torch.randn(D, device="cuda")
+    x0 = x.clone()
+    dq.unpack_dequant_reduce_update(plan, packed, norms_dev, b, eta, x)
+    torch.cuda.synchronize()
+    ref = x0.double() - eta * out.double()
+    assert float(((x.double() - ref).abs() - 2.0 ** -24 * ref.abs()).max()) <= 1e-45
+    x.copy_(x0)
+    dq.unpack_dequant_reduce_update_v(plan, table, packed, norms_dev, eta, x)
+    torch.cuda.synchronize()
+    assert float(((x.double() - ref).abs() - 2.0 ** -24 * ref.abs()).max()) <= 1e-45
+    del x, x0, ref, out_v
+    table.close()
+
+    # sign-only: the plane equals the quantizer's sign plane; server rules on sampled ranges
+    signs = torch.zeros((M, D // 8), dtype=torch.uint8, device="cuda")
+    dq.sign_pack(plan, g, signs)
+    torch.cuda.synchronize()
+    assert torch.equal(signs, packed[:, :D // 8])
+    scales = norms_dev / float(np.sqrt(D))
+    results = {}
+    for name in ("mean", "majority", "scaled"):
+        res = torch.empty(D, dtype=torch.float32, device="cuda")
+        if name == "majority":
+            dq.sign_majority(plan, signs, res)
+        else:
+            dq.sign_reduce(plan, signs, res, scales=scales if name == "scaled" else None)
+        results[name] = res
+    torch.cuda.synchronize()
+    sc = scales.cpu().numpy()
+    ranges = [(0, 1 << 16), ((1 << 27) - (1 << 15), (1 << 27) + (1 << 15)), (D - (1 << 16), D),
+              (8192 * 1237 - 128, 8192 * 1237 + 256)]
+    for p0, p1 in ranges:
+        g_slice = np.ascontiguousarray(g[:, p0:p1].cpu().numpy())
+        want_msg = oracle.sign_pack([p1 - p0], g_slice)
+        assert np.array_equal(signs[:, p0 // 8:p1 // 8].cpu().numpy(), want_msg)
+        assert np.array_equal(results["majority"][p0:p1].cpu().numpy(), oracle.sign_reduce([p1 - p0], want_msg, majority=True))
+        got = results["mean"][p0:p1].cpu().numpy().astype(np.float64)
+        assert np.abs(got - oracle.sign_reduce([p1 - p0], want_msg)).max() <= 1e-6
+        got = results["scaled"][p0:p1].cpu().numpy().astype(np.float64)
+        assert np.abs(got - oracle.sign_reduce([p1 - p0], want_msg, scales=sc)).max() <= 1e-6 * float(sc.mean())
+    # any-size property on the device: mean = (M - 2 * negatives) / M, majority = its sign
+    for c0 in range(0, D, 1 << 26):
+        neg = (g[:, c0:c0 + (1 << 26)] < 0).sum(dim=0).to(torch.float32)      # the data has no zeros or NaNs
+        votes = M - 2 * neg
+        assert torch.equal(results["majority"][c0:c0 + (1 << 26)], torch.sign(votes))
+        assert float((results["mean"][c0:c0 + (1 << 26)] - votes / M).abs().max()) <= 1e-6
+    plan.close()
