@@ -129,7 +129,7 @@ int dqo_norm(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t 
 
 /* ------------------------------------------------------------------------------------------- */
 /* O2: the bit rule, Eq. (17), in level-bit convention.                                           */
-/*   G2 = (1/M) sum_i sum_l N_{i,l}^2                  (G-bar_t^2 of Lemma 1)                     */
+/*   G2 = (1/M) sum_i ||g^(i)||^2, ||g^(i)||^2 = sum_l N_{i,l}^2   (G-bar_t^2 of Lemma 1)         */
 /*   s* = sqrt(T/eps_hat) * alpha^((T-1-t)/2) * sqrt(G2)                                          */
 /* Eq. (17) reads b_paper = log2(s* + 1) + 1, i.e. 2^(b_paper-1) - 1 = s*; with b = b_paper - 1   */
 /* and rounding up to an integer this is: the smallest b with 2^b - 1 >= s*, clamped.             */
@@ -142,11 +142,14 @@ int dqo_select_bits(const float *norms /* [M][n_seg] */, int32_t M, int32_t n_se
     if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQO_ERR_INVALID_ARG;
     if (b_min < 1 || b_max > 8 || b_min > b_max) return DQO_ERR_INVALID_ARG;
     double sum = 0.0;
-    for (int32_t i = 0; i < M; ++i)
+    for (int32_t i = 0; i < M; ++i) {
+        double worker_sq = 0.0; /* ||g^(i)||^2 = sum_l N_{i,l}^2: a worker's squared norm first ... */
         for (int32_t l = 0; l < n_seg; ++l) {
             double n = (double)norms[(int64_t)i * n_seg + l];
-            sum += n * n;
+            worker_sq += n * n;
         }
+        sum += worker_sq;       /* ... then the mean over workers, as Lemma 1 writes G-bar_t^2   */
+    }
     double G2 = sum / (double)M;
     double gbar = sqrt(G2);
     double s_star = sqrt((double)T / eps_hat_q) * pow(alpha, (double)(T - 1 - t) / 2.0) * gbar;
