@@ -200,6 +200,25 @@ def main() -> None:
     t_sr = timed_loop(lambda: dq.sign_reduce(plan, sign_msgs, out))
     t_sm = timed_loop(lambda: dq.sign_majority(plan, sign_msgs, out))
     t_ss = timed_loop(lambda: dq.sign_reduce(plan, sign_msgs, out, scales=norms_dev))
+    # the whole step with the rule evaluated on the GPU (no host round trip; per-tensor-width kernels)
+    table = dq.Widths(plan)
+    b_dev = torch.zeros(n_seg, dtype=torch.int32, device="cuda")
+
+    def device_rule_step(t):
+        dq.norm(plan, grads, norms_dev, ws)
+        dq.select_bits_device(plan, table, norms_dev, t, T, eps_hat, alpha, 2, 8, rule="single", b_out=b_dev)
+        dq.quantize_pack_v(plan, table, grads, norms_dev, wl.QUANT_SEED, t, packed)
+        dq.unpack_dequant_reduce_v(plan, table, packed, norms_dev, out)
+
+    device_rule_step(T - 1)
+    torch.cuda.synchronize()
+    t0_dev = time.perf_counter()
+    for t in range(args.warmup, T):
+        device_rule_step(t)
+    torch.cuda.synchronize()
+    ms_device_rule = (time.perf_counter() - t0_dev) / args.steps * 1e3
+    assert int(b_dev[0]) == b_last, "device rule and host rule disagree"
+    table.close()
     # leave packed/out as the last step left them for anything that follows
     dq.quantize_pack(plan, grads, norms_dev, b_last, wl.QUANT_SEED, T - 1, pk_last)
     dq.unpack_dequant_reduce(plan, pk_last, norms_dev, b_last, out)
@@ -272,6 +291,10 @@ def main() -> None:
             "dq_sign_reduce_scaled": rl(dp * (M / 8 + 4), t_ss),
         },
     }
+    result["device_rule_step"] = {
+        "what": "the same step with dq_select_bits_device and the per-tensor-width kernels: no host round trip",
+        "ms_per_step": round(ms_device_rule, 4), "value": round(in_bytes / (ms_device_rule * 1e-3) / 1e9, 2),
+        "unit": "GB/s of fp32 input"}
     # what a kernel with no arithmetic reaches for the same read/write mixes (large workloads only:
     # below 256 MiB the data sits in the Infinity Cache and the figure says nothing about HBM)
     if M * dp * 4 >= (1 << 28):

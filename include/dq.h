@@ -176,6 +176,20 @@ void dq_widths_destroy(dq_widths_t* widths);
 int dq_widths_set(dq_widths_t* widths, const int32_t* b_host, void* hip_stream);
 int64_t dq_widths_packed_bytes(const dq_widths_t* widths); /* for the widths last set; -1 before */
 
+/* The bit rules evaluated on the GPU, so that a step needs no round trip to the host: reads
+ * norms_dev [M][n_seg] and fills `widths` for the kernels enqueued after it on the same stream.
+ *   rule  0: dq_select_bits (one b for every tensor), 1: dq_select_bits_linf, 2: dq_select_bits_per_tensor
+ * Same binary64 arithmetic and summation order as those host functions, hence the same widths.
+ *   b_out_dev            [n_seg] int32 or NULL: the widths chosen (b_min for an empty tensor)
+ *   gbar_out_dev         NULL, or [1] double for rules 0/1 (Gbar), [n_seg] double for rule 2 (Nbar_l)
+ *   packed_bytes_out_dev NULL, or [1] int64: the message size for the widths chosen
+ * Afterwards dq_widths_packed_bytes returns the size for b_max everywhere, the room every message
+ * buffer used with these widths must have. */
+int dq_select_bits_device(const dq_plan_t* plan, dq_widths_t* widths, const float* norms_dev, int M,
+                          int64_t t, int64_t T, double eps_hat_q, double alpha, int b_min, int b_max,
+                          int rule, int32_t* b_out_dev, double* gbar_out_dev,
+                          int64_t* packed_bytes_out_dev, void* hip_stream);
+
 /* dq_quantize_pack, dq_unpack_dequant_reduce and dq_unpack_dequant_reduce_update with the widths
  * of `widths` (created from `plan`, set at least once) in place of b.  Same arithmetic per element
  * with s = 2^(b_l) - 1 for tensor l; packed_worker_stride_bytes >= dq_widths_packed_bytes. */

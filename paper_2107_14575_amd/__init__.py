@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     probe_stream,
     quantize_pack,
     select_bits,
+    select_bits_device,
     sign_majority,
     sign_pack,
     sign_reduce,
@@ -31,5 +32,5 @@ from .binding import (  # noqa: F401
 
 __all__ = ["DQError", "Plan", "Widths", "comm_cost_bits_per_tensor", "packed_bytes_v", "quantize_pack_v",
            "select_bits_per_tensor", "unpack_dequant_reduce_update_v", "unpack_dequant_reduce_v", "alpha_est", "comm_cost_bits", "library_path", "load_library", "norm", "norm_linf",
-           "probe_stream", "quantize_pack", "select_bits", "select_bits_linf", "sign_majority", "sign_pack", "sign_reduce", "unpack_dequant_reduce",
+           "probe_stream", "quantize_pack", "select_bits", "select_bits_device", "select_bits_linf", "sign_majority", "sign_pack", "sign_reduce", "unpack_dequant_reduce",
            "unpack_dequant_reduce_update"]

@@ -21,7 +21,7 @@ EXPORTS = (
     "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
     "dq_unpack_dequant_reduce_update", "dq_select_bits_per_tensor", "dq_packed_bytes_v",
     "dq_comm_cost_bits_per_tensor", "dq_widths_create", "dq_widths_destroy", "dq_widths_set",
-    "dq_widths_packed_bytes", "dq_quantize_pack_v", "dq_unpack_dequant_reduce_v",
+    "dq_widths_packed_bytes", "dq_select_bits_device", "dq_quantize_pack_v", "dq_unpack_dequant_reduce_v",
     "dq_unpack_dequant_reduce_update_v", "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
 )
 
@@ -98,6 +98,9 @@ def load_library():
     L.dq_widths_set.restype = C.c_int
     L.dq_widths_packed_bytes.argtypes = [vp]
     L.dq_widths_packed_bytes.restype = i64
+    L.dq_select_bits_device.argtypes = [vp, vp, vp, C.c_int, i64, i64, C.c_double, C.c_double, C.c_int, C.c_int,
+                                        C.c_int, vp, vp, vp, vp]
+    L.dq_select_bits_device.restype = C.c_int
     L.dq_quantize_pack_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, C.c_uint64, C.c_uint32, C.c_uint32, vp, i64, vp]
     L.dq_quantize_pack_v.restype = C.c_int
     L.dq_unpack_dequant_reduce_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, vp, vp]
@@ -350,6 +353,22 @@ class Widths:
             self.close()
         except Exception:
             pass
+
+
+RULES = {"single": 0, "single_linf": 1, "per_tensor": 2}
+
+
+def select_bits_device(plan: Plan, widths: Widths, norms, t: int, T: int, eps_hat_q: float, alpha: float,
+                       b_min: int, b_max: int, rule: str = "single", b_out=None, gbar_out=None,
+                       packed_bytes_out=None, stream=None) -> None:
+    """The bit rule on the GPU: fills `widths` from norms (CUDA float32 [M][n_seg]) without a host
+    round trip.  b_out: CUDA int32 [n_seg]; gbar_out: CUDA float64 [1] or [n_seg] (per_tensor);
+    packed_bytes_out: CUDA int64 [1]; all optional."""
+    ptr = lambda x: x.data_ptr() if x is not None else None
+    _check("dq_select_bits_device",
+           load_library().dq_select_bits_device(plan.handle, widths.handle, norms.data_ptr(), int(norms.shape[0]),
+                                                t, T, eps_hat_q, alpha, b_min, b_max, RULES[rule], ptr(b_out),
+                                                ptr(gbar_out), ptr(packed_bytes_out), _stream_handle(stream)))
 
 
 def quantize_pack_v(plan: Plan, widths: Widths, grads, norms, seed: int, step: int, packed_out,

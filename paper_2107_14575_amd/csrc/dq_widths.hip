@@ -18,6 +18,106 @@ namespace {
 
 int64_t padded_len(int64_t len) { return (len + DQ_GRANULE - 1) / DQ_GRANULE * DQ_GRANULE; }
 
+constexpr int SB_THREADS = 256;
+
+__device__ __forceinline__ int smallest_width(double s_star, int b_min, int b_max)
+{
+    int b = b_max;
+    for (int cand = b_max; cand >= b_min; --cand) // same result as the ascending search: the levels grow with cand
+        if (static_cast<double>((1 << cand) - 1) >= s_star) b = cand;
+    return b;
+}
+
+// The bit rules on the device, in the arithmetic of the host functions (binary64, a worker's or a
+// tensor's squares added in index order; products of binary32 norms are exact), so that a step
+// needs no round trip to the host: one workgroup reads the M x n_seg norms, decides the widths,
+// and fills the widths table (b and, by a scan over the tensors, where each tensor's level bytes
+// start).  rule: 0 = Eq. (17) with the l2 norms, 1 = with max norms, 2 = one width per tensor.
+__global__ __launch_bounds__(SB_THREADS) void k_select_bits(
+    const float* __restrict__ norms, int M, int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, dq_cseg_width* __restrict__ table, int rule, double root_T_eps,
+    double weight, int b_min, int b_max, int64_t sign_bytes, int32_t* __restrict__ b_out,
+    double* __restrict__ gbar_out, int64_t* __restrict__ packed_bytes_out)
+{
+    __shared__ double worker_sq[DQ_MAX_WORKERS];
+    __shared__ int b_all;
+    __shared__ int64_t scan[SB_THREADS];
+    __shared__ int64_t carry;
+    const int tid = threadIdx.x;
+    const double factor = root_T_eps * weight;
+
+    if (rule != 2) {
+        if (tid < M) {
+            const float* row = norms + static_cast<int64_t>(tid) * n_seg;
+            double acc = 0.0;
+            for (int32_t l = 0; l < n_seg; ++l) {
+                const double sq = static_cast<double>(row[l]) * static_cast<double>(row[l]);
+                if (rule == 1)
+                    acc = sq > acc ? sq : acc;
+                else
+                    acc += sq;
+            }
+            worker_sq[tid] = acc;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double sum_sq = 0.0;
+            for (int i = 0; i < M; ++i) sum_sq += worker_sq[i];
+            const double gbar = sqrt(sum_sq / static_cast<double>(M));
+            b_all = smallest_width(factor * gbar, b_min, b_max);
+            if (gbar_out) gbar_out[0] = gbar;
+        }
+        __syncthreads();
+        const int b = b_all;
+        if (b_out)
+            for (int32_t l = tid; l < n_seg; l += SB_THREADS) b_out[l] = b;
+        for (int32_t c = tid; c < n_cseg; c += SB_THREADS) table[c].b = b;
+    } else {
+        auto tensor_width = [&](int32_t l, double* nbar_out) {
+            double acc = 0.0;
+            for (int i = 0; i < M; ++i) {
+                const double n = static_cast<double>(norms[static_cast<int64_t>(i) * n_seg + l]);
+                acc += n * n;
+            }
+            const double nbar = sqrt(acc / static_cast<double>(M));
+            if (nbar_out) *nbar_out = nbar;
+            return smallest_width(factor * nbar, b_min, b_max);
+        };
+        if (b_out || gbar_out)
+            for (int32_t l = tid; l < n_seg; l += SB_THREADS) {
+                const int b = tensor_width(l, gbar_out ? gbar_out + l : nullptr);
+                if (b_out) b_out[l] = b;
+            }
+        for (int32_t c = tid; c < n_cseg; c += SB_THREADS) table[c].b = tensor_width(cseg_seg[c], nullptr);
+    }
+    if (tid == 0) carry = 0;
+    __syncthreads();
+
+    // exclusive scan of the tensors' level bytes, 256 tensors per round; thread tid reads back the
+    // width it wrote itself
+    for (int32_t base = 0; base < n_cseg; base += SB_THREADS) {
+        const int32_t c = base + tid;
+        int64_t mine = 0;
+        if (c < n_cseg) {
+            const int64_t len = cseg_valid_end[c] - table[c].seg_start;
+            mine = (len + DQ_GRANULE - 1) / DQ_GRANULE * (DQ_GRANULE / 8) * table[c].b;
+        }
+        scan[tid] = mine;
+        __syncthreads();
+        for (int off = 1; off < SB_THREADS; off <<= 1) {
+            const int64_t add = tid >= off ? scan[tid - off] : 0;
+            __syncthreads();
+            scan[tid] += add;
+            __syncthreads();
+        }
+        if (c < n_cseg) table[c].level_start = carry + scan[tid] - mine;
+        __syncthreads();
+        if (tid == 0) carry += scan[SB_THREADS - 1];
+        __syncthreads();
+    }
+    if (tid == 0 && packed_bytes_out) *packed_bytes_out = sign_bytes + carry;
+}
+
 } // namespace
 
 extern "C" int dq_select_bits_per_tensor(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
@@ -91,6 +191,20 @@ extern "C" int dq_widths_create(const dq_plan_t* plan, dq_widths_t** widths_out)
     ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_table), bytes) == hipSuccess;
     ok = ok && hipHostMalloc(reinterpret_cast<void**>(&w->h_stage), bytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&w->uploaded, hipEventDisableTiming) == hipSuccess;
+    if (ok) {
+        // the fixed part of the table (where each tensor starts); widths come later
+        int32_t c = 0;
+        for (int32_t l = 0; l < plan->n_seg; ++l) {
+            if (plan->seg_len[l] == 0) continue;
+            w->h_stage[c].level_start = 0;
+            w->h_stage[c].seg_start = plan->seg_start[l];
+            w->h_stage[c].b = 0;
+            w->h_stage[c].reserved = 0;
+            ++c;
+        }
+        ok = c == 0 || hipMemcpy(w->d_table, w->h_stage, sizeof(dq_cseg_width) * static_cast<size_t>(c),
+                                 hipMemcpyHostToDevice) == hipSuccess;
+    }
     if (!ok) {
         (void)hipGetLastError();
         dq_widths_destroy(w);
@@ -150,3 +264,34 @@ extern "C" int dq_widths_set(dq_widths_t* w, const int32_t* b_host, void* hip_st
 }
 
 extern "C" int64_t dq_widths_packed_bytes(const dq_widths_t* w) { return w ? w->packed_bytes : -1; }
+
+extern "C" int dq_select_bits_device(const dq_plan_t* plan, dq_widths_t* widths, const float* norms_dev, int M,
+                                     int64_t t, int64_t T, double eps_hat_q, double alpha, int b_min, int b_max,
+                                     int rule, int32_t* b_out_dev, double* gbar_out_dev,
+                                     int64_t* packed_bytes_out_dev, void* hip_stream)
+{
+    if (!plan || !widths || !norms_dev || widths->plan != plan) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS || T < 1 || t < 0 || t >= T) return DQ_ERR_INVALID_ARG;
+    if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQ_ERR_INVALID_ARG;
+    if (b_min < 1 || b_max > 8 || b_min > b_max || rule < 0 || rule > 2) return DQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(norms_dev) & 3u) || (reinterpret_cast<uintptr_t>(b_out_dev) & 3u) ||
+        (reinterpret_cast<uintptr_t>(gbar_out_dev) & 7u) || (reinterpret_cast<uintptr_t>(packed_bytes_out_dev) & 7u))
+        return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    const double root_T_eps = sqrt(static_cast<double>(T) / eps_hat_q);
+    const double weight = pow(alpha, static_cast<double>(T - 1 - t) / 2.0);
+    hipLaunchKernelGGL(k_select_bits, dim3(1), dim3(SB_THREADS), 0, static_cast<hipStream_t>(hip_stream), norms_dev,
+                       M, plan->n_seg, plan->n_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table, rule,
+                       root_T_eps, weight, b_min, b_max, plan->padded_elems / 8, b_out_dev, gbar_out_dev,
+                       packed_bytes_out_dev);
+    if (hipGetLastError() != hipSuccess) return DQ_ERR_HIP;
+    // the host no longer knows the widths: messages must have room for b_max everywhere
+    int64_t level_bytes = 0;
+    for (int32_t l = 0; l < plan->n_seg; ++l) {
+        widths->b_host[l] = 0;
+        level_bytes += padded_len(plan->seg_len[l]) / 8 * b_max;
+    }
+    widths->packed_bytes = plan->padded_elems / 8 + level_bytes;
+    return DQ_OK;
+}

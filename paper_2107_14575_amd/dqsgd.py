@@ -16,6 +16,8 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
   * per_tensor=True: one bit-width per tensor from ``dq_select_bits_per_tensor`` (b0, b_t in the
     result and on_step's b are then arrays of n_seg widths), messages in the per-tensor layout,
     through the ``*_v`` entry points.
+  * device_rule=True: the rule runs on the GPU (``dq_select_bits_device``) and the loop never waits
+    for the host; b_t and the cost are read back once at the end.  alpha must be a number.
   * p: 2 or "inf", the norm of Eq. (5) (the paper leaves p open): ``dq_norm``/``dq_select_bits`` or
     ``dq_norm_linf``/``dq_select_bits_linf``.
 """
@@ -42,7 +44,8 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         M: int, T: int, eta: float, eps_hat_q: float, alpha: Union[float, str], b0: int,
         b_min: int = 1, b_max: int = 8, tau: int = 1, lagged: bool = True, seed: int = 0,
         loss_fn: Optional[Callable[["torch.Tensor"], float]] = None, B_pre: int = 32,
-        on_step: Optional[Callable] = None, p: Union[int, str] = 2, per_tensor: bool = False) -> DQSGDResult:
+        on_step: Optional[Callable] = None, p: Union[int, str] = 2, per_tensor: bool = False,
+        device_rule: bool = False) -> DQSGDResult:
     """grad_fn(t, x, grads_out) fills grads_out[M][D'] (float32, CUDA, padded layout) with the M
     workers' stochastic gradients at x.  on_step(t, b_t, grads, norms_host, packed) is called after
     the quantize pass of every iteration (tests use it to feed the same bytes to the oracle)."""
@@ -50,6 +53,12 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         raise ValueError('p must be 2 or "inf"')
     norm_fn, rule = (_b.norm, _b.select_bits) if p == 2 else (_b.norm_linf, _b.select_bits_linf)
     dp, n_seg = plan.padded_elems, plan.n_seg
+    if device_rule:
+        if per_tensor and p != 2:
+            raise ValueError("per_tensor uses the tensors' own norms: leave p at 2 or run the max norm without it")
+        rule_name = "per_tensor" if per_tensor else ("single" if p == 2 else "single_linf")
+        return _run_device_rule(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged,
+                                seed, B_pre, on_step, norm_fn, rule_name)
     if per_tensor:
         return _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged,
                                seed, B_pre, on_step, norm_fn)
@@ -136,4 +145,66 @@ def _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b
             table.set(b)
     torch.cuda.synchronize()
     table.close()
+    return res
+
+
+def _run_device_rule(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged, seed, B_pre,
+                     on_step, norm_fn, rule_name) -> DQSGDResult:
+    import numpy as np
+    if alpha == "estimate":
+        raise ValueError('alpha="estimate" needs the loss on the host: not available with device_rule')
+    alpha = float(alpha)
+    dp, n_seg = plan.padded_elems, plan.n_seg
+    dev = x0.device
+    x = x0.clone()
+    grads = torch.zeros((M, dp), dtype=torch.float32, device=dev)
+    norms = torch.empty((M, n_seg), dtype=torch.float32, device=dev)
+    ws = torch.empty(plan.workspace_bytes(M), dtype=torch.uint8, device=dev)
+    packed = torch.zeros((M, _b.packed_bytes_v(plan, [b_max] * n_seg)), dtype=torch.uint8, device=dev)
+    # per iteration: the widths used and G-bar (single rules) / the tensors' Nbar (per tensor)
+    b_hist = torch.zeros((T, n_seg), dtype=torch.int32, device=dev)
+    g_cols = n_seg if rule_name == "per_tensor" else 1
+    g_hist = torch.zeros((T, g_cols), dtype=torch.float64, device=dev)
+    b_cur = torch.from_numpy(np.broadcast_to(np.asarray(b0, dtype=np.int32), (n_seg,)).copy()).to(dev)
+    table = _b.Widths(plan, b_cur.cpu().numpy())
+    unused = _b.Widths(plan)
+    for t in range(T):
+        grad_fn(t, x, grads)
+        norm_fn(plan, grads, norms, ws)
+        if not lagged:
+            _b.select_bits_device(plan, table, norms, t, T, eps_hat_q, alpha, b_min, b_max, rule=rule_name,
+                                  b_out=b_hist[t], gbar_out=g_hist[t])
+        else:
+            b_hist[t].copy_(b_cur)
+        _b.quantize_pack_v(plan, table, grads, norms, seed, t, packed)
+        if on_step is not None:
+            torch.cuda.current_stream().synchronize()
+            b_now = b_hist[t].cpu().numpy()
+            on_step(t, b_now if rule_name == "per_tensor" else int(b_now[0]), grads, norms.cpu().numpy(),
+                    packed[:, :_b.packed_bytes_v(plan, b_now)])
+        _b.unpack_dequant_reduce_update_v(plan, table, packed, norms, eta, x)
+        if lagged:
+            # at the update points b_{t+1} comes from these norms with index t+1; otherwise the rule
+            # only serves the record of G-bar and fills a table nothing reads
+            if t + 1 < T and (t + 1) % tau == 0:
+                _b.select_bits_device(plan, table, norms, t + 1, T, eps_hat_q, alpha, b_min, b_max,
+                                      rule=rule_name, b_out=b_cur, gbar_out=g_hist[t])
+            else:
+                _b.select_bits_device(plan, unused, norms, t, T, eps_hat_q, alpha, b_min, b_max,
+                                      rule=rule_name, gbar_out=g_hist[t])
+    torch.cuda.synchronize()
+    table.close()
+    unused.close()
+    res = DQSGDResult(x=x)
+    b_host = b_hist.cpu().numpy()
+    g_host = g_hist.cpu().numpy()
+    for t in range(T):
+        if rule_name == "per_tensor":
+            res.bits.append(b_host[t].copy())
+            res.cost_bits += _b.comm_cost_bits_per_tensor(M, plan.seg_len, b_host[t], B_pre)
+            res.gbar.append(float(np.sqrt((g_host[t] ** 2).sum())))
+        else:
+            res.bits.append(int(b_host[t, 0]))
+            res.cost_bits += _b.comm_cost_bits(M, int(plan.seg_len.sum()), int(b_host[t, 0]), n_seg, B_pre)
+            res.gbar.append(float(g_host[t, 0]))
     return res
