@@ -266,6 +266,27 @@ def main() -> None:
                 "frac": round(a / HBM_PEAK_GBS, 4), "traffic": None, "avg_ms": round(ms, 4),
                 "algorithmic_bytes_per_launch": int(bytes_)}
 
+    def profiled_traffic(kernel_tag: str):
+        """HBM bytes per launch from the committed rocprofv3 counter summary of this kernel, when
+        one exists for exactly this workload (FETCH_SIZE + WRITE_SIZE passes, scaled by a plain
+        copy; the counters cannot be read from inside this process).  None otherwise."""
+        import os
+        import re
+        if args.workload != "flat_student_t" or len(set(bits)) != 1:
+            return None
+        name = f"{kernel_tag}__flat_student_t_d2p{dp.bit_length() - 1}_m{M}_b{bits[0]}.txt"
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", name)
+        try:
+            text = open(path).read()
+        except OSError:
+            return None
+        rd = re.search(r"FETCH_SIZE mean \d+ -> ([0-9.]+) GB read", text)
+        wr = re.search(r"WRITE_SIZE mean \d+ -> ([0-9.]+) GB written", text)
+        if not rd or not wr:
+            return None
+        return {"bytes": int((float(rd.group(1)) + float(wr.group(1))) * 1e9), "read_GB": float(rd.group(1)),
+                "written_GB": float(wr.group(1)), "source": "profiles/" + name}
+
     result = {
         "metric": "quantize+pack and unpack+dequant+reduce GB/s (fp32 in) and % of HBM peak",
         "value": round(value, 2),
@@ -291,6 +312,7 @@ def main() -> None:
             "dq_sign_reduce_scaled": rl(dp * (M / 8 + 4), t_ss),
         },
     }
+    result["roofline"]["traffic"] = profiled_traffic("k_quantize_pack")
     result["device_rule_step"] = {
         "what": "the same step with dq_select_bits_device and the per-tensor-width kernels: no host round trip",
         "ms_per_step": round(ms_device_rule, 4), "value": round(in_bytes / (ms_device_rule * 1e-3) / 1e9, 2),

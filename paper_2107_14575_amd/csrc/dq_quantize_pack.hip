@@ -267,8 +267,19 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_v(
                 level &= (static_cast<uint64_t>(1) << (nv * b)) - 1u;
             }
             lds_sign[it * QP_THREADS + tid] = static_cast<uint8_t>(sign);
-            uint8_t* dst = &lds_level[lds_level_base[local] + static_cast<int32_t>(e >> 3) * b]; // b bytes
-            for (int k = 0; k < b; ++k) dst[k] = static_cast<uint8_t>(level >> (8 * k));
+            // b bytes at an offset that is a multiple of b past a 16-byte boundary (every tensor's
+            // stretch of a chunk starts on one), so the naturally aligned stores of stage_bytes apply
+            uint8_t* dst = &lds_level[lds_level_base[local] + static_cast<int32_t>(e >> 3) * b];
+            switch (b) {
+            case 1: stage_bytes<1>(dst, level); break;
+            case 2: stage_bytes<2>(dst, level); break;
+            case 3: stage_bytes<3>(dst, level); break;
+            case 4: stage_bytes<4>(dst, level); break;
+            case 5: stage_bytes<5>(dst, level); break;
+            case 6: stage_bytes<6>(dst, level); break;
+            case 7: stage_bytes<7>(dst, level); break;
+            default: stage_bytes<8>(dst, level); break;
+            }
         }
     }
     __syncthreads();
