@@ -70,6 +70,11 @@ int64_t dq_plan_segment_start(const dq_plan_t* plan, int32_t l);   /* P_l; -1 if
 int64_t dq_packed_bytes(const dq_plan_t* plan, int b);             /* per worker: D'/8 + D'*b/8; -1 on bad b */
 int64_t dq_workspace_bytes(const dq_plan_t* plan, int M);          /* scratch dq_norm needs; -1 on bad M */
 int dq_plan_has_device(const dq_plan_t* plan);                     /* 1 if the tables are on a GPU    */
+/* 1 if no tensor crosses a multiple of 4096 in the padded index space -- e.g. a gradient cut into
+ * buckets of 128*2^k <= 4096 elements, the practice of the scheme the paper builds on, or small
+ * tensors laid out that way.  For such "chunk-local" plans dq_norm finishes every norm in one pass
+ * however small the tensors, and dq_norm_quantize_pack is available. */
+int dq_plan_is_chunk_local(const dq_plan_t* plan);
 
 /* N[i][l] = ||g_l^(i)||_2, the norm of Eq. (5) (p = 2), for worker i's tensor l.
  *   grads_dev            [M] gradients in padded layout, worker i at grads_dev + i*worker_stride_elems
@@ -118,6 +123,18 @@ int dq_quantize_pack(const dq_plan_t* plan, const float* grads_dev, int64_t work
                      int M, const float* norms_dev, int b, uint64_t seed, uint32_t step,
                      uint32_t worker_base, uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
                      void* hip_stream);
+
+/* dq_norm (linf = 0) or dq_norm_linf (linf != 0) and dq_quantize_pack in one pass over the
+ * gradient, for chunk-local plans and a bit-width that is already known (Algorithm 1: the worker
+ * received b_t with x_t): every workgroup computes the norms of the tensors in its 4096-element
+ * chunk from the values it holds in registers and quantizes them straight away, so the gradient
+ * is read once, 4 + (b+1)/8 bytes per element in all.  norms_dev [M][n_seg] is written (the same
+ * values dq_norm gives for this plan); the messages are those of dq_quantize_pack for these norms.
+ * DQ_ERR_INVALID_ARG when the plan is not chunk-local. */
+int dq_norm_quantize_pack(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                          int M, int linf, int b, uint64_t seed, uint32_t step, uint32_t worker_base,
+                          float* norms_dev, uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                          void* hip_stream);
 
 /* Server side of Algorithm 1: out_P = (1/M) sum_i sgn_{i,P} * level_{i,P} * (N[i][l] / s), every
  * worker's message read once.  The sum runs in binary32 over i ascending, then times 1/M.

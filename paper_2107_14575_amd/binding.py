@@ -18,6 +18,7 @@ MAX_WORKERS = 64
 EXPORTS = (
     "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems",
     "dq_plan_segment_start", "dq_packed_bytes", "dq_workspace_bytes", "dq_plan_has_device",
+    "dq_plan_is_chunk_local", "dq_norm_quantize_pack",
     "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
     "dq_unpack_dequant_reduce_update", "dq_select_bits_per_tensor", "dq_packed_bytes_v",
     "dq_comm_cost_bits_per_tensor", "dq_widths_create", "dq_widths_destroy", "dq_widths_set",
@@ -66,6 +67,11 @@ def load_library():
     L.dq_workspace_bytes.restype = i64
     L.dq_plan_has_device.argtypes = [vp]
     L.dq_plan_has_device.restype = C.c_int
+    L.dq_plan_is_chunk_local.argtypes = [vp]
+    L.dq_plan_is_chunk_local.restype = C.c_int
+    L.dq_norm_quantize_pack.argtypes = [vp, vp, i64, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
+                                        vp, vp, i64, vp]
+    L.dq_norm_quantize_pack.restype = C.c_int
     L.dq_norm.argtypes = [vp, vp, i64, C.c_int, vp, vp, vp]
     L.dq_norm.restype = C.c_int
     L.dq_norm_linf.argtypes = [vp, vp, i64, C.c_int, vp, vp, vp]
@@ -178,6 +184,10 @@ class Plan:
     def has_device(self) -> bool:
         return bool(load_library().dq_plan_has_device(self.handle))
 
+    @property
+    def chunk_local(self) -> bool:
+        return bool(load_library().dq_plan_is_chunk_local(self.handle))
+
     def segment_start(self, l: int) -> int:
         return int(load_library().dq_plan_segment_start(self.handle, l))
 
@@ -225,6 +235,16 @@ def select_bits(norms_host, t: int, T: int, eps_hat_q: float, alpha: float, b_mi
 def select_bits_linf(norms_host, t: int, T: int, eps_hat_q: float, alpha: float, b_min: int, b_max: int):
     """select_bits for norms from norm_linf."""
     return _select_bits("dq_select_bits_linf", norms_host, t, T, eps_hat_q, alpha, b_min, b_max)
+
+
+def norm_quantize_pack(plan: Plan, grads, b: int, seed: int, step: int, norms_out, packed_out,
+                       worker_base: int = 0, linf: bool = False, stream=None) -> None:
+    """One pass over the gradient for chunk-local plans: norms (written to norms_out) and messages."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    _check("dq_norm_quantize_pack",
+           load_library().dq_norm_quantize_pack(plan.handle, grads.data_ptr(), stride, M, 1 if linf else 0, b, seed,
+                                                step, worker_base, norms_out.data_ptr(), packed_out.data_ptr(),
+                                                int(packed_out.stride(0)), _stream_handle(stream)))
 
 
 def quantize_pack(plan: Plan, grads, norms, b: int, seed: int, step: int, packed_out,

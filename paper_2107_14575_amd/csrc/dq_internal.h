@@ -23,6 +23,7 @@ struct dq_plan {
     int32_t n_items;      // norm work items
     int device;           // HIP device the tables live on, -1 if none
     int32_t n_cseg;       // number of non-empty segments
+    bool chunk_local;     // no segment crosses a multiple of 4096 in the padded index space
     // device tables.  Kernels address segments through a compact index c that counts only the
     // non-empty ones, so consecutive granules differ by at most one in c.
     int32_t* d_granule_cseg;       // [D'/128]  compact segment index of each 128-element granule
@@ -30,6 +31,8 @@ struct dq_plan {
     int64_t* d_cseg_valid_end;     // [n_nonempty] P_l + len_l: first padded index past the data
     dq_norm_item* d_items;         // [n_items]
     int32_t* d_seg_item_begin;     // [n_seg + 1] items of segment l are [begin[l], begin[l+1])
+    int32_t* d_finish_seg;         // [n_finish] segments whose norm needs the finishing kernel: all but
+    int32_t n_finish;              //            those of exactly one item (the first kernel finishes these)
 };
 
 // Per-tensor bit-widths (dq_widths_*): one entry per non-empty segment, indexed like the plan's
@@ -51,6 +54,9 @@ struct dq_widths {
 };
 
 static inline bool dq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Fills n floats with +0 (a kernel, not a memset: callers may capture the entry points in a graph).
+int dq_zero_floats(float* dst_dev, int64_t n, hipStream_t stream);
 
 // Checks shared by the device entry points; returns DQ_OK when `plan` can launch work on its GPU
 // and makes that GPU current.

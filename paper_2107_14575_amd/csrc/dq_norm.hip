@@ -5,9 +5,13 @@
 // of up to 4096 valid elements in binary64 (squares of binary32 values are exact there): per-lane
 // partial, wavefront shuffle tree, then the four wave sums through LDS in wave order.  Pass 2: one
 // workgroup per (segment, worker) adds that segment's item partials in a fixed order and takes
-// the square root.  HBM traffic: 4 bytes read per element, plus 8 bytes per 4096 elements.
+// the square root.  A segment of a single item (at most 4096 elements) is finished by pass 1
+// itself -- the same value, since its sum has one term -- so a gradient cut into many small
+// tensors costs no second-pass workgroups.  HBM traffic: 4 bytes read per element, plus 8 bytes
+// per 4096 elements.
 // The max norm takes the same two passes with binary32 maxima in place of the binary64 sums (a
 // maximum does not depend on the order; a NaN element never wins a comparison).
+#include "dq_chunk_norm.h"
 #include "dq_internal.h"
 
 namespace {
@@ -39,7 +43,9 @@ template <bool LINF>
 __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ grads,
                                                       int64_t worker_stride,
                                                       const dq_norm_item* __restrict__ items,
-                                                      int32_t n_items, void* __restrict__ partial_out)
+                                                      int32_t n_items, void* __restrict__ partial_out,
+                                                      const int32_t* __restrict__ seg_item_begin, int32_t n_seg,
+                                                      float* __restrict__ norms)
 {
     __shared__ double wave_part[4];
     const int item_id = blockIdx.x;
@@ -74,7 +80,10 @@ __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ 
             float top = wave_m[0];
 #pragma unroll
             for (int k = 1; k < 4; ++k) top = wave_m[k] > top ? wave_m[k] : top;
-            static_cast<float*>(partial_out)[static_cast<int64_t>(w) * n_items + item_id] = top;
+            if (seg_item_begin[item.seg + 1] - seg_item_begin[item.seg] == 1)
+                norms[static_cast<int64_t>(w) * n_seg + item.seg] = top;
+            else
+                static_cast<float*>(partial_out)[static_cast<int64_t>(w) * n_items + item_id] = top;
         }
         return;
     }
@@ -95,19 +104,24 @@ __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ 
     acc = wave_sum(acc);
     if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
     __syncthreads();
-    if (tid == 0)
-        partial[static_cast<int64_t>(w) * n_items + item_id] =
-            ((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3];
+    if (tid == 0) {
+        const double total = ((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3];
+        if (seg_item_begin[item.seg + 1] - seg_item_begin[item.seg] == 1)
+            norms[static_cast<int64_t>(w) * n_seg + item.seg] = static_cast<float>(sqrt(total));
+        else
+            partial[static_cast<int64_t>(w) * n_items + item_id] = total;
+    }
 }
 
 constexpr int FINISH_THREADS = 1024;
 
 __global__ __launch_bounds__(FINISH_THREADS) void k_norm_finish(const double* __restrict__ partial, int32_t n_items,
                                                                 const int32_t* __restrict__ seg_item_begin,
+                                                                const int32_t* __restrict__ finish_seg,
                                                                 int32_t n_seg, float* __restrict__ norms)
 {
     __shared__ double wave_part[FINISH_THREADS / 64];
-    const int seg = blockIdx.x;
+    const int seg = finish_seg[blockIdx.x];
     const int w = blockIdx.y;
     const int tid = threadIdx.x;
     const int begin = seg_item_begin[seg], end = seg_item_begin[seg + 1];
@@ -136,10 +150,11 @@ __global__ __launch_bounds__(FINISH_THREADS) void k_norm_finish(const double* __
 
 __global__ __launch_bounds__(FINISH_THREADS) void k_norm_linf_finish(const float* __restrict__ partial, int32_t n_items,
                                                                      const int32_t* __restrict__ seg_item_begin,
+                                                                     const int32_t* __restrict__ finish_seg,
                                                                      int32_t n_seg, float* __restrict__ norms)
 {
     __shared__ float wave_m[FINISH_THREADS / 64];
-    const int seg = blockIdx.x;
+    const int seg = finish_seg[blockIdx.x];
     const int w = blockIdx.y;
     const int tid = threadIdx.x;
     const int begin = seg_item_begin[seg], end = seg_item_begin[seg + 1];
@@ -165,10 +180,71 @@ __global__ __launch_bounds__(FINISH_THREADS) void k_norm_linf_finish(const float
     }
 }
 
+// Chunk-local plans: one workgroup per 4096-element chunk finishes the norms of all the tensors
+// inside it, however small they are; no second pass.
+template <bool LINF>
+__global__ __launch_bounds__(256) void k_norm_chunk(const float* __restrict__ grads, int64_t worker_stride,
+                                                    const int32_t* __restrict__ granule_cseg,
+                                                    const int32_t* __restrict__ cseg_seg,
+                                                    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems,
+                                                    int32_t n_seg, float* __restrict__ norms)
+{
+    __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
+    __shared__ float lds_norm[DQ_CHUNK_GRANULES];
+    __shared__ int32_t lds_valid_end[DQ_CHUNK_GRANULES];
+    const int tid = threadIdx.x;
+    const int w = blockIdx.y;
+    const int64_t chunk0 = static_cast<int64_t>(blockIdx.x) * DQ_CHUNK;
+    const uint32_t n_elems = static_cast<uint32_t>(padded_elems - chunk0 < DQ_CHUNK ? padded_elems - chunk0 : DQ_CHUNK);
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride + chunk0;
+    const int32_t* gseg = granule_cseg + (chunk0 >> 7);
+
+    float4 x[2][2];
+    int32_t seg[2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        uint32_t e = it * 2048 + tid * 8;
+        e = e < n_elems ? e : n_elems - 8; // clamped: always in bounds, masked out below
+        x[it][0] = *reinterpret_cast<const float4*>(g + e);
+        x[it][1] = *reinterpret_cast<const float4*>(g + e + 4);
+        seg[it] = gseg[e >> 7];
+    }
+    const int32_t seg_first = gseg[0];
+    const int n_local = gseg[(n_elems - 1) >> 7] - seg_first + 1;
+    if (tid < n_local) {
+        const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+        lds_valid_end[tid] = rel < DQ_CHUNK ? static_cast<int32_t>(rel) : DQ_CHUNK;
+    }
+    __syncthreads();
+    int valid[2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const uint32_t e = it * 2048 + tid * 8;
+        valid[it] = e < n_elems ? lds_valid_end[seg[it] - seg_first] - static_cast<int32_t>(e) : 0;
+    }
+    dq_chunk_norms<LINF>(x, valid, tid, n_elems, gseg, seg_first, n_local, lds_gsum, lds_norm);
+    if (tid < n_local) norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]] = lds_norm[tid];
+}
+
+__global__ __launch_bounds__(256) void k_zero_floats(float* __restrict__ dst, int64_t n)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) dst[i] = 0.0f;
+}
+
 int norm_entry(bool linf, const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
                float* norms_dev, void* workspace_dev, void* hip_stream);
 
 } // namespace
+
+int dq_zero_floats(float* dst_dev, int64_t n, hipStream_t stream)
+{
+    if (n <= 0) return DQ_OK;
+    const int64_t blocks = (n + 255) / 256;
+    if (blocks > INT32_MAX) return DQ_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_zero_floats, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, dst_dev, n);
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
 
 extern "C" int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
                        int M, float* norms_dev, void* workspace_dev, void* hip_stream)
@@ -195,21 +271,46 @@ int norm_entry(bool linf, const dq_plan_t* plan, const float* grads_dev, int64_t
     const int rc = dq_plan_check_device(plan);
     if (rc != DQ_OK) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid_items(plan->n_items, M), grid_segs(plan->n_seg, M);
+    if (plan->chunk_local) {
+        // tensors without elements belong to no chunk: their norm is zero
+        if (plan->n_cseg < plan->n_seg) {
+            const int zrc = dq_zero_floats(norms_dev, static_cast<int64_t>(M) * plan->n_seg, stream);
+            if (zrc != DQ_OK) return zrc;
+        }
+        const int64_t n_chunks = (plan->padded_elems + DQ_CHUNK - 1) / DQ_CHUNK;
+        if (n_chunks > INT32_MAX) return DQ_ERR_INVALID_ARG;
+        const dim3 grid(static_cast<unsigned>(n_chunks), M);
+        if (n_chunks > 0) {
+            if (linf)
+                hipLaunchKernelGGL(k_norm_chunk<true>, grid, dim3(256), 0, stream, grads_dev, worker_stride_elems,
+                                   plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems,
+                                   plan->n_seg, norms_dev);
+            else
+                hipLaunchKernelGGL(k_norm_chunk<false>, grid, dim3(256), 0, stream, grads_dev, worker_stride_elems,
+                                   plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems,
+                                   plan->n_seg, norms_dev);
+        }
+        return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+    }
+    const dim3 grid_items(plan->n_items, M), grid_segs(plan->n_finish, M);
     if (linf) {
         if (plan->n_items > 0)
             hipLaunchKernelGGL(k_norm_partial<true>, grid_items, dim3(256), 0, stream, grads_dev,
-                               worker_stride_elems, plan->d_items, plan->n_items, workspace_dev);
-        hipLaunchKernelGGL(k_norm_linf_finish, grid_segs, dim3(FINISH_THREADS), 0, stream,
-                           static_cast<const float*>(workspace_dev), plan->n_items, plan->d_seg_item_begin,
-                           plan->n_seg, norms_dev);
+                               worker_stride_elems, plan->d_items, plan->n_items, workspace_dev,
+                               plan->d_seg_item_begin, plan->n_seg, norms_dev);
+        if (plan->n_finish > 0)
+            hipLaunchKernelGGL(k_norm_linf_finish, grid_segs, dim3(FINISH_THREADS), 0, stream,
+                               static_cast<const float*>(workspace_dev), plan->n_items, plan->d_seg_item_begin,
+                               plan->d_finish_seg, plan->n_seg, norms_dev);
     } else {
         if (plan->n_items > 0)
             hipLaunchKernelGGL(k_norm_partial<false>, grid_items, dim3(256), 0, stream, grads_dev,
-                               worker_stride_elems, plan->d_items, plan->n_items, workspace_dev);
-        hipLaunchKernelGGL(k_norm_finish, grid_segs, dim3(FINISH_THREADS), 0, stream,
-                           static_cast<const double*>(workspace_dev), plan->n_items, plan->d_seg_item_begin,
-                           plan->n_seg, norms_dev);
+                               worker_stride_elems, plan->d_items, plan->n_items, workspace_dev,
+                               plan->d_seg_item_begin, plan->n_seg, norms_dev);
+        if (plan->n_finish > 0)
+            hipLaunchKernelGGL(k_norm_finish, grid_segs, dim3(FINISH_THREADS), 0, stream,
+                               static_cast<const double*>(workspace_dev), plan->n_items, plan->d_seg_item_begin,
+                               plan->d_finish_seg, plan->n_seg, norms_dev);
     }
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
 }

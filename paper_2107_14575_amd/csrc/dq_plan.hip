@@ -31,6 +31,8 @@ void free_device_tables(dq_plan* p)
     if (p->d_cseg_valid_end) (void)hipFree(p->d_cseg_valid_end);
     if (p->d_items) (void)hipFree(p->d_items);
     if (p->d_seg_item_begin) (void)hipFree(p->d_seg_item_begin);
+    if (p->d_finish_seg) (void)hipFree(p->d_finish_seg);
+    p->d_finish_seg = nullptr;
     p->d_granule_cseg = nullptr;
     p->d_cseg_seg = nullptr;
     p->d_cseg_valid_end = nullptr;
@@ -66,9 +68,11 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
     }
     int64_t n_items = 0;
     p->seg_start[0] = 0;
+    p->chunk_local = true;
     for (int32_t l = 0; l < n_seg; ++l) {
         p->seg_len[l] = seg_len_host[l];
         p->seg_start[l + 1] = p->seg_start[l] + padded_len(seg_len_host[l]);
+        if (seg_len_host[l] > 0 && p->seg_start[l] / 4096 != (p->seg_start[l + 1] - 1) / 4096) p->chunk_local = false;
         n_items += (seg_len_host[l] + DQ_NORM_CHUNK - 1) / DQ_NORM_CHUNK;
     }
     if (n_items > INT32_MAX) {
@@ -94,6 +98,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
     std::vector<int32_t> granule_cseg(static_cast<size_t>(total / DQ_GRANULE));
     std::vector<dq_norm_item> items;
     std::vector<int32_t> item_begin(n_seg + 1);
+    std::vector<int32_t> finish_seg;
     try {
         items.reserve(static_cast<size_t>(n_items));
         for (int32_t l = 0; l < n_seg; ++l) {
@@ -115,6 +120,8 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
             }
         }
         item_begin[n_seg] = static_cast<int32_t>(items.size());
+        for (int32_t l = 0; l < n_seg; ++l)
+            if (item_begin[l + 1] - item_begin[l] != 1) finish_seg.push_back(l);
     } catch (const std::bad_alloc&) {
         dq_plan_destroy(p);
         return DQ_ERR_ALLOC;
@@ -122,7 +129,8 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
 
     const bool ok = upload(&p->d_granule_cseg, granule_cseg) && upload(&p->d_cseg_seg, cseg_seg) &&
                     upload(&p->d_cseg_valid_end, cseg_valid_end) &&
-                    upload(&p->d_items, items) && upload(&p->d_seg_item_begin, item_begin);
+                    upload(&p->d_items, items) && upload(&p->d_seg_item_begin, item_begin) &&
+                    upload(&p->d_finish_seg, finish_seg);
     if (!ok) {
         (void)hipGetLastError();
         free_device_tables(p);
@@ -131,6 +139,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
     }
     p->device = dev;
     p->n_cseg = static_cast<int32_t>(cseg_seg.size());
+    p->n_finish = static_cast<int32_t>(finish_seg.size());
     *plan_out = p;
     return DQ_OK;
 }
@@ -171,6 +180,8 @@ extern "C" int64_t dq_workspace_bytes(const dq_plan_t* plan, int M)
     const int64_t partials = static_cast<int64_t>(M) * plan->n_items * static_cast<int64_t>(sizeof(double));
     return partials < 16 ? 16 : (partials + 15) / 16 * 16;
 }
+
+extern "C" int dq_plan_is_chunk_local(const dq_plan_t* plan) { return plan && plan->chunk_local ? 1 : 0; }
 
 extern "C" int dq_plan_has_device(const dq_plan_t* plan) { return plan && plan->device >= 0 ? 1 : 0; }
 

@@ -12,6 +12,7 @@
 //
 // HBM traffic per element: 4 bytes read, (B+1)/8 bytes written, plus 4 bytes per 128 elements for
 // the granule table.
+#include "dq_chunk_norm.h"
 #include "dq_internal.h"
 
 namespace {
@@ -61,17 +62,21 @@ __device__ __forceinline__ void quantize4(const float4 x, const float scale, con
     }
 }
 
-template <int B, int TILES>
+// NORM = 0: the norms are an input.  NORM = 1 (l2) or 2 (max): chunk-local plans only; the kernel
+// computes the norms of its chunk's tensors itself, writes them to norms_out and quantizes from
+// the registers it already holds -- one read of the gradient instead of two.
+template <int B, int TILES, int NORM>
 __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
     const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
     const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
     const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems,
     uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
-    int64_t packed_stride)
+    int64_t packed_stride, float* __restrict__ norms_out)
 {
     constexpr int CHUNK = QP_TILE * TILES;
     constexpr int MAX_LOCAL_SEG = CHUNK / DQ_GRANULE;
     constexpr float S = static_cast<float>((1 << B) - 1);
+    static_assert(NORM == 0 || CHUNK == DQ_CHUNK, "the fused norm works on 4096-element chunks");
 
     __shared__ float lds_scale[MAX_LOCAL_SEG];
     __shared__ int32_t lds_valid_end[MAX_LOCAL_SEG]; // relative to the chunk, clamped to CHUNK
@@ -103,13 +108,37 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
     // compact segment indices grow by at most one per granule, so the chunk's segments fit the table
     const int32_t seg_first = gseg[0];
     const int32_t seg_last = gseg[(n_elems - 1) >> 7];
-    if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
-        const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]];
-        lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f; // zero, tiny or NaN norm: every level 0
-        const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
-        lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+    if constexpr (NORM == 0) {
+        if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
+            const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]];
+            lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f; // zero, tiny or NaN norm: every level 0
+            const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+            lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+        }
+        __syncthreads();
+    } else {
+        __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
+        const int n_local = seg_last - seg_first + 1;
+        if (static_cast<int32_t>(tid) < n_local) {
+            const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+            lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+        }
+        __syncthreads();
+        int valid[TILES];
+#pragma unroll
+        for (int it = 0; it < TILES; ++it) {
+            const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+            valid[it] = e < n_elems ? lds_valid_end[seg[it] - seg_first] - static_cast<int32_t>(e) : 0;
+        }
+        // the tensor norms of this chunk land in lds_scale, then become the scales s/N
+        dq_chunk_norms<NORM == 2>(x, valid, static_cast<int>(tid), n_elems, gseg, seg_first, n_local, lds_gsum, lds_scale);
+        if (static_cast<int32_t>(tid) < n_local) {
+            const float N = lds_scale[tid];
+            norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]] = N;
+            lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f;
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     // Philox counter words: quad index P>>2 (low word varies per lane, high word is uniform because
     // a chunk never straddles a multiple of 2^34 elements), worker, step
@@ -352,20 +381,37 @@ __global__ __launch_bounds__(QP_THREADS) void k_sign_pack(const float* __restric
     for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
 }
 
-template <int B>
+template <int B, int NORM>
 int launch(const dq_plan* plan, const float* grads, int64_t worker_stride, int M, const float* norms,
            uint64_t seed, uint32_t step, uint32_t worker_base, uint8_t* packed, int64_t packed_stride,
-           hipStream_t stream)
+           float* norms_out, hipStream_t stream)
 {
     constexpr int TILES = DQ_QP_TILES;
     constexpr int CHUNK = QP_TILE * TILES;
     const int64_t n_chunks = (plan->padded_elems + CHUNK - 1) / CHUNK;
     if (n_chunks > INT32_MAX) return DQ_ERR_INVALID_ARG;
-    hipLaunchKernelGGL((k_quantize_pack<B, TILES>), dim3(static_cast<unsigned>(n_chunks), M), dim3(QP_THREADS), 0,
-                       stream, grads, worker_stride, norms, plan->n_seg, plan->d_granule_cseg,
+    hipLaunchKernelGGL((k_quantize_pack<B, TILES, NORM>), dim3(static_cast<unsigned>(n_chunks), M), dim3(QP_THREADS),
+                       0, stream, grads, worker_stride, norms, plan->n_seg, plan->d_granule_cseg,
                        plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, static_cast<uint32_t>(seed),
-                       static_cast<uint32_t>(seed >> 32), step, worker_base, packed, packed_stride);
+                       static_cast<uint32_t>(seed >> 32), step, worker_base, packed, packed_stride, norms_out);
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
+template <int NORM>
+int launch_width(int b, const dq_plan* plan, const float* grads, int64_t worker_stride, int M, const float* norms,
+                 uint64_t seed, uint32_t step, uint32_t worker_base, uint8_t* packed, int64_t packed_stride,
+                 float* norms_out, hipStream_t stream)
+{
+    switch (b) {
+    case 1: return launch<1, NORM>(plan, grads, worker_stride, M, norms, seed, step, worker_base, packed, packed_stride, norms_out, stream);
+    case 2: return launch<2, NORM>(plan, grads, worker_stride, M, norms, seed, step, worker_base, packed, packed_stride, norms_out, stream);
+    case 3: return launch<3, NORM>(plan, grads, worker_stride, M, norms, seed, step, worker_base, packed, packed_stride, norms_out, stream);
+    case 4: return launch<4, NORM>(plan, grads, worker_stride, M, norms, seed, step, worker_base, packed, packed_stride, norms_out, stream);
+    case 5: return launch<5, NORM>(plan, grads, worker_stride, M, norms, seed, step, worker_base, packed, packed_stride, norms_out, stream);
+    case 6: return launch<6, NORM>(plan, grads, worker_stride, M, norms, seed, step, worker_base, packed, packed_stride, norms_out, stream);
+    case 7: return launch<7, NORM>(plan, grads, worker_stride, M, norms, seed, step, worker_base, packed, packed_stride, norms_out, stream);
+    default: return launch<8, NORM>(plan, grads, worker_stride, M, norms, seed, step, worker_base, packed, packed_stride, norms_out, stream);
+    }
 }
 
 } // namespace
@@ -385,17 +431,8 @@ extern "C" int dq_quantize_pack(const dq_plan_t* plan, const float* grads_dev, i
     const int rc = dq_plan_check_device(plan);
     if (rc != DQ_OK) return rc;
     if (plan->padded_elems == 0) return DQ_OK;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    switch (b) {
-    case 1: return launch<1>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
-    case 2: return launch<2>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
-    case 3: return launch<3>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
-    case 4: return launch<4>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
-    case 5: return launch<5>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
-    case 6: return launch<6>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
-    case 7: return launch<7>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
-    default: return launch<8>(plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev, packed_worker_stride_bytes, stream);
-    }
+    return launch_width<0>(b, plan, grads_dev, worker_stride_elems, M, norms_dev, seed, step, worker_base, packed_dev,
+                           packed_worker_stride_bytes, nullptr, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int dq_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
@@ -445,4 +482,32 @@ extern "C" int dq_sign_pack(const dq_plan_t* plan, const float* grads_dev, int64
                        static_cast<hipStream_t>(hip_stream), grads_dev, worker_stride_elems, plan->d_granule_cseg,
                        plan->d_cseg_valid_end, plan->padded_elems, packed_dev, packed_worker_stride_bytes);
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
+extern "C" int dq_norm_quantize_pack(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                                     int M, int linf, int b, uint64_t seed, uint32_t step, uint32_t worker_base,
+                                     float* norms_dev, uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                                     void* hip_stream)
+{
+    if (!plan || !grads_dev || !norms_dev || !packed_dev) return DQ_ERR_INVALID_ARG;
+    if (!plan->chunk_local) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS || b < 1 || b > 8) return DQ_ERR_INVALID_ARG;
+    if (worker_stride_elems < plan->padded_elems || (worker_stride_elems & 3)) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < dq_packed_bytes(plan, b) || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(grads_dev) || !dq_aligned16(packed_dev) || (reinterpret_cast<uintptr_t>(norms_dev) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // tensors without elements belong to no chunk: their norm is zero
+    if (plan->n_cseg < plan->n_seg) {
+        const int zrc = dq_zero_floats(norms_dev, static_cast<int64_t>(M) * plan->n_seg, stream);
+        if (zrc != DQ_OK) return zrc;
+    }
+    if (plan->padded_elems == 0) return DQ_OK;
+    return linf ? launch_width<2>(b, plan, grads_dev, worker_stride_elems, M, nullptr, seed, step, worker_base,
+                                  packed_dev, packed_worker_stride_bytes, norms_dev, stream)
+                : launch_width<1>(b, plan, grads_dev, worker_stride_elems, M, nullptr, seed, step, worker_base,
+                                  packed_dev, packed_worker_stride_bytes, norms_dev, stream);
 }

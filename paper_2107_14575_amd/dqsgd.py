@@ -16,6 +16,10 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
   * per_tensor=True: one bit-width per tensor from ``dq_select_bits_per_tensor`` (b0, b_t in the
     result and on_step's b are then arrays of n_seg widths), messages in the per-tensor layout,
     through the ``*_v`` entry points.
+  * With the lagged rule b_t is known before the gradient is looked at, so on a chunk-local plan
+    (``plan.chunk_local``: no tensor crosses a multiple of 4096 padded elements, e.g. a gradient
+    cut into buckets) the worker side is the single pass ``dq_norm_quantize_pack``; one_pass=False
+    keeps the two calls.
   * device_rule=True: the rule runs on the GPU (``dq_select_bits_device``) and the loop never waits
     for the host; b_t and the cost are read back once at the end.  alpha must be a number.
   * p: 2 or "inf", the norm of Eq. (5) (the paper leaves p open): ``dq_norm``/``dq_select_bits`` or
@@ -45,7 +49,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         b_min: int = 1, b_max: int = 8, tau: int = 1, lagged: bool = True, seed: int = 0,
         loss_fn: Optional[Callable[["torch.Tensor"], float]] = None, B_pre: int = 32,
         on_step: Optional[Callable] = None, p: Union[int, str] = 2, per_tensor: bool = False,
-        device_rule: bool = False) -> DQSGDResult:
+        device_rule: bool = False, one_pass: bool = True) -> DQSGDResult:
     """grad_fn(t, x, grads_out) fills grads_out[M][D'] (float32, CUDA, padded layout) with the M
     workers' stochastic gradients at x.  on_step(t, b_t, grads, norms_host, packed) is called after
     the quantize pass of every iteration (tests use it to feed the same bytes to the oracle)."""
@@ -78,15 +82,22 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
     cur_alpha = 1.0 if estimate else float(alpha)
     b = int(b0)
 
+    single_pass = one_pass and lagged and plan.chunk_local
     for t in range(T):
         grad_fn(t, x, grads)
-        norm_fn(plan, grads, norms, ws)
+        pk = None
+        if single_pass:
+            pk = packed[:, :plan.packed_bytes(b)]
+            _b.norm_quantize_pack(plan, grads, b, seed, t, norms, pk, linf=p != 2)
+        else:
+            norm_fn(plan, grads, norms, ws)
         norms_host.copy_(norms, non_blocking=True)
         if not lagged:
             torch.cuda.current_stream().synchronize()
             b, gb = rule(norms_host.numpy(), t, T, eps_hat_q, cur_alpha, b_min, b_max)
-        pk = packed[:, :plan.packed_bytes(b)]
-        _b.quantize_pack(plan, grads, norms, b, seed, t, pk)
+        if pk is None:
+            pk = packed[:, :plan.packed_bytes(b)]
+            _b.quantize_pack(plan, grads, norms, b, seed, t, pk)
         if on_step is not None:
             torch.cuda.current_stream().synchronize()
             on_step(t, b, grads, norms_host.numpy(), pk)
