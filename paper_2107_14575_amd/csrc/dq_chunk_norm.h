@@ -5,22 +5,43 @@
 //
 // A workgroup of 256 lanes owns the chunk; lane t holds elements [8t, 8t+8) of each of its two
 // 2048-element tiles.  Squares are summed in binary64 (exact products) in a fixed order: the
-// lane's eight, the 16 lanes of a 128-element granule by a butterfly, then the granules of a
-// tensor in ascending order by one lane.  The max norm takes the same route with maxima.
+// lane's eight, the 16 lanes of a 128-element granule by four rotate-and-add steps inside the
+// 16-lane DPP row (the granule's first lane keeps the result), then the granules of a tensor in
+// ascending order by one lane.  The max norm takes the same route with maxima.
 #pragma once
 #include "dq_internal.h"
 
 constexpr int DQ_CHUNK = 4096;
 constexpr int DQ_CHUNK_GRANULES = DQ_CHUNK / DQ_GRANULE; // 32
 
-// x[it][h]: the lane's float4 halves of tile it; valid[it]: how many of the lane's eight elements of
-// tile `it` belong to their tensor (<= 0: none, >= 8: all).  After the call (which contains
-// barriers) lds_norm[j] holds the norm of the chunk's j-th tensor, j < n_local.
-//   lds_gsum   [32] doubles of scratch;  gseg: granule -> compact tensor index, at the chunk's start
+// value of the lane N places further on in the same 16-lane row (DPP row_ror:N)
+template <int N>
+__device__ __forceinline__ float dq_row_ror(float v)
+{
+    return __uint_as_float(static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(__float_as_uint(v)), 0x120 + N, 0xF, 0xF, false)));
+}
+
+template <int N>
+__device__ __forceinline__ double dq_row_ror(double v)
+{
+    const uint64_t bits = static_cast<uint64_t>(__double_as_longlong(v));
+    const uint32_t lo = static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(static_cast<uint32_t>(bits)), 0x120 + N, 0xF, 0xF, false));
+    const uint32_t hi = static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(static_cast<uint32_t>(bits >> 32)), 0x120 + N, 0xF, 0xF, false));
+    return __longlong_as_double(static_cast<long long>((static_cast<uint64_t>(hi) << 32) | lo));
+}
+
+// Step 1 (every lane): x[it][h] are the lane's float4 halves of tile it; valid[it] says how many
+// of the lane's eight elements of tile `it` belong to their tensor (<= 0: none, >= 8: all);
+// local[it] is the index of that tensor among the chunk's tensors.  Leaves the sum (or maximum)
+// of every 128-element granule in lds_gsum[32] and the granule's tensor index in lds_glocal[32].
+// The caller puts a barrier between the two steps.
 template <bool LINF>
-__device__ __forceinline__ void dq_chunk_norms(const float4 (&x)[2][2], const int (&valid)[2], int tid,
-                                               uint32_t n_elems, const int32_t* __restrict__ gseg,
-                                               int32_t seg_first, int n_local, double* lds_gsum, float* lds_norm)
+__device__ __forceinline__ void dq_chunk_granule_sums(const float4 (&x)[2][2], const int (&valid)[2],
+                                                      const int (&local)[2], int tid, double* lds_gsum,
+                                                      int32_t* lds_glocal)
 {
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
@@ -34,38 +55,53 @@ __device__ __forceinline__ void dq_chunk_norms(const float4 (&x)[2][2], const in
                 const float a = k < valid[it] ? fabsf(v[k]) : 0.0f;
                 m = a > m ? a : m;
             }
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) {
-                const float o = __shfl_xor(m, off, 16);
-                m = o > m ? o : m;
-            }
+            float o;
+            o = dq_row_ror<8>(m); m = o > m ? o : m;
+            o = dq_row_ror<4>(m); m = o > m ? o : m;
+            o = dq_row_ror<2>(m); m = o > m ? o : m;
+            o = dq_row_ror<1>(m); m = o > m ? o : m;
             granule = static_cast<double>(m);
         } else {
             double acc = 0.0;
+            if (valid[it] >= 8) { // the usual case: no element of the lane is past its tensor's end
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const double e = k < valid[it] ? static_cast<double>(v[k]) : 0.0;
-                acc = __builtin_fma(e, e, acc);
+                for (int k = 0; k < 8; ++k) {
+                    const double e = static_cast<double>(v[k]);
+                    acc = __builtin_fma(e, e, acc);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const double e = static_cast<double>(k < valid[it] ? v[k] : 0.0f);
+                    acc = __builtin_fma(e, e, acc);
+                }
             }
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1)
-                acc += __shfl_xor(acc, off, 16); // both partners add the same two values: the 16 lanes end equal
-            granule = acc;
+            acc += dq_row_ror<8>(acc);
+            acc += dq_row_ror<4>(acc);
+            acc += dq_row_ror<2>(acc);
+            acc += dq_row_ror<1>(acc);
+            granule = acc; // every lane of the row now has all sixteen terms; the first lane's order is the one used
         }
-        if ((tid & 15) == 0) lds_gsum[it * 16 + (tid >> 4)] = granule;
-    }
-    __syncthreads();
-    if (tid < n_local) {
-        const int n_gran = static_cast<int>(n_elems >> 7);
-        double total = 0.0;
-        for (int g = 0; g < n_gran; ++g) {
-            if (gseg[g] - seg_first != tid) continue;
-            if constexpr (LINF)
-                total = lds_gsum[g] > total ? lds_gsum[g] : total;
-            else
-                total += lds_gsum[g];
+        if ((tid & 15) == 0) {
+            lds_gsum[it * 16 + (tid >> 4)] = granule;
+            lds_glocal[it * 16 + (tid >> 4)] = local[it];
         }
-        lds_norm[tid] = LINF ? static_cast<float>(total) : static_cast<float>(sqrt(total));
     }
-    __syncthreads();
+}
+
+// Step 2 (one lane per tensor of the chunk): the norm of tensor `j` from its granules, in
+// ascending order.
+template <bool LINF>
+__device__ __forceinline__ float dq_chunk_tensor_norm(int j, int n_granules, const double* lds_gsum,
+                                                      const int32_t* lds_glocal)
+{
+    double total = 0.0;
+    for (int g = 0; g < n_granules; ++g) {
+        if (lds_glocal[g] != j) continue;
+        if constexpr (LINF)
+            total = lds_gsum[g] > total ? lds_gsum[g] : total;
+        else
+            total += lds_gsum[g];
+    }
+    return LINF ? static_cast<float>(total) : static_cast<float>(sqrt(total));
 }

@@ -89,17 +89,29 @@ __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ 
     }
     double* partial = static_cast<double*>(partial_out);
     double acc = 0.0;
+    if (item.count == DQ_NORM_CHUNK) { // a full item (uniform): no masks
 #pragma unroll
-    for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
-        const int e = (k * 256 + tid) * 4;
-        const double x0 = e + 0 < item.count ? static_cast<double>(v[k].x) : 0.0;
-        const double x1 = e + 1 < item.count ? static_cast<double>(v[k].y) : 0.0;
-        const double x2 = e + 2 < item.count ? static_cast<double>(v[k].z) : 0.0;
-        const double x3 = e + 3 < item.count ? static_cast<double>(v[k].w) : 0.0;
-        acc = __builtin_fma(x0, x0, acc);
-        acc = __builtin_fma(x1, x1, acc);
-        acc = __builtin_fma(x2, x2, acc);
-        acc = __builtin_fma(x3, x3, acc);
+        for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
+            const double x0 = static_cast<double>(v[k].x), x1 = static_cast<double>(v[k].y);
+            const double x2 = static_cast<double>(v[k].z), x3 = static_cast<double>(v[k].w);
+            acc = __builtin_fma(x0, x0, acc);
+            acc = __builtin_fma(x1, x1, acc);
+            acc = __builtin_fma(x2, x2, acc);
+            acc = __builtin_fma(x3, x3, acc);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
+            const int e = (k * 256 + tid) * 4;
+            const double x0 = static_cast<double>(e + 0 < item.count ? v[k].x : 0.0f);
+            const double x1 = static_cast<double>(e + 1 < item.count ? v[k].y : 0.0f);
+            const double x2 = static_cast<double>(e + 2 < item.count ? v[k].z : 0.0f);
+            const double x3 = static_cast<double>(e + 3 < item.count ? v[k].w : 0.0f);
+            acc = __builtin_fma(x0, x0, acc);
+            acc = __builtin_fma(x1, x1, acc);
+            acc = __builtin_fma(x2, x2, acc);
+            acc = __builtin_fma(x3, x3, acc);
+        }
     }
     acc = wave_sum(acc);
     if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
@@ -190,7 +202,7 @@ __global__ __launch_bounds__(256) void k_norm_chunk(const float* __restrict__ gr
                                                     int32_t n_seg, float* __restrict__ norms)
 {
     __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
-    __shared__ float lds_norm[DQ_CHUNK_GRANULES];
+    __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
     __shared__ int32_t lds_valid_end[DQ_CHUNK_GRANULES];
     const int tid = threadIdx.x;
     const int w = blockIdx.y;
@@ -216,14 +228,18 @@ __global__ __launch_bounds__(256) void k_norm_chunk(const float* __restrict__ gr
         lds_valid_end[tid] = rel < DQ_CHUNK ? static_cast<int32_t>(rel) : DQ_CHUNK;
     }
     __syncthreads();
-    int valid[2];
+    int valid[2], local[2];
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const uint32_t e = it * 2048 + tid * 8;
-        valid[it] = e < n_elems ? lds_valid_end[seg[it] - seg_first] - static_cast<int32_t>(e) : 0;
+        local[it] = seg[it] - seg_first;
+        valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
     }
-    dq_chunk_norms<LINF>(x, valid, tid, n_elems, gseg, seg_first, n_local, lds_gsum, lds_norm);
-    if (tid < n_local) norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]] = lds_norm[tid];
+    dq_chunk_granule_sums<LINF>(x, valid, local, tid, lds_gsum, lds_glocal);
+    __syncthreads();
+    if (tid < n_local)
+        norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]] =
+            dq_chunk_tensor_norm<LINF>(tid, static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal);
 }
 
 __global__ __launch_bounds__(256) void k_zero_floats(float* __restrict__ dst, int64_t n)

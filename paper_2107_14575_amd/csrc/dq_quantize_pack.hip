@@ -118,22 +118,25 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
         __syncthreads();
     } else {
         __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
+        __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
         const int n_local = seg_last - seg_first + 1;
         if (static_cast<int32_t>(tid) < n_local) {
             const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
             lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
         }
         __syncthreads();
-        int valid[TILES];
+        int valid[TILES], local[TILES];
 #pragma unroll
         for (int it = 0; it < TILES; ++it) {
             const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
-            valid[it] = e < n_elems ? lds_valid_end[seg[it] - seg_first] - static_cast<int32_t>(e) : 0;
+            local[it] = seg[it] - seg_first;
+            valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
         }
-        // the tensor norms of this chunk land in lds_scale, then become the scales s/N
-        dq_chunk_norms<NORM == 2>(x, valid, static_cast<int>(tid), n_elems, gseg, seg_first, n_local, lds_gsum, lds_scale);
+        dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+        __syncthreads();
         if (static_cast<int32_t>(tid) < n_local) {
-            const float N = lds_scale[tid];
+            const float N = dq_chunk_tensor_norm<NORM == 2>(static_cast<int>(tid), static_cast<int>(n_elems >> 7),
+                                                            lds_gsum, lds_glocal);
             norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]] = N;
             lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f;
         }
