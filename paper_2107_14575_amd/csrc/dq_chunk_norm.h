@@ -6,8 +6,8 @@
 // A workgroup of 256 lanes owns the chunk; lane t holds elements [8t, 8t+8) of each of its two
 // 2048-element tiles.  Squares are summed in binary64 (exact products) in a fixed order: the
 // lane's eight, the 16 lanes of a 128-element granule by four rotate-and-add steps inside the
-// 16-lane DPP row (the granule's first lane keeps the result), then the granules of a tensor in
-// ascending order by one lane.  The max norm takes the same route with maxima.
+// 16-lane DPP row (the granule's first lane keeps the result), then the granules of a tensor by a
+// segmented scan over the chunk's 32 granules.  The max norm takes the same route with maxima.
 #pragma once
 #include "dq_internal.h"
 
@@ -89,19 +89,56 @@ __device__ __forceinline__ void dq_chunk_granule_sums(const float4 (&x)[2][2], c
     }
 }
 
-// Step 2 (one lane per tensor of the chunk): the norm of tensor `j` from its granules, in
-// ascending order.
-template <bool LINF>
-__device__ __forceinline__ float dq_chunk_tensor_norm(int j, int n_granules, const double* lds_gsum,
-                                                      const int32_t* lds_glocal)
+// value of the lane N places back in the same 16-lane row, 0 for the first N lanes (DPP row_shr:N)
+template <int N>
+__device__ __forceinline__ int dq_row_shr(int v)
 {
-    double total = 0.0;
-    for (int g = 0; g < n_granules; ++g) {
-        if (lds_glocal[g] != j) continue;
-        if constexpr (LINF)
-            total = lds_gsum[g] > total ? lds_gsum[g] : total;
-        else
-            total += lds_gsum[g];
-    }
-    return LINF ? static_cast<float>(total) : static_cast<float>(sqrt(total));
+    return __builtin_amdgcn_update_dpp(0, v, 0x110 + N, 0xF, 0xF, true);
+}
+
+template <int N>
+__device__ __forceinline__ double dq_row_shr(double v)
+{
+    const uint64_t bits = static_cast<uint64_t>(__double_as_longlong(v));
+    const uint32_t lo = static_cast<uint32_t>(dq_row_shr<N>(static_cast<int>(static_cast<uint32_t>(bits))));
+    const uint32_t hi = static_cast<uint32_t>(dq_row_shr<N>(static_cast<int>(static_cast<uint32_t>(bits >> 32))));
+    return __longlong_as_double(static_cast<long long>((static_cast<uint64_t>(hi) << 32) | lo));
+}
+
+template <bool LINF>
+__device__ __forceinline__ double dq_chunk_combine(double a, double b)
+{
+    if constexpr (LINF)
+        return b > a ? b : a;
+    else
+        return a + b;
+}
+
+// Step 2 (the first 32 lanes of the workgroup, one per granule; call it under `if (tid < 32)`):
+// a segmented scan over the granules -- four shift-and-combine steps inside each 16-lane row, then
+// the second row takes over what the first row's last granule has gathered when a tensor spans
+// both -- after which the lane of a tensor's last granule holds the tensor's total and calls
+// emit(local tensor index, norm).  A fixed combination order, the same wherever this is used.
+template <bool LINF, typename Emit>
+__device__ __forceinline__ void dq_chunk_tensor_norms(int g, int n_granules, const double* lds_gsum,
+                                                      const int32_t* lds_glocal, Emit&& emit)
+{
+    const bool used = g < n_granules;
+    double v = used ? lds_gsum[g] : 0.0;
+    const int t = used ? lds_glocal[g] + 1 : 0; // 0: unused slot, and what a shift past the row's start reads
+    double pv;
+    int pt;
+    pv = dq_row_shr<1>(v); pt = dq_row_shr<1>(t); if (pt == t) v = dq_chunk_combine<LINF>(v, pv);
+    pv = dq_row_shr<2>(v); pt = dq_row_shr<2>(t); if (pt == t) v = dq_chunk_combine<LINF>(v, pv);
+    pv = dq_row_shr<4>(v); pt = dq_row_shr<4>(t); if (pt == t) v = dq_chunk_combine<LINF>(v, pv);
+    pv = dq_row_shr<8>(v); pt = dq_row_shr<8>(t); if (pt == t) v = dq_chunk_combine<LINF>(v, pv);
+    // lane 15: the total of the tensor that ends the first row, as far as that row goes
+    const uint64_t bits = static_cast<uint64_t>(__double_as_longlong(v));
+    const uint32_t tail_lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(bits)), 15));
+    const uint32_t tail_hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(bits >> 32)), 15));
+    const int tail_t = __builtin_amdgcn_readlane(t, 15);
+    const double tail = __longlong_as_double(static_cast<long long>((static_cast<uint64_t>(tail_hi) << 32) | tail_lo));
+    if (g >= 16 && t == tail_t) v = dq_chunk_combine<LINF>(tail, v);
+    if (used && (g == n_granules - 1 || lds_glocal[g + 1] + 1 != t))
+        emit(t - 1, LINF ? static_cast<float>(v) : static_cast<float>(sqrt(v)));
 }

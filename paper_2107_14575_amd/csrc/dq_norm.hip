@@ -237,9 +237,10 @@ __global__ __launch_bounds__(256) void k_norm_chunk(const float* __restrict__ gr
     }
     dq_chunk_granule_sums<LINF>(x, valid, local, tid, lds_gsum, lds_glocal);
     __syncthreads();
-    if (tid < n_local)
-        norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]] =
-            dq_chunk_tensor_norm<LINF>(tid, static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal);
+    if (tid < DQ_CHUNK_GRANULES)
+        dq_chunk_tensor_norms<LINF>(tid, static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal, [&](int j, float N) {
+            norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
+        });
 }
 
 __global__ __launch_bounds__(256) void k_zero_floats(float* __restrict__ dst, int64_t n)

@@ -119,8 +119,7 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
     } else {
         __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
         __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
-        const int n_local = seg_last - seg_first + 1;
-        if (static_cast<int32_t>(tid) < n_local) {
+        if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
             const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
             lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
         }
@@ -134,12 +133,12 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack(
         }
         dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
         __syncthreads();
-        if (static_cast<int32_t>(tid) < n_local) {
-            const float N = dq_chunk_tensor_norm<NORM == 2>(static_cast<int>(tid), static_cast<int>(n_elems >> 7),
-                                                            lds_gsum, lds_glocal);
-            norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]] = N;
-            lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f;
-        }
+        if (tid < DQ_CHUNK_GRANULES)
+            dq_chunk_tensor_norms<NORM == 2>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+                                             [&](int j, float N) {
+                                                 norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
+                                                 lds_scale[j] = N >= DQ_MIN_NORM ? S / N : 0.0f;
+                                             });
         __syncthreads();
     }
 
