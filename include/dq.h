@@ -32,7 +32,10 @@
  *           only the plan's tables (dq_plan_create / dq_plan_destroy) and the per-tensor width
  *           tables (dq_widths_create / dq_widths_destroy).
  * STREAMS   Device entry points enqueue on `hip_stream` (a hipStream_t passed as void*; NULL is
- *           the default stream) and return without synchronising.
+ *           the default stream) and return without synchronising.  They enqueue kernels only -- no
+ *           allocation, memset or copy -- so a sequence of them can be captured into a HIP graph;
+ *           the exceptions are dq_plan_create, dq_widths_create and dq_widths_set (allocation,
+ *           host-to-device copies), which belong outside a capture.
  * ERRORS    Every int-returning function returns DQ_OK (0) or a negative dq_status; nothing
  *           throws, aborts or sets errno.  On error nothing has been enqueued.
  */
