@@ -247,6 +247,13 @@ int dq_sign_reduce(const dq_plan_t* plan, const uint8_t* packed_dev, int64_t pac
 int dq_sign_majority(const dq_plan_t* plan, const uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
                      int M, float* out_dev, void* hip_stream);
 
+/* dq_norm_quantize_pack with the widths of `widths`: one pass over the gradient for chunk-local
+ * plans, per-tensor (e.g. per-bucket) widths that were decided beforehand. */
+int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
+                            int64_t worker_stride_elems, int M, int linf, uint64_t seed, uint32_t step,
+                            uint32_t worker_base, float* norms_dev, uint8_t* packed_dev,
+                            int64_t packed_worker_stride_bytes, void* hip_stream);
+
 /* Eq. (24), the practical estimate of the convergence factor: alpha_est = (F(x_t)/F(x_0))^(1/t).
  * Host code.  Returns -1 unless t >= 1, F_t > 0 and F_0 > 0. */
 double dq_alpha_est(double F_t, double F_0, int64_t t);

@@ -18,7 +18,7 @@ MAX_WORKERS = 64
 EXPORTS = (
     "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems",
     "dq_plan_segment_start", "dq_packed_bytes", "dq_workspace_bytes", "dq_plan_has_device",
-    "dq_plan_is_chunk_local", "dq_norm_quantize_pack",
+    "dq_plan_is_chunk_local", "dq_norm_quantize_pack", "dq_norm_quantize_pack_v",
     "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
     "dq_unpack_dequant_reduce_update", "dq_select_bits_per_tensor", "dq_packed_bytes_v",
     "dq_comm_cost_bits_per_tensor", "dq_widths_create", "dq_widths_destroy", "dq_widths_set",
@@ -109,6 +109,9 @@ def load_library():
     L.dq_select_bits_device.restype = C.c_int
     L.dq_quantize_pack_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, C.c_uint64, C.c_uint32, C.c_uint32, vp, i64, vp]
     L.dq_quantize_pack_v.restype = C.c_int
+    L.dq_norm_quantize_pack_v.argtypes = [vp, vp, vp, i64, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
+                                          vp, vp, i64, vp]
+    L.dq_norm_quantize_pack_v.restype = C.c_int
     L.dq_unpack_dequant_reduce_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, vp, vp]
     L.dq_unpack_dequant_reduce_v.restype = C.c_int
     L.dq_unpack_dequant_reduce_update_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, C.c_float, vp, vp, vp]
@@ -398,6 +401,17 @@ def quantize_pack_v(plan: Plan, widths: Widths, grads, norms, seed: int, step: i
            load_library().dq_quantize_pack_v(plan.handle, widths.handle, grads.data_ptr(), stride, M,
                                              norms.data_ptr(), seed, step, worker_base, packed_out.data_ptr(),
                                              int(packed_out.stride(0)), _stream_handle(stream)))
+
+
+def norm_quantize_pack_v(plan: Plan, widths: Widths, grads, seed: int, step: int, norms_out, packed_out,
+                         worker_base: int = 0, linf: bool = False, stream=None) -> None:
+    """norm_quantize_pack with per-tensor widths (chunk-local plans)."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    _check("dq_norm_quantize_pack_v",
+           load_library().dq_norm_quantize_pack_v(plan.handle, widths.handle, grads.data_ptr(), stride, M,
+                                                  1 if linf else 0, seed, step, worker_base, norms_out.data_ptr(),
+                                                  packed_out.data_ptr(), int(packed_out.stride(0)),
+                                                  _stream_handle(stream)))
 
 
 def unpack_dequant_reduce_v(plan: Plan, widths: Widths, packed, norms, out, stream=None) -> None:

@@ -212,16 +212,17 @@ __device__ __forceinline__ void quantize4_v(const float4 x, const float scale, c
     }
 }
 
-template <int TILES>
+template <int TILES, int NORM> // NORM as in k_quantize_pack
 __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_v(
     const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
     const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
     const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths, int64_t padded_elems,
     uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
-    int64_t packed_stride)
+    int64_t packed_stride, float* __restrict__ norms_out)
 {
     constexpr int CHUNK = QP_TILE * TILES;
     constexpr int MAX_LOCAL_SEG = CHUNK / DQ_GRANULE;
+    static_assert(NORM == 0 || CHUNK == DQ_CHUNK, "the fused norm works on 4096-element chunks");
 
     __shared__ float lds_scale[MAX_LOCAL_SEG];
     __shared__ float lds_levels[MAX_LOCAL_SEG];      // s = 2^b - 1 of the segment
@@ -258,8 +259,10 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_v(
     if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
         const dq_cseg_width e = widths[seg_first + tid];
         const float S = static_cast<float>((1 << e.b) - 1);
-        const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]];
-        lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f;
+        if constexpr (NORM == 0) {
+            const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]];
+            lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f;
+        }
         lds_levels[tid] = S;
         lds_b[tid] = e.b;
         // chunk0 - seg_start is a multiple of 128 of either sign, so the shift is exact
@@ -268,6 +271,26 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_v(
         lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
     }
     __syncthreads();
+    if constexpr (NORM != 0) {
+        __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
+        __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
+        int valid[TILES], local[TILES];
+#pragma unroll
+        for (int it = 0; it < TILES; ++it) {
+            const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+            local[it] = seg[it] - seg_first;
+            valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
+        }
+        dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+        __syncthreads();
+        if (tid < DQ_CHUNK_GRANULES)
+            dq_chunk_tensor_norms<NORM == 2>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+                                             [&](int j, float N) {
+                                                 norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
+                                                 lds_scale[j] = N >= DQ_MIN_NORM ? lds_levels[j] / N : 0.0f;
+                                             });
+        __syncthreads();
+    }
 
     const uint32_t quad_lo0 = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 2);
     const uint32_t quad_hi = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 34);
@@ -437,32 +460,70 @@ extern "C" int dq_quantize_pack(const dq_plan_t* plan, const float* grads_dev, i
                            packed_worker_stride_bytes, nullptr, static_cast<hipStream_t>(hip_stream));
 }
 
-extern "C" int dq_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
-                                  int64_t worker_stride_elems, int M, const float* norms_dev, uint64_t seed,
-                                  uint32_t step, uint32_t worker_base, uint8_t* packed_dev,
-                                  int64_t packed_worker_stride_bytes, void* hip_stream)
+namespace {
+
+int quantize_v_entry(int norm_mode, const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
+                     int64_t worker_stride_elems, int M, const float* norms_in, float* norms_out, uint64_t seed,
+                     uint32_t step, uint32_t worker_base, uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                     void* hip_stream)
 {
-    if (!plan || !widths || !grads_dev || !norms_dev || !packed_dev) return DQ_ERR_INVALID_ARG;
+    const float* norms_any = norm_mode == 0 ? norms_in : norms_out;
+    if (!plan || !widths || !grads_dev || !norms_any || !packed_dev) return DQ_ERR_INVALID_ARG;
     if (widths->plan != plan || widths->packed_bytes < 0) return DQ_ERR_INVALID_ARG;
+    if (norm_mode != 0 && !plan->chunk_local) return DQ_ERR_INVALID_ARG;
     if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
     if (worker_stride_elems < plan->padded_elems || (worker_stride_elems & 3)) return DQ_ERR_INVALID_ARG;
     if (packed_worker_stride_bytes < widths->packed_bytes || (packed_worker_stride_bytes & 15))
         return DQ_ERR_INVALID_ARG;
-    if (!dq_aligned16(grads_dev) || !dq_aligned16(packed_dev) || (reinterpret_cast<uintptr_t>(norms_dev) & 3u))
+    if (!dq_aligned16(grads_dev) || !dq_aligned16(packed_dev) || (reinterpret_cast<uintptr_t>(norms_any) & 3u))
         return DQ_ERR_INVALID_ARG;
     const int rc = dq_plan_check_device(plan);
     if (rc != DQ_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (norm_mode != 0 && plan->n_cseg < plan->n_seg) { // tensors without elements: norm zero
+        const int zrc = dq_zero_floats(norms_out, static_cast<int64_t>(M) * plan->n_seg, stream);
+        if (zrc != DQ_OK) return zrc;
+    }
     if (plan->padded_elems == 0) return DQ_OK;
     constexpr int TILES = DQ_QP_TILES;
     constexpr int CHUNK = QP_TILE * TILES;
     const int64_t n_chunks = (plan->padded_elems + CHUNK - 1) / CHUNK;
     if (n_chunks > INT32_MAX) return DQ_ERR_INVALID_ARG;
-    hipLaunchKernelGGL((k_quantize_pack_v<TILES>), dim3(static_cast<unsigned>(n_chunks), M), dim3(QP_THREADS), 0,
-                       static_cast<hipStream_t>(hip_stream), grads_dev, worker_stride_elems, norms_dev, plan->n_seg,
-                       plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table,
-                       plan->padded_elems, static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), step,
-                       worker_base, packed_dev, packed_worker_stride_bytes);
+    const dim3 grid(static_cast<unsigned>(n_chunks), M), block(QP_THREADS);
+#define DQ_LAUNCH_QV(NORM)                                                                                        \
+    hipLaunchKernelGGL((k_quantize_pack_v<TILES, NORM>), grid, block, 0, stream, grads_dev, worker_stride_elems,  \
+                       norms_in, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end,     \
+                       widths->d_table, plan->padded_elems, static_cast<uint32_t>(seed),                          \
+                       static_cast<uint32_t>(seed >> 32), step, worker_base, packed_dev, packed_worker_stride_bytes, \
+                       norms_out)
+    if (norm_mode == 0)
+        DQ_LAUNCH_QV(0);
+    else if (norm_mode == 1)
+        DQ_LAUNCH_QV(1);
+    else
+        DQ_LAUNCH_QV(2);
+#undef DQ_LAUNCH_QV
     return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
+} // namespace
+
+extern "C" int dq_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
+                                  int64_t worker_stride_elems, int M, const float* norms_dev, uint64_t seed,
+                                  uint32_t step, uint32_t worker_base, uint8_t* packed_dev,
+                                  int64_t packed_worker_stride_bytes, void* hip_stream)
+{
+    return quantize_v_entry(0, plan, widths, grads_dev, worker_stride_elems, M, norms_dev, nullptr, seed, step,
+                            worker_base, packed_dev, packed_worker_stride_bytes, hip_stream);
+}
+
+extern "C" int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
+                                       int64_t worker_stride_elems, int M, int linf, uint64_t seed, uint32_t step,
+                                       uint32_t worker_base, float* norms_dev, uint8_t* packed_dev,
+                                       int64_t packed_worker_stride_bytes, void* hip_stream)
+{
+    return quantize_v_entry(linf ? 2 : 1, plan, widths, grads_dev, worker_stride_elems, M, nullptr, norms_dev, seed,
+                            step, worker_base, packed_dev, packed_worker_stride_bytes, hip_stream);
 }
 
 extern "C" int dq_sign_pack(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,

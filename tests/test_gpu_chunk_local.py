@@ -146,3 +146,28 @@ def test_algorithm1_lagged_loop_takes_the_single_pass(dq, oracle):
     assert one.cost_bits == two.cost_bits
     assert float((one.x - target).norm()) < 0.2 * float(target.norm())
     plan.close()
+
+
+@pytest.mark.parametrize("name", ["granules", "buckets512_ragged_end", "mixed"])
+@pytest.mark.parametrize("linf", [False, True])
+def test_one_pass_with_per_tensor_widths(dq, oracle, name, linf):
+    seg_len = LAYOUTS[name]
+    M = 3
+    g = _grads(seg_len, M, 103)
+    g_host = np.ascontiguousarray(g.numpy())
+    g_dev = g.cuda()
+    plan = dq.Plan(seg_len)
+    rng = np.random.default_rng(104)
+    widths = rng.integers(1, 9, size=len(seg_len)).astype(np.int32)
+    table = dq.Widths(plan, widths)
+    two_pass = gpu_norm(dq, plan, g_dev, linf)
+    norms = torch.full((M, plan.n_seg), float("nan"), dtype=torch.float32, device="cuda")
+    packed = torch.full((M, table.packed_bytes + 16), 0xA5, dtype=torch.uint8, device="cuda")
+    dq.norm_quantize_pack_v(plan, table, g_dev, SEED, 5, norms, packed, worker_base=1, linf=linf)
+    torch.cuda.synchronize()
+    assert torch.equal(norms.view(torch.int32), two_pass.view(torch.int32))
+    got = packed.cpu().numpy()
+    want = oracle.quantize_pack_v(seg_len, g_host, norms.cpu().numpy(), widths, SEED, 5, worker_base=1)
+    assert np.array_equal(got[:, :want.shape[1]], want) and np.all(got[:, want.shape[1]:] == 0xA5)
+    table.close()
+    plan.close()
