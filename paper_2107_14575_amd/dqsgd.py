@@ -65,7 +65,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
                                 seed, B_pre, on_step, norm_fn, rule_name)
     if per_tensor:
         return _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged,
-                               seed, B_pre, on_step, norm_fn)
+                               seed, B_pre, on_step, norm_fn, one_pass and lagged and plan.chunk_local, p != 2)
     dev = x0.device
     x = x0.clone()
     grads = torch.zeros((M, dp), dtype=torch.float32, device=dev)
@@ -118,7 +118,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
 
 
 def _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged, seed, B_pre,
-                    on_step, norm_fn) -> DQSGDResult:
+                    on_step, norm_fn, single_pass=False, linf=False) -> DQSGDResult:
     import numpy as np
     if alpha == "estimate":
         raise ValueError('alpha="estimate" is not available with per_tensor')
@@ -135,14 +135,19 @@ def _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b
     res = DQSGDResult(x=x)
     for t in range(T):
         grad_fn(t, x, grads)
-        norm_fn(plan, grads, norms, ws)
+        if single_pass:
+            pk = packed[:, :table.packed_bytes]
+            _b.norm_quantize_pack_v(plan, table, grads, seed, t, norms, pk, linf=linf)
+        else:
+            norm_fn(plan, grads, norms, ws)
         norms_host.copy_(norms, non_blocking=True)
         if not lagged:
             torch.cuda.current_stream().synchronize()
             b, _ = _b.select_bits_per_tensor(norms_host.numpy(), t, T, eps_hat_q, float(alpha), b_min, b_max)
             table.set(b)
-        pk = packed[:, :table.packed_bytes]
-        _b.quantize_pack_v(plan, table, grads, norms, seed, t, pk)
+        if not single_pass:
+            pk = packed[:, :table.packed_bytes]
+            _b.quantize_pack_v(plan, table, grads, norms, seed, t, pk)
         if on_step is not None:
             torch.cuda.current_stream().synchronize()
             on_step(t, b.copy(), grads, norms_host.numpy(), pk)
