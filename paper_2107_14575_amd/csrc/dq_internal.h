@@ -49,6 +49,7 @@ struct dq_widths {
     dq_cseg_width* d_table;  // device [plan->n_cseg]
     dq_cseg_width* h_stage;  // pinned host staging of the same size
     hipEvent_t uploaded;     // recorded after the last upload; the staging is reused only after it
+    double* d_worker_sq;     // device [DQ_MAX_WORKERS]: per-worker squared norms between the rule's kernels
     int64_t packed_bytes;    // message size for the widths last set, -1 before the first set
     int32_t* b_host;         // [n_seg] widths last set
 };

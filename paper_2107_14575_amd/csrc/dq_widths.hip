@@ -118,6 +118,122 @@ __global__ __launch_bounds__(SB_THREADS) void k_select_bits(
     if (tid == 0 && packed_bytes_out) *packed_bytes_out = sign_bytes + carry;
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same rules for plans with many tensors (a bucketed gradient has tens of thousands), split
+// over several launches so that no single workgroup walks the whole table.  Every sum keeps the
+// order of the one-workgroup kernel, so the widths are the same.
+// ---------------------------------------------------------------------------------------------
+constexpr int SB_STAGE = 2048; // norms of one worker staged in LDS per round
+
+// grid = M: worker i's squared whole-gradient norm (or squared max norm), its tensors added in
+// index order by one lane; the other lanes only fetch the norms into LDS with coalesced loads.
+__global__ __launch_bounds__(SB_THREADS) void k_rule_worker_sums(const float* __restrict__ norms, int32_t n_seg,
+                                                                 int linf, double* __restrict__ worker_sq)
+{
+    __shared__ float stage[SB_STAGE];
+    const int tid = threadIdx.x;
+    const float* row = norms + static_cast<int64_t>(blockIdx.x) * n_seg;
+    double acc = 0.0;
+    for (int32_t base = 0; base < n_seg; base += SB_STAGE) {
+        const int32_t n = n_seg - base < SB_STAGE ? n_seg - base : SB_STAGE;
+        for (int32_t k = tid; k < n; k += SB_THREADS) stage[k] = row[base + k];
+        __syncthreads();
+        if (tid == 0) {
+            int32_t k = 0;
+            for (; k + 16 <= n; k += 16) { // sixteen LDS reads in flight, then the adds in index order
+                double sq[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) sq[j] = static_cast<double>(stage[k + j]) * static_cast<double>(stage[k + j]);
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc = linf ? (sq[j] > acc ? sq[j] : acc) : acc + sq[j];
+            }
+            for (; k < n; ++k) {
+                const double sq = static_cast<double>(stage[k]) * static_cast<double>(stage[k]);
+                acc = linf ? (sq > acc ? sq : acc) : acc + sq;
+            }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) worker_sq[blockIdx.x] = acc;
+}
+
+// grid over max(n_seg, n_cseg): rules 0/1 -- every lane repeats the short sum over the M workers
+// and the search for b, then writes its tensor's and its table entry's width.
+__global__ __launch_bounds__(SB_THREADS) void k_rule_apply_single(
+    const double* __restrict__ worker_sq, int M, int32_t n_seg, int32_t n_cseg, dq_cseg_width* __restrict__ table,
+    double factor, int b_min, int b_max, int32_t* __restrict__ b_out, double* __restrict__ gbar_out)
+{
+    double sum_sq = 0.0;
+    for (int i = 0; i < M; ++i) sum_sq += worker_sq[i];
+    const double gbar = sqrt(sum_sq / static_cast<double>(M));
+    const int b = smallest_width(factor * gbar, b_min, b_max);
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * SB_THREADS + threadIdx.x;
+    if (t == 0 && gbar_out) gbar_out[0] = gbar;
+    if (b_out && t < n_seg) b_out[t] = b;
+    if (t < n_cseg) table[t].b = b;
+}
+
+// grid over max(n_seg, n_cseg): rule 2 -- lane t decides tensor t's width for the outputs and
+// table entry t's width for the kernels.
+__global__ __launch_bounds__(SB_THREADS) void k_rule_tensor_widths(
+    const float* __restrict__ norms, int M, int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ cseg_seg,
+    dq_cseg_width* __restrict__ table, double factor, int b_min, int b_max, int32_t* __restrict__ b_out,
+    double* __restrict__ nbar_out)
+{
+    auto tensor_width = [&](int32_t l, double* nbar_dst) {
+        double acc = 0.0;
+        for (int i = 0; i < M; ++i) {
+            const double n = static_cast<double>(norms[static_cast<int64_t>(i) * n_seg + l]);
+            acc += n * n;
+        }
+        const double nbar = sqrt(acc / static_cast<double>(M));
+        if (nbar_dst) *nbar_dst = nbar;
+        return smallest_width(factor * nbar, b_min, b_max);
+    };
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * SB_THREADS + threadIdx.x;
+    if ((b_out || nbar_out) && t < n_seg) {
+        const int b = tensor_width(static_cast<int32_t>(t), nbar_out ? nbar_out + t : nullptr);
+        if (b_out) b_out[t] = b;
+    }
+    if (t < n_cseg) table[t].b = tensor_width(cseg_seg[t], nullptr);
+}
+
+// one workgroup of 1024 lanes: exclusive scan of the tensors' level bytes; every lane owns a
+// contiguous run of table entries.
+constexpr int SCAN_THREADS = 1024;
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_rule_scan(int32_t n_cseg, const int64_t* __restrict__ cseg_valid_end,
+                                                            dq_cseg_width* __restrict__ table, int64_t sign_bytes,
+                                                            int64_t* __restrict__ packed_bytes_out)
+{
+    __shared__ int64_t part[SCAN_THREADS];
+    const int tid = threadIdx.x;
+    const int32_t per = (n_cseg + SCAN_THREADS - 1) / SCAN_THREADS;
+    const int32_t begin = tid * per < n_cseg ? tid * per : n_cseg;
+    const int32_t end = begin + per < n_cseg ? begin + per : n_cseg;
+    auto level_bytes = [&](int32_t c) {
+        const int64_t len = cseg_valid_end[c] - table[c].seg_start;
+        return (len + DQ_GRANULE - 1) / DQ_GRANULE * (DQ_GRANULE / 8) * table[c].b;
+    };
+    int64_t mine = 0;
+    for (int32_t c = begin; c < end; ++c) mine += level_bytes(c);
+    part[tid] = mine;
+    __syncthreads();
+    for (int off = 1; off < SCAN_THREADS; off <<= 1) {
+        const int64_t add = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    int64_t run = part[tid] - mine;
+    for (int32_t c = begin; c < end; ++c) {
+        const int64_t bytes = level_bytes(c);
+        table[c].level_start = run;
+        run += bytes;
+    }
+    if (tid == SCAN_THREADS - 1 && packed_bytes_out) *packed_bytes_out = sign_bytes + part[tid];
+}
+
 } // namespace
 
 extern "C" int dq_select_bits_per_tensor(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
@@ -191,6 +307,7 @@ extern "C" int dq_widths_create(const dq_plan_t* plan, dq_widths_t** widths_out)
     ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_table), bytes) == hipSuccess;
     ok = ok && hipHostMalloc(reinterpret_cast<void**>(&w->h_stage), bytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&w->uploaded, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_worker_sq), sizeof(double) * DQ_MAX_WORKERS) == hipSuccess;
     if (ok) {
         // the fixed part of the table (where each tensor starts); widths come later
         int32_t c = 0;
@@ -225,6 +342,7 @@ extern "C" void dq_widths_destroy(dq_widths_t* w)
             (void)hipEventDestroy(w->uploaded);
         }
         if (w->d_table) (void)hipFree(w->d_table);
+        if (w->d_worker_sq) (void)hipFree(w->d_worker_sq);
         if (w->h_stage) (void)hipHostFree(w->h_stage);
     }
     if (have_cur) (void)hipSetDevice(cur);
@@ -281,10 +399,27 @@ extern "C" int dq_select_bits_device(const dq_plan_t* plan, dq_widths_t* widths,
     if (rc != DQ_OK) return rc;
     const double root_T_eps = sqrt(static_cast<double>(T) / eps_hat_q);
     const double weight = pow(alpha, static_cast<double>(T - 1 - t) / 2.0);
-    hipLaunchKernelGGL(k_select_bits, dim3(1), dim3(SB_THREADS), 0, static_cast<hipStream_t>(hip_stream), norms_dev,
-                       M, plan->n_seg, plan->n_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table, rule,
-                       root_T_eps, weight, b_min, b_max, plan->padded_elems / 8, b_out_dev, gbar_out_dev,
-                       packed_bytes_out_dev);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (plan->n_seg <= 1024) {
+        hipLaunchKernelGGL(k_select_bits, dim3(1), dim3(SB_THREADS), 0, stream, norms_dev, M, plan->n_seg, plan->n_cseg,
+                           plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table, rule, root_T_eps, weight, b_min,
+                           b_max, plan->padded_elems / 8, b_out_dev, gbar_out_dev, packed_bytes_out_dev);
+    } else {
+        const double factor = root_T_eps * weight;
+        const int32_t widest = plan->n_seg > plan->n_cseg ? plan->n_seg : plan->n_cseg;
+        const dim3 grid((widest + SB_THREADS - 1) / SB_THREADS), block(SB_THREADS);
+        if (rule == 2) {
+            hipLaunchKernelGGL(k_rule_tensor_widths, grid, block, 0, stream, norms_dev, M, plan->n_seg, plan->n_cseg,
+                               plan->d_cseg_seg, widths->d_table, factor, b_min, b_max, b_out_dev, gbar_out_dev);
+        } else {
+            hipLaunchKernelGGL(k_rule_worker_sums, dim3(M), block, 0, stream, norms_dev, plan->n_seg, rule == 1 ? 1 : 0,
+                               widths->d_worker_sq);
+            hipLaunchKernelGGL(k_rule_apply_single, grid, block, 0, stream, widths->d_worker_sq, M, plan->n_seg,
+                               plan->n_cseg, widths->d_table, factor, b_min, b_max, b_out_dev, gbar_out_dev);
+        }
+        hipLaunchKernelGGL(k_rule_scan, dim3(1), dim3(SCAN_THREADS), 0, stream, plan->n_cseg, plan->d_cseg_valid_end,
+                           widths->d_table, plan->padded_elems / 8, packed_bytes_out_dev);
+    }
     if (hipGetLastError() != hipSuccess) return DQ_ERR_HIP;
     // the host no longer knows the widths: messages must have room for b_max everywhere
     int64_t level_bytes = 0;

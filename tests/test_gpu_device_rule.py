@@ -21,7 +21,7 @@ def _device_rule(dq, plan, table, norms_dev, t, T, eps, alpha, b_min, b_max, rul
     return b_out.cpu().numpy(), g_out.cpu().numpy(), int(bytes_out.item())
 
 
-@pytest.mark.parametrize("n_seg", [1, 7, 62, 257, 700])
+@pytest.mark.parametrize("n_seg", [1, 7, 62, 257, 700, 1025, 5000])
 def test_same_widths_as_the_host_rules_and_the_oracle(dq, oracle, n_seg):
     rng = np.random.default_rng(80 + n_seg)
     seg_len = [int(x) for x in rng.choice([0, 1, 64, 128, 129, 300, 1000], size=n_seg)]
