@@ -89,29 +89,18 @@ __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ 
     }
     double* partial = static_cast<double*>(partial_out);
     double acc = 0.0;
-    if (item.count == DQ_NORM_CHUNK) { // a full item (uniform): no masks
+    // masked in binary32 before the conversion (measured faster than a separate unmasked path for full items)
 #pragma unroll
-        for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
-            const double x0 = static_cast<double>(v[k].x), x1 = static_cast<double>(v[k].y);
-            const double x2 = static_cast<double>(v[k].z), x3 = static_cast<double>(v[k].w);
-            acc = __builtin_fma(x0, x0, acc);
-            acc = __builtin_fma(x1, x1, acc);
-            acc = __builtin_fma(x2, x2, acc);
-            acc = __builtin_fma(x3, x3, acc);
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
-            const int e = (k * 256 + tid) * 4;
-            const double x0 = static_cast<double>(e + 0 < item.count ? v[k].x : 0.0f);
-            const double x1 = static_cast<double>(e + 1 < item.count ? v[k].y : 0.0f);
-            const double x2 = static_cast<double>(e + 2 < item.count ? v[k].z : 0.0f);
-            const double x3 = static_cast<double>(e + 3 < item.count ? v[k].w : 0.0f);
-            acc = __builtin_fma(x0, x0, acc);
-            acc = __builtin_fma(x1, x1, acc);
-            acc = __builtin_fma(x2, x2, acc);
-            acc = __builtin_fma(x3, x3, acc);
-        }
+    for (int k = 0; k < DQ_NORM_CHUNK / 1024; ++k) {
+        const int e = (k * 256 + tid) * 4;
+        const double x0 = static_cast<double>(e + 0 < item.count ? v[k].x : 0.0f);
+        const double x1 = static_cast<double>(e + 1 < item.count ? v[k].y : 0.0f);
+        const double x2 = static_cast<double>(e + 2 < item.count ? v[k].z : 0.0f);
+        const double x3 = static_cast<double>(e + 3 < item.count ? v[k].w : 0.0f);
+        acc = __builtin_fma(x0, x0, acc);
+        acc = __builtin_fma(x1, x1, acc);
+        acc = __builtin_fma(x2, x2, acc);
+        acc = __builtin_fma(x3, x3, acc);
     }
     acc = wave_sum(acc);
     if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
