@@ -157,3 +157,37 @@ def test_per_tensor_host_functions_against_the_oracle(dq, oracle):
         plan.close()
     with pytest.raises(dq.DQError):
         dq.select_bits_per_tensor(np.ones((2, 2), dtype=np.float32), 5, 5, 0.1, 0.9, 1, 8)
+
+
+def test_newer_device_entry_points_validate_before_touching_a_gpu(dq):
+    """same for the max norm, update, sign-only, one-pass and per-tensor entry points"""
+    lib = dq.load_library()
+    plan = dq.Plan([1000])           # chunk-local
+    wide = dq.Plan([5000])           # not chunk-local
+    h, hw = plan.handle, wide.handle
+    fake = 0x1000
+    assert plan.chunk_local and not wide.chunk_local
+    assert lib.dq_plan_is_chunk_local(None) == 0
+    assert lib.dq_norm_linf(h, None, 1024, 1, fake, fake, None) == -1
+    assert lib.dq_unpack_dequant_reduce_update(h, fake, 4096, 1, fake, 4, 0.1, None, None, None) == -1   # no x
+    assert lib.dq_unpack_dequant_reduce_update(h, fake, 4096, 1, fake, 4, float("nan"), fake, None, None) == -1
+    assert lib.dq_sign_pack(h, fake, 1024, 1, fake, 112, None) == -1                                   # short stride
+    assert lib.dq_sign_reduce(h, fake, 128, 0, None, fake, None) == -1                                 # M < 1
+    assert lib.dq_sign_majority(h, fake, 128, 1, None, None) == -1                                     # no output
+    assert lib.dq_norm_quantize_pack(hw, fake, 5120, 1, 0, 4, 1, 0, 0, fake, fake, 8192, None) == -1  # not chunk-local
+    assert lib.dq_norm_quantize_pack(h, fake, 1024, 1, 0, 9, 1, 0, 0, fake, fake, 8192, None) == -1   # b = 9
+    assert lib.dq_quantize_pack_v(h, None, fake, 1024, 1, fake, 1, 0, 0, fake, 8192, None) == -1       # no widths
+    assert lib.dq_unpack_dequant_reduce_v(h, None, fake, 8192, 1, fake, fake, None) == -1
+    assert lib.dq_select_bits_device(h, None, fake, 1, 0, 5, 0.1, 0.9, 1, 8, 0, None, None, None, None) == -1
+    assert lib.dq_widths_set(None, None, None) == -1 and lib.dq_widths_packed_bytes(None) == -1
+    lib.dq_widths_destroy(None)      # harmless
+    if not plan.has_device:
+        import ctypes as C
+        w = C.c_void_p()
+        assert lib.dq_widths_create(h, C.byref(w)) == -2 and not w.value
+        assert lib.dq_norm_linf(h, fake, 1024, 1, fake, fake, None) == -2
+        assert lib.dq_sign_pack(h, fake, 1024, 1, fake, 128, None) == -2
+        assert lib.dq_sign_reduce(h, fake, 128, 1, None, fake, None) == -2
+        assert lib.dq_norm_quantize_pack(h, fake, 1024, 1, 0, 4, 1, 0, 0, fake, fake, 8192, None) == -2
+    wide.close()
+    plan.close()
