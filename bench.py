@@ -337,6 +337,10 @@ def main() -> None:
         },
     }
     result["roofline"]["traffic"] = profiled_traffic("k_quantize_pack")
+    # f_Q of Eq. (7) for the timed steps: what the M workers would have put on the wire
+    sent = sum(dq.comm_cost_bits(M, D, b, n_seg, 32) for b in bits)
+    result["comm_cost"] = {"bits_sent": sent, "bits_uncompressed": len(bits) * dq.comm_cost_bits(M, D, 31, 0, 32),
+                           "ratio": round(sent / (len(bits) * dq.comm_cost_bits(M, D, 31, 0, 32)), 5)}
     if one_pass is not None:
         t_fused, t_bred, ms_lagged, n_buckets = one_pass
         result["kernels"]["dq_norm_quantize_pack"] = rl(M * dp * (4 + (b_last + 1) / 8), t_fused)

@@ -1,0 +1,24 @@
+"""The oracle under AddressSanitizer and UndefinedBehaviorSanitizer (host code only): builds
+oracle/dqo.c with oracle/sanitize_check.c and runs the driver on the CPU."""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="needs gcc")
+def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
+    exe = str(tmp_path / "sanitize_check")
+    cmd = ["gcc", "-O1", "-g", "-std=c99", "-ffp-contract=off", "-fno-omit-frame-pointer",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-static-libasan", "-static-libubsan",
+           os.path.join(ROOT, "oracle", "dqo.c"), os.path.join(ROOT, "oracle", "sanitize_check.c"), "-o", exe, "-lm"]
+    build = subprocess.run(cmd, capture_output=True, text=True)
+    if build.returncode != 0 and "cannot find" in build.stderr:
+        pytest.skip("static sanitizer runtimes are not installed")
+    assert build.returncode == 0, build.stderr
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert run.returncode == 0 and run.stdout.strip() == "ok", run.stdout + run.stderr
