@@ -239,16 +239,19 @@ static int widths_ok(const int32_t *b_seg, int32_t n_seg)
     return 1;
 }
 
-/* b_seg == NULL: every tensor uses b level bits; otherwise tensor l uses b_seg[l] (the
- * per-tensor widths further down) and b is ignored. */
+/* b_seg == NULL: every tensor uses b level bits; otherwise worker i's tensor l uses
+ * b_seg[i * b_worker_stride + l] (b_worker_stride = 0: the workers share one set of per-tensor
+ * widths; = n_seg: every worker has its own; both further down) and b is ignored. */
 static int quantize_range(const int64_t *seg_len, int32_t n_seg, const float *grads,
                           int64_t worker_stride, int32_t M, const float *norms /* [M][n_seg] */, int b,
-                          const int32_t *b_seg, uint64_t seed, uint32_t step, uint32_t worker_base,
-                          int64_t p_begin, int64_t p_end, uint8_t *sign, uint8_t *level)
+                          const int32_t *b_seg, int32_t b_worker_stride, uint64_t seed, uint32_t step,
+                          uint32_t worker_base, int64_t p_begin, int64_t p_end, uint8_t *sign, uint8_t *level)
 {
     if (!seg_len || !grads || !norms || !sign || !level) return DQO_ERR_INVALID_ARG;
     if (n_seg < 1 || M < 1) return DQO_ERR_INVALID_ARG;
-    if (b_seg ? !widths_ok(b_seg, n_seg) : (b < 1 || b > 8)) return DQO_ERR_INVALID_ARG;
+    if (!b_seg && (b < 1 || b > 8)) return DQO_ERR_INVALID_ARG;
+    for (int32_t i = 0; b_seg && i < (b_worker_stride ? M : 1); ++i)
+        if (!widths_ok(b_seg + (int64_t)i * b_worker_stride, n_seg)) return DQO_ERR_INVALID_ARG;
     int64_t dp = dqo_padded_elems(seg_len, n_seg);
     if (dp < 0 || p_begin < 0 || p_end > dp || p_begin > p_end) return DQO_ERR_INVALID_ARG;
     if (p_begin % DQO_GRANULE || p_end % DQO_GRANULE) return DQO_ERR_INVALID_ARG;
@@ -264,7 +267,8 @@ static int quantize_range(const int64_t *seg_len, int32_t n_seg, const float *gr
         memset(lv, 0, (size_t)span);
         int64_t start = 0;
         for (int32_t l = 0; l < n_seg; ++l) {
-            const float s = (float)((1u << (b_seg ? b_seg[l] : b)) - 1u); /* quantization levels */
+            const int width = b_seg ? b_seg[(int64_t)i * b_worker_stride + l] : b;
+            const float s = (float)((1u << width) - 1u); /* quantization levels */
             const float N = norms[(int64_t)i * n_seg + l];
             const int usable = norm_is_usable(N);
             const float scale = usable ? s / N : 0.0f; /* one binary32 division per segment */
@@ -300,7 +304,7 @@ int dqo_quantize_range(const int64_t *seg_len, int32_t n_seg, const float *grads
                        uint64_t seed, uint32_t step, uint32_t worker_base, int64_t p_begin,
                        int64_t p_end, uint8_t *sign, uint8_t *level)
 {
-    return quantize_range(seg_len, n_seg, grads, worker_stride, M, norms, b, NULL, seed, step,
+    return quantize_range(seg_len, n_seg, grads, worker_stride, M, norms, b, NULL, 0, seed, step,
                           worker_base, p_begin, p_end, sign, level);
 }
 
@@ -375,11 +379,14 @@ int dqo_unpack(const uint8_t *packed, int64_t dp, int b, uint8_t *sign, uint8_t 
  * of 128); out has p_end - p_begin entries. */
 static int dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign,
                                 const uint8_t *level, int32_t M, const float *norms /* [M][n_seg] */,
-                                int b, const int32_t *b_seg, int64_t p_begin, int64_t p_end, float *out)
+                                int b, const int32_t *b_seg, int32_t b_worker_stride, int64_t p_begin,
+                                int64_t p_end, float *out)
 {
     if (!seg_len || !sign || !level || !norms || !out) return DQO_ERR_INVALID_ARG;
     if (n_seg < 1 || M < 1) return DQO_ERR_INVALID_ARG;
-    if (b_seg ? !widths_ok(b_seg, n_seg) : (b < 1 || b > 8)) return DQO_ERR_INVALID_ARG;
+    if (!b_seg && (b < 1 || b > 8)) return DQO_ERR_INVALID_ARG;
+    for (int32_t i = 0; b_seg && i < (b_worker_stride ? M : 1); ++i)
+        if (!widths_ok(b_seg + (int64_t)i * b_worker_stride, n_seg)) return DQO_ERR_INVALID_ARG;
     int64_t dp = dqo_padded_elems(seg_len, n_seg);
     if (dp < 0 || p_begin < 0 || p_end > dp || p_begin > p_end) return DQO_ERR_INVALID_ARG;
     if (p_begin % DQO_GRANULE || p_end % DQO_GRANULE) return DQO_ERR_INVALID_ARG;
@@ -388,7 +395,6 @@ static int dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uin
     int64_t start = 0;
     for (int32_t l = 0; l < n_seg; ++l) {
         const int64_t len = seg_len[l];
-        const float s = (float)((1u << (b_seg ? b_seg[l] : b)) - 1u);
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < len; ++j) {
             const int64_t P = start + j;
@@ -396,6 +402,8 @@ static int dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uin
             const int64_t q = P - p_begin;
             double acc = 0.0;
             for (int32_t i = 0; i < M; ++i) {
+                const int width = b_seg ? b_seg[(int64_t)i * b_worker_stride + l] : b;
+                const float s = (float)((1u << width) - 1u);
                 const float N = norms[(int64_t)i * n_seg + l];
                 const float unit = norm_is_usable(N) ? N / s : 0.0f;
                 float v = (float)level[(int64_t)i * span + q] * unit;
@@ -413,7 +421,7 @@ int dqo_dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uint8_
                              const uint8_t *level, int32_t M, const float *norms /* [M][n_seg] */,
                              int b, int64_t p_begin, int64_t p_end, float *out)
 {
-    return dequant_reduce_range(seg_len, n_seg, sign, level, M, norms, b, NULL, p_begin, p_end, out);
+    return dequant_reduce_range(seg_len, n_seg, sign, level, M, norms, b, NULL, 0, p_begin, p_end, out);
 }
 
 int dqo_dequant_reduce(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign /* [M][D'] */,
@@ -527,7 +535,7 @@ int dqo_quantize_v_range(const int64_t *seg_len, int32_t n_seg, const float *gra
                          uint32_t worker_base, int64_t p_begin, int64_t p_end, uint8_t *sign, uint8_t *level)
 {
     if (!b_seg) return DQO_ERR_INVALID_ARG;
-    return quantize_range(seg_len, n_seg, grads, worker_stride, M, norms, 0, b_seg, seed, step,
+    return quantize_range(seg_len, n_seg, grads, worker_stride, M, norms, 0, b_seg, 0, seed, step,
                           worker_base, p_begin, p_end, sign, level);
 }
 
@@ -591,7 +599,7 @@ int dqo_dequant_reduce_v_range(const int64_t *seg_len, int32_t n_seg, const uint
                                int64_t p_end, float *out)
 {
     if (!b_seg) return DQO_ERR_INVALID_ARG;
-    return dequant_reduce_range(seg_len, n_seg, sign, level, M, norms, 0, b_seg, p_begin, p_end, out);
+    return dequant_reduce_range(seg_len, n_seg, sign, level, M, norms, 0, b_seg, 0, p_begin, p_end, out);
 }
 
 int dqo_dequant_reduce_v(const int64_t *seg_len, int32_t n_seg, const uint8_t *sign, const uint8_t *level,
@@ -636,6 +644,84 @@ int dqo_unpack_dequant_reduce_v(const int64_t *seg_len, int32_t n_seg, const uin
         dqo_unpack_v(packed + (int64_t)i * packed_stride, seg_len, n_seg, b_seg, sign + (int64_t)i * dp,
                      level + (int64_t)i * dp);
     return dqo_dequant_reduce_v(seg_len, n_seg, sign, level, M, norms, b_seg, out);
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* One bit-width per worker and tensor.                                                           */
+/*                                                                                                */
+/* Lemma 1 is written for workers that share b_t; with worker i using s_i levels the variance of  */
+/* the average is (1/M^2) sum_i d N_i^2 / (4 s_i^2), so the constraint term Gbar^2/s^2 =          */
+/* (1/M) sum_i N_i^2 / s^2 becomes (1/M) sum_i N_i^2 / s_i^2 and the cost d sum_i b_i.  The       */
+/* Lagrangian steps of the appendix give s_i proportional to alpha^((T-1-t)/2) N_i, and the       */
+/* constraint fixes the factor: s*_{t,i} = sqrt(T/eps_hat) alpha^((T-1-t)/2) N_{t,i} -- Eq. (17)  */
+/* with the worker's own norm, which a worker can evaluate without the server.  With a level      */
+/* count per worker AND tensor the same argument gives N_{t,i,l} in that place.                   */
+/*   per_tensor = 0: b[i][l] = b_i from N_i = sqrt(sum_l N_{i,l}^2);  1: b[i][l] from N_{i,l}.    */
+/* ------------------------------------------------------------------------------------------- */
+int dqo_select_bits_per_worker(const float *norms /* [M][n_seg] */, int32_t M, int32_t n_seg, int64_t t,
+                               int64_t T, double eps_hat_q, double alpha, int b_min, int b_max,
+                               int per_tensor, int32_t *b_out /* [M][n_seg] */)
+{
+    if (!norms || !b_out || M < 1 || n_seg < 1 || T < 1 || t < 0 || t >= T) return DQO_ERR_INVALID_ARG;
+    if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQO_ERR_INVALID_ARG;
+    if (b_min < 1 || b_max > 8 || b_min > b_max) return DQO_ERR_INVALID_ARG;
+    const double factor = sqrt((double)T / eps_hat_q) * pow(alpha, (double)(T - 1 - t) / 2.0);
+    for (int32_t i = 0; i < M; ++i) {
+        double worker_sq = 0.0;
+        for (int32_t l = 0; l < n_seg; ++l) {
+            double n = (double)norms[(int64_t)i * n_seg + l];
+            worker_sq += n * n;
+        }
+        for (int32_t l = 0; l < n_seg; ++l) {
+            double n = per_tensor ? (double)norms[(int64_t)i * n_seg + l] : sqrt(worker_sq);
+            double s_star = factor * n;
+            int b = b_max;
+            for (int cand = b_min; cand <= b_max; ++cand) {
+                double levels = (double)((1 << cand) - 1);
+                if (levels >= s_star) { b = cand; break; }
+            }
+            b_out[(int64_t)i * n_seg + l] = b;
+        }
+    }
+    return DQO_OK;
+}
+
+/* Messages with per-worker widths b[i][l]: worker i's message is the per-tensor message for its */
+/* own widths, so the messages of one step can differ in length; each starts at i*packed_stride. */
+int dqo_quantize_pack_w(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t worker_stride,
+                        int32_t M, const float *norms, const int32_t *b /* [M][n_seg] */, uint64_t seed,
+                        uint32_t step, uint32_t worker_base, uint8_t *packed, int64_t packed_stride,
+                        uint8_t *scratch /* 2*D' bytes */)
+{
+    if (!grads || !norms || !b || !packed || !scratch || M < 1) return DQO_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < M; ++i) {
+        const int32_t *bi = b + (int64_t)i * n_seg;
+        int64_t bytes = dqo_packed_bytes_v(seg_len, n_seg, bi);
+        if (bytes < 0 || packed_stride < bytes) return DQO_ERR_INVALID_ARG;
+        int rc = dqo_quantize_pack_v(seg_len, n_seg, grads + (int64_t)i * worker_stride, worker_stride, 1,
+                                     norms + (int64_t)i * n_seg, bi, seed, step, worker_base + (uint32_t)i,
+                                     packed + (int64_t)i * packed_stride, packed_stride, scratch);
+        if (rc != DQO_OK) return rc;
+    }
+    return DQO_OK;
+}
+
+/* Average of messages with per-worker widths: worker i's tensor l dequantizes with unit        */
+/* N_{i,l} / (2^(b[i][l]) - 1).  scratch holds 2*M*D' bytes.                                      */
+int dqo_unpack_dequant_reduce_w(const int64_t *seg_len, int32_t n_seg, const uint8_t *packed,
+                                int64_t packed_stride, int32_t M, const float *norms,
+                                const int32_t *b /* [M][n_seg] */, float *out, uint8_t *scratch)
+{
+    if (!packed || !scratch || !b || M < 1) return DQO_ERR_INVALID_ARG;
+    int64_t dp = dqo_padded_elems(seg_len, n_seg);
+    if (dp < 0) return DQO_ERR_INVALID_ARG;
+    uint8_t *sign = scratch, *level = scratch + (int64_t)M * dp;
+    for (int32_t i = 0; i < M; ++i) {
+        int rc = dqo_unpack_v(packed + (int64_t)i * packed_stride, seg_len, n_seg, b + (int64_t)i * n_seg,
+                              sign + (int64_t)i * dp, level + (int64_t)i * dp);
+        if (rc != DQO_OK) return rc;
+    }
+    return dequant_reduce_range(seg_len, n_seg, sign, level, M, norms, 0, b, n_seg, 0, dp, out);
 }
 
 /* Eq. (7) with per-tensor widths, one iteration: W [ sum_l d_l (b_l + 1) + n_seg B_pre ] bits. */

@@ -92,6 +92,11 @@ def lib():
                                                   f32p, u8p]
         L.dqo_comm_cost_bits_per_tensor.argtypes = [C.c_int, i64p, i32p, C.c_int32, C.c_int]
         L.dqo_comm_cost_bits_per_tensor.restype = C.c_int64
+        L.dqo_select_bits_per_worker.argtypes = [f32p, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_double,
+                                                 C.c_double, C.c_int, C.c_int, C.c_int, i32p]
+        L.dqo_quantize_pack_w.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, f32p, i32p, C.c_uint64,
+                                          C.c_uint32, C.c_uint32, u8p, C.c_int64, u8p]
+        L.dqo_unpack_dequant_reduce_w.argtypes = [i64p, C.c_int32, u8p, C.c_int64, C.c_int32, f32p, i32p, f32p, u8p]
         L.dqo_sign_pack.argtypes = [i64p, C.c_int32, f32p, C.c_int64, C.c_int32, u8p, C.c_int64]
         L.dqo_sign_reduce.argtypes = [i64p, C.c_int32, u8p, C.c_int64, C.c_int32, f32p, C.c_int, f32p]
         L.dqo_update.argtypes = [f32p, f32p, C.c_int64, C.c_float]
@@ -531,4 +536,58 @@ def sign_reduce(seg_len, packed, scales=None, majority=False):
     _check(lib().dqo_sign_reduce(_p(s, C.c_int64), s.size, _p(pk, C.c_uint8), pk.shape[1], M,
                                  _p(sc, C.c_float) if sc is not None else None, 1 if majority else 0,
                                  _p(out, C.c_float)), "sign_reduce")
+    return out
+
+
+# --------------------------------------------------------- one bit-width per worker and tensor
+def _widths2d(b, M, n_seg):
+    a = np.ascontiguousarray(np.asarray(b, dtype=np.int32))
+    if a.shape != (M, n_seg):
+        raise ValueError("widths must be [M][n_seg]")
+    return a
+
+
+def select_bits_per_worker(norms, t, T, eps_hat_q, alpha, b_min, b_max, per_tensor=False):
+    """-> b[M][n_seg] int32."""
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32))
+    if n.ndim != 2:
+        raise ValueError("norms must be [M][n_seg]")
+    b = np.zeros(n.shape, dtype=np.int32)
+    _check(lib().dqo_select_bits_per_worker(_p(n, C.c_float), n.shape[0], n.shape[1], t, T, eps_hat_q, alpha,
+                                            b_min, b_max, 1 if per_tensor else 0, _p(b, C.c_int32)),
+           "select_bits_per_worker")
+    return b
+
+
+def quantize_pack_w(seg_len, grads, norms, b, seed, step, worker_base=0):
+    """-> packed[M][stride], stride = the longest worker message; shorter messages are zero padded."""
+    s = _segs(seg_len)
+    dp = padded_elems(s)
+    g = _grads2d(grads, dp)
+    M = g.shape[0]
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    w = _widths2d(b, M, s.size)
+    stride = max(packed_bytes_v(s, w[i]) for i in range(M))
+    packed = np.zeros((M, stride), dtype=np.uint8)
+    scratch = np.zeros(2 * dp, dtype=np.uint8)
+    _check(lib().dqo_quantize_pack_w(_p(s, C.c_int64), s.size, _p(g, C.c_float), g.shape[1], M, _p(n, C.c_float),
+                                     _p(w, C.c_int32), seed, step, worker_base, _p(packed, C.c_uint8), stride,
+                                     _p(scratch, C.c_uint8)), "quantize_pack_w")
+    return packed
+
+
+def unpack_dequant_reduce_w(seg_len, packed, norms, b):
+    s = _segs(seg_len)
+    dp = padded_elems(s)
+    pk = np.asarray(packed)
+    if pk.dtype != np.uint8 or pk.ndim != 2 or not pk.flags.c_contiguous:
+        raise ValueError("packed must be a C-contiguous uint8 [M][stride] array")
+    M = pk.shape[0]
+    n = np.ascontiguousarray(np.asarray(norms, dtype=np.float32)).reshape(M, s.size)
+    w = _widths2d(b, M, s.size)
+    out = np.zeros(dp, dtype=np.float32)
+    scratch = np.zeros(2 * M * dp, dtype=np.uint8)
+    _check(lib().dqo_unpack_dequant_reduce_w(_p(s, C.c_int64), s.size, _p(pk, C.c_uint8), pk.shape[1], M,
+                                             _p(n, C.c_float), _p(w, C.c_int32), _p(out, C.c_float),
+                                             _p(scratch, C.c_uint8)), "unpack_dequant_reduce_w")
     return out
