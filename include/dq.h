@@ -196,6 +196,28 @@ void dq_widths_destroy(dq_widths_t* widths);
 int dq_widths_set(dq_widths_t* widths, const int32_t* b_host, void* hip_stream);
 int64_t dq_widths_packed_bytes(const dq_widths_t* widths); /* for the widths last set; -1 before */
 
+/* ---- one bit-width per worker (and tensor) ---------------------------------------------------
+ * Lemma 1 is written for workers that share b_t.  With worker i using s_i levels the variance of
+ * the average is (1/M^2) sum_i d N_i^2/(4 s_i^2); the Lagrangian argument behind Eq. (17) then
+ * gives s*_i = sqrt(T/eps_hat_q) alpha^((T-1-t)/2) N_i -- Eq. (17) with the worker's own norm,
+ * which a worker can evaluate without the server -- and N[i][l] in that place when every worker
+ * also has a width per tensor.  Messages of one step then differ in length; each is the
+ * per-tensor message for its worker's widths.
+ */
+
+/* b_out_host [M][n_seg]: per_tensor = 0: row i holds b_i from N_i = sqrt(sum_l N[i][l]^2);
+ * per_tensor != 0: b[i][l] from N[i][l].  Rounding and clamping as dq_select_bits.  Host code. */
+int dq_select_bits_per_worker(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
+                              double eps_hat_q, double alpha, int b_min, int b_max, int per_tensor,
+                              int32_t* b_out_host);
+
+/* A widths table with one row per worker: dq_widths_set then takes b_host [M][n_seg], and the
+ * *_v entry points given it must be called with the same M.  dq_widths_packed_bytes returns the
+ * longest worker's message (what packed_worker_stride_bytes must cover),
+ * dq_widths_worker_packed_bytes one worker's.  dq_select_bits_device does not accept such a table. */
+int dq_widths_create_per_worker(const dq_plan_t* plan, int M, dq_widths_t** widths_out);
+int64_t dq_widths_worker_packed_bytes(const dq_widths_t* widths, int worker);
+
 /* The bit rules evaluated on the GPU, so that a step needs no round trip to the host: reads
  * norms_dev [M][n_seg] and fills `widths` for the kernels enqueued after it on the same stream.
  *   rule  0: dq_select_bits (one b for every tensor), 1: dq_select_bits_linf, 2: dq_select_bits_per_tensor

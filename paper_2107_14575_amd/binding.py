@@ -22,7 +22,8 @@ EXPORTS = (
     "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
     "dq_unpack_dequant_reduce_update", "dq_select_bits_per_tensor", "dq_packed_bytes_v",
     "dq_comm_cost_bits_per_tensor", "dq_widths_create", "dq_widths_destroy", "dq_widths_set",
-    "dq_widths_packed_bytes", "dq_select_bits_device", "dq_quantize_pack_v", "dq_unpack_dequant_reduce_v",
+    "dq_widths_packed_bytes", "dq_widths_create_per_worker", "dq_widths_worker_packed_bytes",
+    "dq_select_bits_per_worker", "dq_select_bits_device", "dq_quantize_pack_v", "dq_unpack_dequant_reduce_v",
     "dq_unpack_dequant_reduce_update_v", "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
 )
 
@@ -104,6 +105,13 @@ def load_library():
     L.dq_widths_set.restype = C.c_int
     L.dq_widths_packed_bytes.argtypes = [vp]
     L.dq_widths_packed_bytes.restype = i64
+    L.dq_widths_create_per_worker.argtypes = [vp, C.c_int, C.POINTER(vp)]
+    L.dq_widths_create_per_worker.restype = C.c_int
+    L.dq_widths_worker_packed_bytes.argtypes = [vp, C.c_int]
+    L.dq_widths_worker_packed_bytes.restype = i64
+    L.dq_select_bits_per_worker.argtypes = [f32p, C.c_int, C.c_int, i64, i64, C.c_double, C.c_double,
+                                            C.c_int, C.c_int, C.c_int, i32p]
+    L.dq_select_bits_per_worker.restype = C.c_int
     L.dq_select_bits_device.argtypes = [vp, vp, vp, C.c_int, i64, i64, C.c_double, C.c_double, C.c_int, C.c_int,
                                         C.c_int, vp, vp, vp, vp]
     L.dq_select_bits_device.restype = C.c_int
@@ -341,18 +349,27 @@ def comm_cost_bits_per_tensor(W: int, seg_len, b_seg, B_pre: int = 32) -> int:
 
 
 class Widths:
-    """Per-tensor level bit-widths of a plan, as a table on the plan's GPU."""
+    """Level bit-widths of a plan's tensors as a table on the plan's GPU: one row shared by the
+    workers (workers=None), or one row per worker (workers=M; b_seg is then [M][n_seg])."""
 
-    def __init__(self, plan: Plan, b_seg=None, stream=None):
+    def __init__(self, plan: Plan, b_seg=None, stream=None, workers=None):
         handle = C.c_void_p()
-        _check("dq_widths_create", load_library().dq_widths_create(plan.handle, C.byref(handle)))
+        if workers is None:
+            _check("dq_widths_create", load_library().dq_widths_create(plan.handle, C.byref(handle)))
+        else:
+            _check("dq_widths_create_per_worker",
+                   load_library().dq_widths_create_per_worker(plan.handle, int(workers), C.byref(handle)))
         self._h = handle
         self.plan = plan
+        self.workers = workers
         if b_seg is not None:
             self.set(b_seg, stream)
 
     def set(self, b_seg, stream=None) -> None:
-        b = _widths_array(b_seg, self.plan.n_seg)
+        rows = 1 if self.workers is None else int(self.workers)
+        b = np.ascontiguousarray(np.asarray(b_seg, dtype=np.int32).reshape(-1))
+        if b.size != rows * self.plan.n_seg:
+            raise ValueError("one width per tensor" if rows == 1 else "one width per worker and tensor")
         _check("dq_widths_set", load_library().dq_widths_set(self.handle, b.ctypes.data_as(C.POINTER(C.c_int32)),
                                                              _stream_handle(stream)))
 
@@ -366,6 +383,9 @@ class Widths:
     def packed_bytes(self) -> int:
         return int(load_library().dq_widths_packed_bytes(self.handle))
 
+    def worker_packed_bytes(self, worker: int) -> int:
+        return int(load_library().dq_widths_worker_packed_bytes(self.handle, worker))
+
     def close(self) -> None:
         if getattr(self, "_h", None) is not None and self._h.value:
             load_library().dq_widths_destroy(self._h)
@@ -376,6 +396,20 @@ class Widths:
             self.close()
         except Exception:
             pass
+
+
+def select_bits_per_worker(norms_host, t: int, T: int, eps_hat_q: float, alpha: float, b_min: int, b_max: int,
+                           per_tensor: bool = False):
+    """norms_host [M][n_seg] -> b[M][n_seg] int32: Eq. (17) with each worker's own norm."""
+    n = np.ascontiguousarray(np.asarray(norms_host, dtype=np.float32))
+    if n.ndim != 2:
+        raise ValueError("norms must be [M][n_seg]")
+    b = np.zeros(n.shape, dtype=np.int32)
+    _check("dq_select_bits_per_worker",
+           load_library().dq_select_bits_per_worker(n.ctypes.data_as(C.POINTER(C.c_float)), n.shape[0], n.shape[1],
+                                                    t, T, eps_hat_q, alpha, b_min, b_max, 1 if per_tensor else 0,
+                                                    b.ctypes.data_as(C.POINTER(C.c_int32))))
+    return b
 
 
 RULES = {"single": 0, "single_linf": 1, "per_tensor": 2}

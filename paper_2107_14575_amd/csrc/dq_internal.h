@@ -46,12 +46,14 @@ struct dq_cseg_width {
 
 struct dq_widths {
     const dq_plan* plan;
-    dq_cseg_width* d_table;  // device [plan->n_cseg]
+    int32_t n_workers;       // 1: the workers share the widths; M: one row of the table per worker
+    dq_cseg_width* d_table;  // device [n_workers][plan->n_cseg]
     dq_cseg_width* h_stage;  // pinned host staging of the same size
     hipEvent_t uploaded;     // recorded after the last upload; the staging is reused only after it
     double* d_worker_sq;     // device [DQ_MAX_WORKERS]: per-worker squared norms between the rule's kernels
-    int64_t packed_bytes;    // message size for the widths last set, -1 before the first set
-    int32_t* b_host;         // [n_seg] widths last set
+    int64_t packed_bytes;    // message size for the widths last set (the longest worker's), -1 before the first set
+    int64_t* worker_bytes;   // [n_workers] message size of each row
+    int32_t* b_host;         // [n_workers][n_seg] widths last set
 };
 
 static inline bool dq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

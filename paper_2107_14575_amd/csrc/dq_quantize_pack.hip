@@ -216,13 +216,16 @@ template <int TILES, int NORM> // NORM as in k_quantize_pack
 __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_v(
     const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
     const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
-    const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths, int64_t padded_elems,
+    const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths_table,
+    int32_t widths_worker_stride, int64_t padded_elems,
     uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
     int64_t packed_stride, float* __restrict__ norms_out)
 {
     constexpr int CHUNK = QP_TILE * TILES;
     constexpr int MAX_LOCAL_SEG = CHUNK / DQ_GRANULE;
     static_assert(NORM == 0 || CHUNK == DQ_CHUNK, "the fused norm works on 4096-element chunks");
+    // this worker's row of the table (stride 0: the workers share one row)
+    const dq_cseg_width* __restrict__ widths = widths_table + static_cast<int64_t>(blockIdx.y) * widths_worker_stride;
 
     __shared__ float lds_scale[MAX_LOCAL_SEG];
     __shared__ float lds_levels[MAX_LOCAL_SEG];      // s = 2^b - 1 of the segment
@@ -472,6 +475,8 @@ int quantize_v_entry(int norm_mode, const dq_plan_t* plan, const dq_widths_t* wi
     if (widths->plan != plan || widths->packed_bytes < 0) return DQ_ERR_INVALID_ARG;
     if (norm_mode != 0 && !plan->chunk_local) return DQ_ERR_INVALID_ARG;
     if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
+    if (widths->n_workers != 1 && widths->n_workers != M) return DQ_ERR_INVALID_ARG;
+    const int32_t row_stride = widths->n_workers == 1 ? 0 : plan->n_cseg;
     if (worker_stride_elems < plan->padded_elems || (worker_stride_elems & 3)) return DQ_ERR_INVALID_ARG;
     if (packed_worker_stride_bytes < widths->packed_bytes || (packed_worker_stride_bytes & 15))
         return DQ_ERR_INVALID_ARG;
@@ -493,7 +498,7 @@ int quantize_v_entry(int norm_mode, const dq_plan_t* plan, const dq_widths_t* wi
 #define DQ_LAUNCH_QV(NORM)                                                                                        \
     hipLaunchKernelGGL((k_quantize_pack_v<TILES, NORM>), grid, block, 0, stream, grads_dev, worker_stride_elems,  \
                        norms_in, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end,     \
-                       widths->d_table, plan->padded_elems, static_cast<uint32_t>(seed),                          \
+                       widths->d_table, row_stride, plan->padded_elems, static_cast<uint32_t>(seed),              \
                        static_cast<uint32_t>(seed >> 32), step, worker_base, packed_dev, packed_worker_stride_bytes, \
                        norms_out)
     if (norm_mode == 0)

@@ -67,6 +67,30 @@ __device__ __forceinline__ void for_each_level(const uint32_t (&wd)[B], F&& f)
     }
 }
 
+// One worker's contribution to a lane's 32 elements: acc[k] += sgn_k * level_k * unit, from the
+// worker's sign dword and its B level dwords.
+template <int B>
+__device__ __forceinline__ void accumulate_words(uint32_t sg, const uint32_t (&wd)[B], float unit,
+                                                 float (&acc)[UR_PER_LANE])
+{
+    for_each_level<B>(wd, [&](int k, float lv) {
+        // sign bit of element k on top of the unit, whose own sign bit is always clear
+        const float su = __uint_as_float(__float_as_uint(unit) | ((sg << (31 - k)) & 0x80000000u));
+        acc[k] = __builtin_fmaf(lv, su, acc[k]);
+    });
+}
+
+// The same from eight loaded dwords of which the first B count (per-worker widths).
+template <int B>
+__device__ __forceinline__ void accumulate_first_words(uint32_t sg, const uint32_t (&wd8)[8], float unit,
+                                                       float (&acc)[UR_PER_LANE])
+{
+    uint32_t wd[B];
+#pragma unroll
+    for (int q = 0; q < B; ++q) wd[q] = wd8[q];
+    accumulate_words<B>(sg, wd, unit, acc);
+}
+
 // The M workers' contributions to a lane's 32 elements: acc[k] += sgn * level * unit, workers in
 // ascending order.  sign_ptr / level_ptr address worker 0's sign dword and B level dwords of the
 // lane; unit_ptr[w] is worker w's N/s for the lane's segment.
@@ -96,13 +120,7 @@ __device__ __forceinline__ void accumulate_lane(const uint8_t* __restrict__ sign
             for (int q = 0; q < B; ++q) wd[q] = lp[q];
         }
     };
-    auto accumulate = [&](uint32_t sg, const uint32_t (&wd)[B], float unit) {
-        for_each_level<B>(wd, [&](int k, float lv) {
-            // sign bit of element k on top of the unit, whose own sign bit is always clear
-            const float su = __uint_as_float(__float_as_uint(unit) | ((sg << (31 - k)) & 0x80000000u));
-            acc[k] = __builtin_fmaf(lv, su, acc[k]);
-        });
-    };
+    auto accumulate = [&](uint32_t sg, const uint32_t (&wd)[B], float unit) { accumulate_words<B>(sg, wd, unit, acc); };
     // workers four at a time, so that four messages' loads are in flight together
     constexpr int GROUP = 4;
     int w = 0;
@@ -265,6 +283,100 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_v(
         case 7: accumulate_lane<7>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
         case 8: accumulate_lane<8>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
         default: break; // the host only uploads widths in 1..8
+        }
+    }
+    finish_tile<UPDATE>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
+}
+
+// Per-worker widths: every worker's message has its own layout, so a lane looks up b and the
+// place of its level dwords once per worker and decodes that worker's dwords with the code
+// specialised for its b.
+struct worker_entry { // what a lane needs to decode one worker's tensor: 16 bytes, one LDS read
+    float unit;         // N / s for that worker and tensor
+    int32_t b;          // level bits
+    int64_t level_base; // level-plane byte offset of padded index P is level_base + (P >> 3) * b
+};
+
+template <bool UPDATE>
+__global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_w(
+    const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
+    int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths, int64_t padded_elems,
+    float inv_M, float* __restrict__ out, float* __restrict__ x, float eta)
+{
+    extern __shared__ __align__(16) uint8_t lds_raw[];
+    float4* lds_out = reinterpret_cast<float4*>(lds_raw);
+    worker_entry* lds_entry = reinterpret_cast<worker_entry*>(lds_raw + UR_TILE * sizeof(float)); // [local seg][M]
+
+    const int tid = threadIdx.x;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * UR_TILE;
+    const int64_t tile_end = tile0 + UR_TILE < padded_elems ? tile0 + UR_TILE : padded_elems;
+    const int64_t P0 = tile0 + tid * UR_PER_LANE;
+    const bool active = P0 < tile_end;
+
+    const int32_t seg_first = granule_cseg[tile0 >> 7];
+    const int32_t seg_last = granule_cseg[(tile_end - 1) >> 7];
+    const int n_local = seg_last - seg_first + 1;
+    for (int i = tid; i < n_local * M; i += UR_THREADS) {
+        const int local = i / M, w = i - local * M;
+        const dq_cseg_width e = widths[static_cast<int64_t>(w) * n_cseg + seg_first + local];
+        const float S = static_cast<float>((1 << e.b) - 1);
+        const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + local]];
+        worker_entry we;
+        we.unit = N >= DQ_MIN_NORM ? N / S : 0.0f;
+        we.b = e.b;
+        we.level_base = e.level_start - (e.seg_start >> 3) * e.b; // seg_start is a multiple of 128
+        lds_entry[i] = we;
+    }
+    int32_t c = 0;
+    int64_t n_valid = 0;
+    if (active) {
+        c = granule_cseg[P0 >> 7];
+        n_valid = cseg_valid_end[c] - P0;
+    }
+    __syncthreads();
+
+    float acc[UR_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < UR_PER_LANE; ++k) acc[k] = 0.0f;
+
+    if (active) {
+        const worker_entry* entry = lds_entry + (c - seg_first) * M;
+        const uint8_t* sign_ptr = packed + (P0 >> 3);
+        const uint8_t* level_plane = packed + (padded_elems >> 3);
+        // workers four at a time: sign dwords and up to eight level dwords each are fetched first
+        // (loads past a worker's width are skipped), then decoded width by width
+        constexpr int GROUP = 4;
+        for (int w0 = 0; w0 < M; w0 += GROUP) {
+            uint32_t sg[GROUP], wd[GROUP][8];
+            worker_entry we[GROUP];
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i) {
+                we[i].b = 0;
+                if (w0 + i < M) {
+                    we[i] = entry[w0 + i];
+                    const int64_t msg = static_cast<int64_t>(w0 + i) * packed_stride;
+                    const uint32_t* lp =
+                        reinterpret_cast<const uint32_t*>(level_plane + msg + we[i].level_base + (P0 >> 3) * we[i].b);
+                    sg[i] = *reinterpret_cast<const uint32_t*>(sign_ptr + msg);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) wd[i][q] = q < we[i].b ? lp[q] : 0u;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i) {
+                switch (we[i].b) {
+                case 1: accumulate_first_words<1>(sg[i], wd[i], we[i].unit, acc); break;
+                case 2: accumulate_first_words<2>(sg[i], wd[i], we[i].unit, acc); break;
+                case 3: accumulate_first_words<3>(sg[i], wd[i], we[i].unit, acc); break;
+                case 4: accumulate_first_words<4>(sg[i], wd[i], we[i].unit, acc); break;
+                case 5: accumulate_first_words<5>(sg[i], wd[i], we[i].unit, acc); break;
+                case 6: accumulate_first_words<6>(sg[i], wd[i], we[i].unit, acc); break;
+                case 7: accumulate_first_words<7>(sg[i], wd[i], we[i].unit, acc); break;
+                case 8: accumulate_first_words<8>(sg[i], wd[i], we[i].unit, acc); break;
+                default: break; // past the last worker, or a width the host never uploads
+                }
+            }
         }
     }
     finish_tile<UPDATE>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
@@ -454,6 +566,7 @@ int reduce_entry_v(const dq_plan_t* plan, const dq_widths_t* widths, const uint8
     if (!plan || !widths || !packed_dev || !norms_dev || (!out_dev && !x_dev)) return DQ_ERR_INVALID_ARG;
     if (widths->plan != plan || widths->packed_bytes < 0) return DQ_ERR_INVALID_ARG;
     if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
+    if (widths->n_workers != 1 && widths->n_workers != M) return DQ_ERR_INVALID_ARG;
     if (packed_worker_stride_bytes < widths->packed_bytes || (packed_worker_stride_bytes & 15))
         return DQ_ERR_INVALID_ARG;
     if (!dq_aligned16(packed_dev) || !dq_aligned16(out_dev) || !dq_aligned16(x_dev) ||
@@ -469,6 +582,20 @@ int reduce_entry_v(const dq_plan_t* plan, const dq_widths_t* widths, const uint8
     const dim3 grid(static_cast<unsigned>(n_tiles)), block(UR_THREADS);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const float inv_M = 1.0f / static_cast<float>(M);
+    if (widths->n_workers != 1) {
+        const size_t lds_w = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(worker_entry);
+        if (x_dev)
+            hipLaunchKernelGGL(k_unpack_dequant_reduce_w<true>, grid, block, lds_w, stream, packed_dev,
+                               packed_worker_stride_bytes, M, norms_dev, plan->n_seg, plan->n_cseg,
+                               plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table,
+                               plan->padded_elems, inv_M, out_dev, x_dev, eta);
+        else
+            hipLaunchKernelGGL(k_unpack_dequant_reduce_w<false>, grid, block, lds_w, stream, packed_dev,
+                               packed_worker_stride_bytes, M, norms_dev, plan->n_seg, plan->n_cseg,
+                               plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, widths->d_table,
+                               plan->padded_elems, inv_M, out_dev, x_dev, eta);
+        return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+    }
     if (x_dev)
         hipLaunchKernelGGL(k_unpack_dequant_reduce_v<true>, grid, block, lds_bytes, stream, packed_dev,
                            packed_worker_stride_bytes, M, norms_dev, plan->n_seg, plan->d_granule_cseg,

@@ -289,38 +289,43 @@ extern "C" int64_t dq_packed_bytes_v(const dq_plan_t* plan, const int32_t* b_hos
     return bytes;
 }
 
-extern "C" int dq_widths_create(const dq_plan_t* plan, dq_widths_t** widths_out)
+namespace {
+
+int widths_create(const dq_plan_t* plan, int n_workers, dq_widths_t** widths_out)
 {
     if (!widths_out) return DQ_ERR_INVALID_ARG;
     *widths_out = nullptr;
-    if (!plan) return DQ_ERR_INVALID_ARG;
+    if (!plan || n_workers < 1 || n_workers > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
     const int rc = dq_plan_check_device(plan);
     if (rc != DQ_OK) return rc;
     dq_widths* w = new (std::nothrow) dq_widths();
     if (!w) return DQ_ERR_ALLOC;
     memset(w, 0, sizeof(*w));
     w->plan = plan;
+    w->n_workers = n_workers;
     w->packed_bytes = -1;
-    const size_t bytes = sizeof(dq_cseg_width) * static_cast<size_t>(plan->n_cseg > 0 ? plan->n_cseg : 1);
-    w->b_host = static_cast<int32_t*>(malloc(sizeof(int32_t) * plan->n_seg));
-    bool ok = w->b_host != nullptr;
+    const size_t rows = static_cast<size_t>(n_workers);
+    const size_t bytes = sizeof(dq_cseg_width) * rows * static_cast<size_t>(plan->n_cseg > 0 ? plan->n_cseg : 1);
+    w->b_host = static_cast<int32_t*>(malloc(sizeof(int32_t) * rows * plan->n_seg));
+    w->worker_bytes = static_cast<int64_t*>(malloc(sizeof(int64_t) * rows));
+    bool ok = w->b_host != nullptr && w->worker_bytes != nullptr;
     ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_table), bytes) == hipSuccess;
     ok = ok && hipHostMalloc(reinterpret_cast<void**>(&w->h_stage), bytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&w->uploaded, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_worker_sq), sizeof(double) * DQ_MAX_WORKERS) == hipSuccess;
     if (ok) {
         // the fixed part of the table (where each tensor starts); widths come later
-        int32_t c = 0;
-        for (int32_t l = 0; l < plan->n_seg; ++l) {
-            if (plan->seg_len[l] == 0) continue;
-            w->h_stage[c].level_start = 0;
-            w->h_stage[c].seg_start = plan->seg_start[l];
-            w->h_stage[c].b = 0;
-            w->h_stage[c].reserved = 0;
-            ++c;
-        }
-        ok = c == 0 || hipMemcpy(w->d_table, w->h_stage, sizeof(dq_cseg_width) * static_cast<size_t>(c),
-                                 hipMemcpyHostToDevice) == hipSuccess;
+        size_t k = 0;
+        for (int r = 0; r < n_workers; ++r)
+            for (int32_t l = 0; l < plan->n_seg; ++l) {
+                if (plan->seg_len[l] == 0) continue;
+                w->h_stage[k].level_start = 0;
+                w->h_stage[k].seg_start = plan->seg_start[l];
+                w->h_stage[k].b = 0;
+                w->h_stage[k].reserved = 0;
+                ++k;
+            }
+        ok = k == 0 || hipMemcpy(w->d_table, w->h_stage, sizeof(dq_cseg_width) * k, hipMemcpyHostToDevice) == hipSuccess;
     }
     if (!ok) {
         (void)hipGetLastError();
@@ -329,6 +334,18 @@ extern "C" int dq_widths_create(const dq_plan_t* plan, dq_widths_t** widths_out)
     }
     *widths_out = w;
     return DQ_OK;
+}
+
+} // namespace
+
+extern "C" int dq_widths_create(const dq_plan_t* plan, dq_widths_t** widths_out)
+{
+    return widths_create(plan, 1, widths_out);
+}
+
+extern "C" int dq_widths_create_per_worker(const dq_plan_t* plan, int M, dq_widths_t** widths_out)
+{
+    return widths_create(plan, M, widths_out);
 }
 
 extern "C" void dq_widths_destroy(dq_widths_t* w)
@@ -347,6 +364,7 @@ extern "C" void dq_widths_destroy(dq_widths_t* w)
     }
     if (have_cur) (void)hipSetDevice(cur);
     free(w->b_host);
+    free(w->worker_bytes);
     delete w;
 }
 
@@ -354,31 +372,45 @@ extern "C" int dq_widths_set(dq_widths_t* w, const int32_t* b_host, void* hip_st
 {
     if (!w || !b_host) return DQ_ERR_INVALID_ARG;
     const dq_plan* plan = w->plan;
-    for (int32_t l = 0; l < plan->n_seg; ++l)
-        if (b_host[l] < 1 || b_host[l] > 8) return DQ_ERR_INVALID_ARG;
+    const int64_t n_widths = static_cast<int64_t>(w->n_workers) * plan->n_seg;
+    for (int64_t k = 0; k < n_widths; ++k)
+        if (b_host[k] < 1 || b_host[k] > 8) return DQ_ERR_INVALID_ARG;
     const int rc = dq_plan_check_device(plan);
     if (rc != DQ_OK) return rc;
     // the previous upload must have left the staging buffer before it is overwritten
     if (w->packed_bytes >= 0 && hipEventSynchronize(w->uploaded) != hipSuccess) return DQ_ERR_HIP;
-    int64_t level_bytes = 0;
-    int32_t c = 0;
-    for (int32_t l = 0; l < plan->n_seg; ++l) {
-        if (plan->seg_len[l] == 0) continue;
-        dq_cseg_width& e = w->h_stage[c++];
-        e.level_start = level_bytes;
-        e.seg_start = plan->seg_start[l];
-        e.b = b_host[l];
-        e.reserved = 0;
-        level_bytes += padded_len(plan->seg_len[l]) / 8 * b_host[l];
+    size_t k = 0;
+    int64_t longest = 0;
+    for (int r = 0; r < w->n_workers; ++r) {
+        const int32_t* row = b_host + static_cast<int64_t>(r) * plan->n_seg;
+        int64_t level_bytes = 0;
+        for (int32_t l = 0; l < plan->n_seg; ++l) {
+            if (plan->seg_len[l] == 0) continue;
+            dq_cseg_width& e = w->h_stage[k++];
+            e.level_start = level_bytes;
+            e.seg_start = plan->seg_start[l];
+            e.b = row[l];
+            e.reserved = 0;
+            level_bytes += padded_len(plan->seg_len[l]) / 8 * row[l];
+        }
+        w->worker_bytes[r] = plan->padded_elems / 8 + level_bytes;
+        longest = w->worker_bytes[r] > longest ? w->worker_bytes[r] : longest;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (c > 0 && hipMemcpyAsync(w->d_table, w->h_stage, sizeof(dq_cseg_width) * static_cast<size_t>(c),
-                                hipMemcpyHostToDevice, stream) != hipSuccess)
+    if (k > 0 && hipMemcpyAsync(w->d_table, w->h_stage, sizeof(dq_cseg_width) * k, hipMemcpyHostToDevice, stream) !=
+                     hipSuccess)
         return DQ_ERR_HIP;
     if (hipEventRecord(w->uploaded, stream) != hipSuccess) return DQ_ERR_HIP;
-    memcpy(w->b_host, b_host, sizeof(int32_t) * plan->n_seg);
-    w->packed_bytes = plan->padded_elems / 8 + level_bytes;
+    memcpy(w->b_host, b_host, sizeof(int32_t) * static_cast<size_t>(n_widths));
+    w->packed_bytes = longest;
     return DQ_OK;
+}
+
+extern "C" int64_t dq_widths_worker_packed_bytes(const dq_widths_t* w, int worker)
+{
+    if (!w || w->packed_bytes < 0 || worker < 0) return -1;
+    if (w->n_workers == 1) return w->worker_bytes[0];
+    return worker < w->n_workers ? w->worker_bytes[worker] : -1;
 }
 
 extern "C" int64_t dq_widths_packed_bytes(const dq_widths_t* w) { return w ? w->packed_bytes : -1; }
@@ -389,6 +421,7 @@ extern "C" int dq_select_bits_device(const dq_plan_t* plan, dq_widths_t* widths,
                                      int64_t* packed_bytes_out_dev, void* hip_stream)
 {
     if (!plan || !widths || !norms_dev || widths->plan != plan) return DQ_ERR_INVALID_ARG;
+    if (widths->n_workers != 1) return DQ_ERR_INVALID_ARG; // the device rules decide widths the workers share
     if (M < 1 || M > DQ_MAX_WORKERS || T < 1 || t < 0 || t >= T) return DQ_ERR_INVALID_ARG;
     if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQ_ERR_INVALID_ARG;
     if (b_min < 1 || b_max > 8 || b_min > b_max || rule < 0 || rule > 2) return DQ_ERR_INVALID_ARG;
@@ -428,5 +461,36 @@ extern "C" int dq_select_bits_device(const dq_plan_t* plan, dq_widths_t* widths,
         level_bytes += padded_len(plan->seg_len[l]) / 8 * b_max;
     }
     widths->packed_bytes = plan->padded_elems / 8 + level_bytes;
+    widths->worker_bytes[0] = widths->packed_bytes;
+    return DQ_OK;
+}
+
+// Eq. (17) with each worker's own norm (or each worker's tensor norms): see the header.
+extern "C" int dq_select_bits_per_worker(const float* norms_host, int M, int n_seg, int64_t t, int64_t T,
+                                         double eps_hat_q, double alpha, int b_min, int b_max, int per_tensor,
+                                         int32_t* b_out_host)
+{
+    if (!norms_host || !b_out_host || M < 1 || n_seg < 1) return DQ_ERR_INVALID_ARG;
+    if (T < 1 || t < 0 || t >= T) return DQ_ERR_INVALID_ARG;
+    if (!(eps_hat_q > 0.0) || !(alpha > 0.0) || !(alpha <= 1.0)) return DQ_ERR_INVALID_ARG;
+    if (b_min < 1 || b_max > 8 || b_min > b_max) return DQ_ERR_INVALID_ARG;
+    const double factor = sqrt(static_cast<double>(T) / eps_hat_q) * pow(alpha, static_cast<double>(T - 1 - t) / 2.0);
+    for (int i = 0; i < M; ++i) {
+        const float* row = norms_host + static_cast<int64_t>(i) * n_seg;
+        double worker_sq = 0.0;
+        for (int l = 0; l < n_seg; ++l) worker_sq += static_cast<double>(row[l]) * static_cast<double>(row[l]);
+        const double worker_norm = sqrt(worker_sq);
+        for (int l = 0; l < n_seg; ++l) {
+            const double s_star = factor * (per_tensor ? static_cast<double>(row[l]) : worker_norm);
+            int b = b_max;
+            for (int cand = b_min; cand <= b_max; ++cand) {
+                if (static_cast<double>((1 << cand) - 1) >= s_star) {
+                    b = cand;
+                    break;
+                }
+            }
+            b_out_host[static_cast<int64_t>(i) * n_seg + l] = b;
+        }
+    }
     return DQ_OK;
 }

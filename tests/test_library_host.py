@@ -159,6 +159,24 @@ def test_per_tensor_host_functions_against_the_oracle(dq, oracle):
         dq.select_bits_per_tensor(np.ones((2, 2), dtype=np.float32), 5, 5, 0.1, 0.9, 1, 8)
 
 
+def test_per_worker_rule_against_the_oracle(dq, oracle):
+    rng = np.random.default_rng(8)
+    for _ in range(500):
+        M, n_seg = int(rng.integers(1, 17)), int(rng.integers(1, 10))
+        norms = (10 ** rng.uniform(-6, 1, size=(M, n_seg))).astype(np.float32)
+        T = int(rng.integers(1, 500))
+        t = int(rng.integers(0, T))
+        eps, alpha = float(10 ** rng.uniform(-8, 2)), float(rng.uniform(0.5, 1.0))
+        b_min = int(rng.integers(1, 9))
+        b_max = int(rng.integers(b_min, 9))
+        for per_tensor in (False, True):
+            got = dq.select_bits_per_worker(norms, t, T, eps, alpha, b_min, b_max, per_tensor=per_tensor)
+            want = oracle.select_bits_per_worker(norms, t, T, eps, alpha, b_min, b_max, per_tensor=per_tensor)
+            assert np.array_equal(got, want)
+    with pytest.raises(dq.DQError):
+        dq.select_bits_per_worker(np.ones((2, 2), dtype=np.float32), 0, 5, 0.0, 0.9, 1, 8)
+
+
 def test_newer_device_entry_points_validate_before_touching_a_gpu(dq):
     """same for the max norm, update, sign-only, one-pass and per-tensor entry points"""
     lib = dq.load_library()
