@@ -20,6 +20,8 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
     (``plan.chunk_local``: no tensor crosses a multiple of 4096 padded elements, e.g. a gradient
     cut into buckets) the worker side is the single pass ``dq_norm_quantize_pack``; one_pass=False
     keeps the two calls.
+  * per_worker=True: every worker takes Eq. (17) with its own norm (``dq_select_bits_per_worker``;
+    with per_tensor=True also one width per tensor); b_t in the result are [M][n_seg] arrays.
   * device_rule=True: the rule runs on the GPU (``dq_select_bits_device``) and the loop never waits
     for the host; b_t and the cost are read back once at the end.  alpha must be a number.
   * p: 2 or "inf", the norm of Eq. (5) (the paper leaves p open): ``dq_norm``/``dq_select_bits`` or
@@ -49,7 +51,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         b_min: int = 1, b_max: int = 8, tau: int = 1, lagged: bool = True, seed: int = 0,
         loss_fn: Optional[Callable[["torch.Tensor"], float]] = None, B_pre: int = 32,
         on_step: Optional[Callable] = None, p: Union[int, str] = 2, per_tensor: bool = False,
-        device_rule: bool = False, one_pass: bool = True) -> DQSGDResult:
+        device_rule: bool = False, one_pass: bool = True, per_worker: bool = False) -> DQSGDResult:
     """grad_fn(t, x, grads_out) fills grads_out[M][D'] (float32, CUDA, padded layout) with the M
     workers' stochastic gradients at x.  on_step(t, b_t, grads, norms_host, packed) is called after
     the quantize pass of every iteration (tests use it to feed the same bytes to the oracle)."""
@@ -57,6 +59,11 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         raise ValueError('p must be 2 or "inf"')
     norm_fn, rule = (_b.norm, _b.select_bits) if p == 2 else (_b.norm_linf, _b.select_bits_linf)
     dp, n_seg = plan.padded_elems, plan.n_seg
+    if per_worker:
+        if device_rule or p != 2:
+            raise ValueError("per_worker runs the host rule with the l2 norm")
+        return _run_per_worker(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged,
+                               seed, B_pre, on_step, per_tensor, one_pass and lagged and plan.chunk_local)
     if device_rule:
         if per_tensor and p != 2:
             raise ValueError("per_tensor uses the tensors' own norms: leave p at 2 or run the max norm without it")
@@ -223,4 +230,50 @@ def _run_device_rule(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, 
             res.bits.append(int(b_host[t, 0]))
             res.cost_bits += _b.comm_cost_bits(M, int(plan.seg_len.sum()), int(b_host[t, 0]), n_seg, B_pre)
             res.gbar.append(float(g_host[t, 0]))
+    return res
+
+
+def _run_per_worker(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged, seed, B_pre,
+                    on_step, per_tensor, single_pass) -> DQSGDResult:
+    import numpy as np
+    if alpha == "estimate":
+        raise ValueError('alpha="estimate" is not available with per_worker')
+    dp, n_seg = plan.padded_elems, plan.n_seg
+    dev = x0.device
+    x = x0.clone()
+    grads = torch.zeros((M, dp), dtype=torch.float32, device=dev)
+    norms = torch.empty((M, n_seg), dtype=torch.float32, device=dev)
+    norms_host = torch.empty((M, n_seg), dtype=torch.float32).pin_memory()
+    ws = torch.empty(plan.workspace_bytes(M), dtype=torch.uint8, device=dev)
+    packed = torch.zeros((M, _b.packed_bytes_v(plan, [b_max] * n_seg)), dtype=torch.uint8, device=dev)
+    b = np.broadcast_to(np.asarray(b0, dtype=np.int32), (M, n_seg)).copy()
+    table = _b.Widths(plan, b, workers=M)
+    res = DQSGDResult(x=x)
+    for t in range(T):
+        grad_fn(t, x, grads)
+        if single_pass:
+            _b.norm_quantize_pack_v(plan, table, grads, seed, t, norms, packed)
+        else:
+            _b.norm(plan, grads, norms, ws)
+        norms_host.copy_(norms, non_blocking=True)
+        if not lagged:
+            torch.cuda.current_stream().synchronize()
+            b = _b.select_bits_per_worker(norms_host.numpy(), t, T, eps_hat_q, float(alpha), b_min, b_max, per_tensor)
+            table.set(b)
+        if not single_pass:
+            _b.quantize_pack_v(plan, table, grads, norms, seed, t, packed)
+        if on_step is not None:
+            torch.cuda.current_stream().synchronize()
+            on_step(t, b.copy(), grads, norms_host.numpy(), packed[:, :table.packed_bytes])
+        _b.unpack_dequant_reduce_update_v(plan, table, packed, norms, eta, x)
+        res.bits.append(b.copy())
+        res.cost_bits += sum(_b.comm_cost_bits_per_tensor(1, plan.seg_len, b[i], B_pre) for i in range(M))
+        torch.cuda.current_stream().synchronize()
+        res.gbar.append(float(np.sqrt((norms_host.numpy().astype(np.float64) ** 2).sum() / M)))
+        if lagged and t + 1 < T and (t + 1) % tau == 0:
+            b = _b.select_bits_per_worker(norms_host.numpy(), t + 1, T, eps_hat_q, float(alpha), b_min, b_max,
+                                          per_tensor)
+            table.set(b)
+    torch.cuda.synchronize()
+    table.close()
     return res

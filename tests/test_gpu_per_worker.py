@@ -152,3 +152,51 @@ def test_argument_checks(dq):
     torch.cuda.synchronize()
     table.close()
     plan.close()
+
+
+@pytest.mark.parametrize("per_tensor", [False, True])
+def test_algorithm1_loop_with_per_worker_widths(dq, oracle, per_tensor):
+    """workers whose noise differs by 8x each step: every worker picks its own width; widths,
+    bitstreams and the model follow the oracle loop"""
+    from paper_2107_14575_amd import dqsgd
+    seg_len = [700, 300, 77]
+    plan = dq.Plan(seg_len)
+    starts, dp = wl.seg_starts(seg_len)
+    M, T, eta, alpha, tau, eps_hat = 4, 30, 0.2, 0.9, 5, 0.05
+    gen = torch.Generator().manual_seed(134)
+    valid = torch.zeros(dp)
+    for st, n in zip(starts, seg_len):
+        valid[st:st + n] = 1
+    target = (torch.randn(dp, generator=gen) * valid).cuda()
+    scale = torch.tensor([0.02, 0.05, 0.1, 0.16]).view(1, M, 1)
+    noise = (torch.randn((T, M, dp), generator=gen) * scale * valid).cuda()
+
+    def grad_fn(t, x, grads):
+        grads.copy_((x - target).unsqueeze(0) + noise[t])
+
+    x_or = np.zeros(dp, dtype=np.float32)
+    state = dict(b=np.full((M, 3), 2, dtype=np.int32), bits=[])
+
+    def on_step(t, b, grads, norms, packed):
+        g_host = np.ascontiguousarray(grads.cpu().numpy())
+        assert np.array_equal(b, state["b"]), t
+        want = oracle.quantize_pack_w(seg_len, g_host, norms, b, SEED, t)
+        got = packed.cpu().numpy()
+        for i in range(M):
+            n = oracle.packed_bytes_v(seg_len, b[i])
+            assert np.array_equal(got[i, :n], want[i, :n]), (t, i)
+        oracle.update(x_or, oracle.unpack_dequant_reduce_w(seg_len, want, norms, b), eta)
+        state["bits"].append(b.copy())
+        if t + 1 < T and (t + 1) % tau == 0:
+            state["b"] = oracle.select_bits_per_worker(norms, t + 1, T, eps_hat, alpha, 1, 8, per_tensor=per_tensor)
+
+    x0 = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    res = dqsgd.run(plan, x0, grad_fn, M, T, eta, eps_hat, alpha, b0=2, b_min=1, b_max=8, tau=tau, lagged=True,
+                    seed=SEED, on_step=on_step, per_worker=True, per_tensor=per_tensor)
+    assert all(np.array_equal(a, c) for a, c in zip(res.bits, state["bits"]))
+    last = res.bits[-1]
+    assert len(np.unique(last[:, 0])) >= 2                       # the workers really differ
+    x_gpu = res.x.cpu().numpy()
+    assert np.abs(x_gpu - x_or).max() <= T * (2.0 ** -23 * np.abs(x_or).max() + eta * 1e-6 * 4.0)
+    assert float((res.x - target).norm()) < 0.2 * float(target.norm())
+    plan.close()
