@@ -194,6 +194,10 @@ def main() -> None:
     t_qv = timed_loop(lambda: dq.quantize_pack_v(plan, table, grads, norms_dev, wl.QUANT_SEED, T, pk_last))
     t_rv = timed_loop(lambda: dq.unpack_dequant_reduce_v(plan, table, pk_last, norms_dev, out))
     table.close()
+    # the reduce with a widths table that has one row per worker (here all rows equal)
+    table_w = dq.Widths(plan, [[b_last] * n_seg] * M, workers=M)
+    t_rw = timed_loop(lambda: dq.unpack_dequant_reduce_v(plan, table_w, pk_last, norms_dev, out))
+    table_w.close()
     # sign-only baseline (one bit per element)
     sign_msgs = packed[:, :dp // 8]
     t_sp = timed_loop(lambda: dq.sign_pack(plan, grads, sign_msgs))
@@ -330,6 +334,7 @@ def main() -> None:
             "dq_norm_linf": rl(n_bytes, t_ninf),
             "dq_quantize_pack_v": rl(M * dp * (4 + (b_last + 1) / 8), t_qv),
             "dq_unpack_dequant_reduce_v": rl(dp * (M * (b_last + 1) / 8 + 4), t_rv),
+            "dq_unpack_dequant_reduce_v_per_worker": rl(dp * (M * (b_last + 1) / 8 + 4), t_rw),
             "dq_sign_pack": rl(M * dp * (4 + 1 / 8), t_sp),
             "dq_sign_reduce": rl(dp * (M / 8 + 4), t_sr),
             "dq_sign_majority": rl(dp * (M / 8 + 4), t_sm),
