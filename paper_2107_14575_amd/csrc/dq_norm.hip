@@ -11,6 +11,9 @@
 // per 4096 elements.
 // The max norm takes the same two passes with binary32 maxima in place of the binary64 sums (a
 // maximum does not depend on the order; a NaN element never wins a comparison).
+//
+// Plans in which no tensor crosses a multiple of 4096 padded elements take k_norm_chunk instead:
+// one workgroup per chunk finishes the norms of all the tensors inside it, one pass.
 #include "dq_chunk_norm.h"
 #include "dq_internal.h"
 

@@ -1,5 +1,7 @@
 // Per-tensor bit-widths: the table that tells the kernels each tensor's level bits and where its
-// level fields start in the message, the bit rule that fills it, and the cost accounting.
+// level fields start in the message (one row shared by the workers, or one row per worker), the
+// bit rules that fill it -- on the host, or on the GPU without a round trip -- and the cost
+// accounting.
 //
 // Rule.  The paper's program (the one Eq. (17) solves, appendix "Proof of Eq. (17)") with one
 // level count s_l per tensor: Lemma 1's variance bound of an iteration becomes
