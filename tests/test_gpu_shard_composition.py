@@ -80,3 +80,30 @@ def test_shard_reduce_equals_the_slice_of_the_full_reduce(dq, b):
         shard.close()
     assert covered == dp
     plan.close()
+
+
+def test_rank_by_rank_worker_side_equals_the_simulated_workers(dq):
+    """rank i quantizing its own gradient with worker_base = i produces row i of the M-worker call
+    (the Philox counter carries the global worker id), also through the one-pass kernel"""
+    seg_len = [512] * 30 + [100]
+    starts, dp = wl.seg_starts(seg_len)
+    M, b = 5, 3
+    gen = torch.Generator().manual_seed(141)
+    g = torch.zeros((M, dp), dtype=torch.float32)
+    for st, n in zip(starts, seg_len):
+        g[:, st:st + n] = torch.randn((M, n), generator=gen) * 1e-2
+    plan = dq.Plan(seg_len)
+    g_dev = g.cuda()
+    norms = gpu_norm(dq, plan, g_dev)
+    together = torch.zeros((M, plan.packed_bytes(b)), dtype=torch.uint8, device="cuda")
+    dq.quantize_pack(plan, g_dev, norms, b, SEED, 9, together)
+    for i in range(M):
+        alone = torch.zeros((1, plan.packed_bytes(b)), dtype=torch.uint8, device="cuda")
+        dq.quantize_pack(plan, g_dev[i:i + 1], norms[i:i + 1], b, SEED, 9, alone, worker_base=i)
+        fused = torch.zeros_like(alone)
+        n_out = torch.empty((1, plan.n_seg), dtype=torch.float32, device="cuda")
+        dq.norm_quantize_pack(plan, g_dev[i:i + 1], b, SEED, 9, n_out, fused, worker_base=i)
+        torch.cuda.synchronize()
+        assert torch.equal(alone[0], together[i]) and torch.equal(fused[0], together[i])
+        assert torch.equal(n_out.view(torch.int32), norms[i:i + 1].view(torch.int32))
+    plan.close()
