@@ -37,6 +37,24 @@ import torch
 from . import binding as _b
 
 
+# Table 1 of the paper ("Parameters"): iterations, learning rate, batch size, and the two DQ-SGD
+# hyper-parameters k and alpha per task; W = 8 workers and tau = 100 throughout (Section 6).  The
+# paper never defines k; the only free constant of Eq. (17) besides alpha is sqrt(T / eps_hat_Q),
+# so k is read as that factor: s*_t = k * alpha^((T-1-t)/2) * G-bar_t, eps_hat_Q = T / k^2.
+PAPER_PRESETS = {
+    "ag_news_bilstm": dict(T=1000, eta=0.005, batch=32, k=5.0, alpha=0.994, W=8, tau=100),
+    "cifar10_resnet18": dict(T=6000, eta=0.1, batch=32, k=20.0, alpha=0.999, W=8, tau=100),
+    "cifar100_resnet34": dict(T=6000, eta=0.01, batch=64, k=10.0, alpha=0.999, W=8, tau=100),
+}
+
+
+def eps_hat_from_k(T: int, k: float) -> float:
+    """eps_hat_Q for which sqrt(T / eps_hat_Q) = k (the reading of Table 1's k stated above)."""
+    if T < 1 or not k > 0:
+        raise ValueError("T >= 1 and k > 0")
+    return T / (k * k)
+
+
 @dataclass
 class DQSGDResult:
     x: "torch.Tensor"                      # x_T, padded layout

@@ -130,3 +130,26 @@ def test_one_step_of_the_loop_obeys_theorem3_isotropic_case(oracle):
     assert abs(vals.mean() - want) <= 5 * se + 1e-6 * want
     # and the quantization term is what separates it from the noiseless contraction
     assert vals.mean() > beta * F(x_t) + 0.5 * 0.5 * lam * eta ** 2 * tr_sigma
+
+
+def test_table1_presets_and_the_reading_of_k(oracle):
+    """with eps_hat = T/k^2 the rule is s*_t = k alpha^((T-1-t)/2) Gbar_t: at the last iteration
+    s* = k Gbar, so b jumps exactly where k*Gbar crosses 2^b - 1"""
+    from paper_2107_14575_amd import dqsgd
+    assert set(dqsgd.PAPER_PRESETS) == {"ag_news_bilstm", "cifar10_resnet18", "cifar100_resnet34"}
+    for name, p in dqsgd.PAPER_PRESETS.items():
+        eps = dqsgd.eps_hat_from_k(p["T"], p["k"])
+        assert abs(np.sqrt(p["T"] / eps) - p["k"]) < 1e-12
+        for levels in (1, 3, 7, 15, 31, 63, 127):
+            below = np.array([[levels * 0.999 / p["k"]]], dtype=np.float32)
+            above = np.array([[levels * 1.001 / p["k"]]], dtype=np.float32)
+            b_lo, _ = oracle.select_bits(below, p["T"] - 1, p["T"], eps, p["alpha"], 1, 8)
+            b_hi, _ = oracle.select_bits(above, p["T"] - 1, p["T"], eps, p["alpha"], 1, 8)
+            assert (1 << b_lo) - 1 == levels and b_hi == b_lo + 1
+        # at t = 0 the factor is smaller by alpha^((T-1)/2): the schedule starts lower and rises
+        g = np.array([[1.0]], dtype=np.float32)
+        b0, _ = oracle.select_bits(g, 0, p["T"], eps, p["alpha"], 1, 8)
+        bT, _ = oracle.select_bits(g, p["T"] - 1, p["T"], eps, p["alpha"], 1, 8)
+        assert b0 <= bT
+    with pytest.raises(ValueError):
+        dqsgd.eps_hat_from_k(10, 0.0)
