@@ -16,15 +16,21 @@ GRANULE = 128
 MAX_WORKERS = 64
 
 EXPORTS = (
-    "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems",
-    "dq_plan_segment_start", "dq_packed_bytes", "dq_workspace_bytes", "dq_plan_has_device",
-    "dq_plan_is_chunk_local", "dq_norm_quantize_pack", "dq_norm_quantize_pack_v",
-    "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_probe_stream",
-    "dq_unpack_dequant_reduce_update", "dq_select_bits_per_tensor", "dq_packed_bytes_v",
-    "dq_comm_cost_bits_per_tensor", "dq_widths_create", "dq_widths_destroy", "dq_widths_set",
-    "dq_widths_packed_bytes", "dq_widths_create_per_worker", "dq_widths_worker_packed_bytes",
-    "dq_select_bits_per_worker", "dq_select_bits_device", "dq_quantize_pack_v", "dq_unpack_dequant_reduce_v",
-    "dq_unpack_dequant_reduce_update_v", "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority", "dq_alpha_est", "dq_comm_cost_bits", "dq_status_string",
+    # plan and sizes
+    "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems", "dq_plan_segment_start",
+    "dq_plan_has_device", "dq_plan_is_chunk_local", "dq_packed_bytes", "dq_packed_bytes_v", "dq_workspace_bytes",
+    # the path
+    "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack",
+    "dq_unpack_dequant_reduce", "dq_unpack_dequant_reduce_update", "dq_norm_quantize_pack",
+    # widths per tensor / per worker, rules on the GPU
+    "dq_select_bits_per_tensor", "dq_select_bits_per_worker", "dq_select_bits_device", "dq_widths_create",
+    "dq_widths_create_per_worker", "dq_widths_destroy", "dq_widths_set", "dq_widths_packed_bytes",
+    "dq_widths_worker_packed_bytes", "dq_quantize_pack_v", "dq_norm_quantize_pack_v", "dq_unpack_dequant_reduce_v",
+    "dq_unpack_dequant_reduce_update_v",
+    # sign-only baseline
+    "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority",
+    # accounting and aids
+    "dq_alpha_est", "dq_comm_cost_bits", "dq_comm_cost_bits_per_tensor", "dq_probe_stream", "dq_status_string",
 )
 
 
