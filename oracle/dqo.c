@@ -127,6 +127,26 @@ int dqo_norm(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t 
     return DQO_OK;
 }
 
+/* A worker's squared whole-gradient norm sum_l N_{i,l}^2 in binary64: the tensors are taken in */
+/* blocks of 1024, each block added in index order, then the block sums added in index order.  */
+/* Up to 1024 tensors this is the plain running sum; beyond that it is the same sum with the   */
+/* parentheses moved (the paper says nothing about the order of a sum), chosen so that a       */
+/* gradient cut into tens of thousands of buckets can be summed by many lanes at once.          */
+#define DQO_SUM_BLOCK 1024
+static double worker_squared_norm(const float *row, int32_t n_seg)
+{
+    double total = 0.0;
+    for (int32_t base = 0; base < n_seg; base += DQO_SUM_BLOCK) {
+        double block = 0.0;
+        for (int32_t l = base; l < n_seg && l < base + DQO_SUM_BLOCK; ++l) {
+            double n = (double)row[l];
+            block += n * n;
+        }
+        total += block;
+    }
+    return total;
+}
+
 /* ------------------------------------------------------------------------------------------- */
 /* O2: the bit rule, Eq. (17), in level-bit convention.                                           */
 /*   G2 = (1/M) sum_i ||g^(i)||^2, ||g^(i)||^2 = sum_l N_{i,l}^2   (G-bar_t^2 of Lemma 1)         */
@@ -143,11 +163,8 @@ int dqo_select_bits(const float *norms /* [M][n_seg] */, int32_t M, int32_t n_se
     if (b_min < 1 || b_max > 8 || b_min > b_max) return DQO_ERR_INVALID_ARG;
     double sum = 0.0;
     for (int32_t i = 0; i < M; ++i) {
-        double worker_sq = 0.0; /* ||g^(i)||^2 = sum_l N_{i,l}^2: a worker's squared norm first ... */
-        for (int32_t l = 0; l < n_seg; ++l) {
-            double n = (double)norms[(int64_t)i * n_seg + l];
-            worker_sq += n * n;
-        }
+        /* ||g^(i)||^2 = sum_l N_{i,l}^2: a worker's squared norm first ...                        */
+        double worker_sq = worker_squared_norm(norms + (int64_t)i * n_seg, n_seg);
         sum += worker_sq;       /* ... then the mean over workers, as Lemma 1 writes G-bar_t^2   */
     }
     double G2 = sum / (double)M;
@@ -667,11 +684,7 @@ int dqo_select_bits_per_worker(const float *norms /* [M][n_seg] */, int32_t M, i
     if (b_min < 1 || b_max > 8 || b_min > b_max) return DQO_ERR_INVALID_ARG;
     const double factor = sqrt((double)T / eps_hat_q) * pow(alpha, (double)(T - 1 - t) / 2.0);
     for (int32_t i = 0; i < M; ++i) {
-        double worker_sq = 0.0;
-        for (int32_t l = 0; l < n_seg; ++l) {
-            double n = (double)norms[(int64_t)i * n_seg + l];
-            worker_sq += n * n;
-        }
+        double worker_sq = worker_squared_norm(norms + (int64_t)i * n_seg, n_seg);
         for (int32_t l = 0; l < n_seg; ++l) {
             double n = per_tensor ? (double)norms[(int64_t)i * n_seg + l] : sqrt(worker_sq);
             double s_star = factor * n;

@@ -58,6 +58,22 @@ struct dq_widths {
 
 static inline bool dq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// sum_l N_l^2 of one worker's row of norms in binary64: blocks of DQ_SUM_BLOCK tensors, each added
+// in index order, then the block sums in index order (the plain running sum up to 1024 tensors).
+// Host and device rules share this order so that they agree bit for bit.
+constexpr int DQ_SUM_BLOCK = 1024;
+static inline double dq_worker_squared_norm(const float* row, int32_t n_seg)
+{
+    double total = 0.0;
+    for (int32_t base = 0; base < n_seg; base += DQ_SUM_BLOCK) {
+        double block = 0.0;
+        for (int32_t l = base; l < n_seg && l < base + DQ_SUM_BLOCK; ++l)
+            block += static_cast<double>(row[l]) * static_cast<double>(row[l]);
+        total += block;
+    }
+    return total;
+}
+
 // Fills n floats with +0 (a kernel, not a memset: callers may capture the entry points in a graph).
 int dq_zero_floats(float* dst_dev, int64_t n, hipStream_t stream);
 

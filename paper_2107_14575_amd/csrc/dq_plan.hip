@@ -209,12 +209,13 @@ static int select_bits(bool linf, const float* norms_host, int M, int n_seg, int
     for (int i = 0; i < M; ++i) {
         const float* row = norms_host + static_cast<int64_t>(i) * n_seg;
         double worker_sq = 0.0;
-        for (int l = 0; l < n_seg; ++l) {
-            const double sq = static_cast<double>(row[l]) * static_cast<double>(row[l]);
-            if (linf)
+        if (linf) {
+            for (int l = 0; l < n_seg; ++l) {
+                const double sq = static_cast<double>(row[l]) * static_cast<double>(row[l]);
                 worker_sq = sq > worker_sq ? sq : worker_sq;
-            else
-                worker_sq += sq;
+            }
+        } else {
+            worker_sq = dq_worker_squared_norm(row, n_seg);
         }
         sum_sq += worker_sq;
     }

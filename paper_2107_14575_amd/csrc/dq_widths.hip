@@ -125,38 +125,41 @@ __global__ __launch_bounds__(SB_THREADS) void k_select_bits(
 // over several launches so that no single workgroup walks the whole table.  Every sum keeps the
 // order of the one-workgroup kernel, so the widths are the same.
 // ---------------------------------------------------------------------------------------------
-constexpr int SB_STAGE = 2048; // norms of one worker staged in LDS per round
-
-// grid = M: worker i's squared whole-gradient norm (or squared max norm), its tensors added in
-// index order by one lane; the other lanes only fetch the norms into LDS with coalesced loads.
+// grid = M: worker i's squared whole-gradient norm (or squared max norm).  Lane j adds blocks j,
+// j + 256, ... of DQ_SUM_BLOCK tensors, each in index order; lane 0 then adds the block sums in
+// index order -- the order of dq_worker_squared_norm.  (A maximum needs no order.)
 __global__ __launch_bounds__(SB_THREADS) void k_rule_worker_sums(const float* __restrict__ norms, int32_t n_seg,
-                                                                 int linf, double* __restrict__ worker_sq)
+                                                                 int linf, double* __restrict__ worker_sq,
+                                                                 double* __restrict__ block_sums)
 {
-    __shared__ float stage[SB_STAGE];
     const int tid = threadIdx.x;
     const float* row = norms + static_cast<int64_t>(blockIdx.x) * n_seg;
-    double acc = 0.0;
-    for (int32_t base = 0; base < n_seg; base += SB_STAGE) {
-        const int32_t n = n_seg - base < SB_STAGE ? n_seg - base : SB_STAGE;
-        for (int32_t k = tid; k < n; k += SB_THREADS) stage[k] = row[base + k];
-        __syncthreads();
-        if (tid == 0) {
-            int32_t k = 0;
-            for (; k + 16 <= n; k += 16) { // sixteen LDS reads in flight, then the adds in index order
-                double sq[16];
+    const int32_t n_blocks = (n_seg + DQ_SUM_BLOCK - 1) / DQ_SUM_BLOCK;
+    double* mine = block_sums + static_cast<int64_t>(blockIdx.x) * n_blocks;
+    for (int32_t blk = tid; blk < n_blocks; blk += SB_THREADS) {
+        const int32_t begin = blk * DQ_SUM_BLOCK;
+        const int32_t end = begin + DQ_SUM_BLOCK < n_seg ? begin + DQ_SUM_BLOCK : n_seg;
+        double acc = 0.0;
+        int32_t l = begin;
+        for (; l + 16 <= end; l += 16) { // sixteen loads in flight, then the adds in index order
+            double sq[16];
 #pragma unroll
-                for (int j = 0; j < 16; ++j) sq[j] = static_cast<double>(stage[k + j]) * static_cast<double>(stage[k + j]);
+            for (int j = 0; j < 16; ++j) sq[j] = static_cast<double>(row[l + j]) * static_cast<double>(row[l + j]);
 #pragma unroll
-                for (int j = 0; j < 16; ++j) acc = linf ? (sq[j] > acc ? sq[j] : acc) : acc + sq[j];
-            }
-            for (; k < n; ++k) {
-                const double sq = static_cast<double>(stage[k]) * static_cast<double>(stage[k]);
-                acc = linf ? (sq > acc ? sq : acc) : acc + sq;
-            }
+            for (int j = 0; j < 16; ++j) acc = linf ? (sq[j] > acc ? sq[j] : acc) : acc + sq[j];
         }
-        __syncthreads();
+        for (; l < end; ++l) {
+            const double sq = static_cast<double>(row[l]) * static_cast<double>(row[l]);
+            acc = linf ? (sq > acc ? sq : acc) : acc + sq;
+        }
+        mine[blk] = acc;
     }
-    if (tid == 0) worker_sq[blockIdx.x] = acc;
+    __syncthreads(); // the block sums written above are read below by lane 0 of the same workgroup
+    if (tid == 0) {
+        double total = 0.0;
+        for (int32_t blk = 0; blk < n_blocks; ++blk) total = linf ? (mine[blk] > total ? mine[blk] : total) : total + mine[blk];
+        worker_sq[blockIdx.x] = total;
+    }
 }
 
 // grid over max(n_seg, n_cseg): rules 0/1 -- every lane repeats the short sum over the M workers
@@ -314,7 +317,10 @@ int widths_create(const dq_plan_t* plan, int n_workers, dq_widths_t** widths_out
     ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_table), bytes) == hipSuccess;
     ok = ok && hipHostMalloc(reinterpret_cast<void**>(&w->h_stage), bytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&w->uploaded, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_worker_sq), sizeof(double) * DQ_MAX_WORKERS) == hipSuccess;
+    // per-worker squared norms, followed by the block sums they are made of (multi-launch rules)
+    const size_t n_sum_blocks = static_cast<size_t>((plan->n_seg + DQ_SUM_BLOCK - 1) / DQ_SUM_BLOCK);
+    ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_worker_sq),
+                         sizeof(double) * DQ_MAX_WORKERS * (1 + n_sum_blocks)) == hipSuccess;
     if (ok) {
         // the fixed part of the table (where each tensor starts); widths come later
         size_t k = 0;
@@ -448,7 +454,7 @@ extern "C" int dq_select_bits_device(const dq_plan_t* plan, dq_widths_t* widths,
                                plan->d_cseg_seg, widths->d_table, factor, b_min, b_max, b_out_dev, gbar_out_dev);
         } else {
             hipLaunchKernelGGL(k_rule_worker_sums, dim3(M), block, 0, stream, norms_dev, plan->n_seg, rule == 1 ? 1 : 0,
-                               widths->d_worker_sq);
+                               widths->d_worker_sq, widths->d_worker_sq + DQ_MAX_WORKERS);
             hipLaunchKernelGGL(k_rule_apply_single, grid, block, 0, stream, widths->d_worker_sq, M, plan->n_seg,
                                plan->n_cseg, widths->d_table, factor, b_min, b_max, b_out_dev, gbar_out_dev);
         }
@@ -479,9 +485,7 @@ extern "C" int dq_select_bits_per_worker(const float* norms_host, int M, int n_s
     const double factor = sqrt(static_cast<double>(T) / eps_hat_q) * pow(alpha, static_cast<double>(T - 1 - t) / 2.0);
     for (int i = 0; i < M; ++i) {
         const float* row = norms_host + static_cast<int64_t>(i) * n_seg;
-        double worker_sq = 0.0;
-        for (int l = 0; l < n_seg; ++l) worker_sq += static_cast<double>(row[l]) * static_cast<double>(row[l]);
-        const double worker_norm = sqrt(worker_sq);
+        const double worker_norm = sqrt(dq_worker_squared_norm(row, n_seg));
         for (int l = 0; l < n_seg; ++l) {
             const double s_star = factor * (per_tensor ? static_cast<double>(row[l]) : worker_norm);
             int b = b_max;

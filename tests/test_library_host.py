@@ -209,3 +209,19 @@ def test_newer_device_entry_points_validate_before_touching_a_gpu(dq):
         assert lib.dq_norm_quantize_pack(h, fake, 1024, 1, 0, 4, 1, 0, 0, fake, fake, 8192, None) == -2
     wide.close()
     plan.close()
+
+
+def test_rules_agree_with_the_oracle_beyond_one_summation_block(dq, oracle):
+    """more than 1024 tensors: a worker's squared norm is added block by block; host and oracle agree
+    bit for bit, and the value is the plain sum to rounding"""
+    rng = np.random.default_rng(9)
+    for n_seg in (1024, 1025, 3000, 70000):
+        M = 3
+        norms = (10 ** rng.uniform(-4, 0, size=(M, n_seg))).astype(np.float32)
+        got = dq.select_bits(norms, 2, 9, 1e-3, 0.9, 1, 8)
+        want = oracle.select_bits(norms, 2, 9, 1e-3, 0.9, 1, 8)
+        assert got == want
+        plain = np.sqrt((norms.astype(np.float64) ** 2).sum() / M)
+        assert abs(got[1] - plain) <= 1e-13 * plain
+        assert np.array_equal(dq.select_bits_per_worker(norms, 2, 9, 1e-3, 0.9, 1, 8),
+                              oracle.select_bits_per_worker(norms, 2, 9, 1e-3, 0.9, 1, 8))
