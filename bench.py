@@ -47,10 +47,12 @@ def make_workload(name: str, M: int | None, log2d: int | None):
     return seg_len, grads, label
 
 
-def cpu_baseline(seg_len, grads_dev, b: int, target_elems: int):
+def cpu_baseline(seg_len, grads_dev, b: int, target_elems: int, n_steps: int):
     """The oracle as it stands, timed on the host over a bounded sample: the first
     min(D', target) elements of every worker of the same workload (single-tensor workloads) or the
-    whole gradient when it is small.  One full step: norm + quantize+pack + unpack+dequant+average."""
+    whole gradient when it is small.  n_steps full steps (norm + quantize+pack +
+    unpack+dequant+average, the step index advancing as in Algorithm 1), about 10 s of host work
+    at the defaults."""
     import numpy as np
     from oracle import dqo
     from paper_2107_14575_amd import workloads as wl
@@ -69,15 +71,16 @@ def cpu_baseline(seg_len, grads_dev, b: int, target_elems: int):
     dqo.build()
     threads = dqo.num_threads()
     t0 = time.perf_counter()
-    norms = dqo.norm(sample_seg, g)
-    packed = dqo.quantize_pack(sample_seg, g, norms, b, wl.QUANT_SEED, 0)
-    out = dqo.unpack_dequant_reduce(sample_seg, packed, norms, b)
+    for step in range(n_steps):
+        norms = dqo.norm(sample_seg, g)
+        packed = dqo.quantize_pack(sample_seg, g, norms, b, wl.QUANT_SEED, step)
+        out = dqo.unpack_dequant_reduce(sample_seg, packed, norms, b)
     dt = time.perf_counter() - t0
     assert out.shape[0] == wl.seg_starts(sample_seg)[1]
-    n_in = M * sum(sample_seg) * 4
+    n_in = n_steps * M * sum(sample_seg) * 4
     return {"value": round(n_in / dt / 1e9, 4), "unit": "GB/s of fp32 input", "cores": threads,
             "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"one step (norm, quantize+pack, unpack+dequant+average) at b={b} on {what}"}
+            "sample": f"{n_steps} steps (norm, quantize+pack, unpack+dequant+average) at b={b} on {what}"}
 
 
 def main() -> None:
@@ -92,6 +95,7 @@ def main() -> None:
     ap.add_argument("--fixed-bits", type=int, default=0, help="use this b every step instead of the rule")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=26)
+    ap.add_argument("--cpu-steps", type=int, default=5, help="steps of the oracle timed for cpu_baseline")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, one plain device copy of the output buffer (4*D' bytes "
                          "read, 4*D' written): the known-size reference for scaling rocprofv3's "
@@ -378,7 +382,8 @@ def main() -> None:
         result["roofline"]["frac_of_plain_kernel"] = result["kernels"]["dq_quantize_pack"].get("frac_of_plain_kernel")
     if not args.no_cpu_baseline:
         b_mode = max(set(bits), key=bits.count)
-        result["cpu_baseline"] = cpu_baseline(seg_len, grads, b_mode, 1 << args.cpu_sample_log2)
+        result["cpu_baseline"] = cpu_baseline(seg_len, grads, b_mode, 1 << args.cpu_sample_log2,
+                                                  max(1, args.cpu_steps))
     print(json.dumps(result), flush=True)
     plan.close()
 
