@@ -380,6 +380,30 @@ def main() -> None:
         if ceil.get("read_only"):
             result["kernels"]["dq_norm"]["frac_of_plain_kernel"] = round(result["kernels"]["dq_norm"]["achieved"] / ceil["read_only"], 4)
         result["roofline"]["frac_of_plain_kernel"] = result["kernels"]["dq_quantize_pack"].get("frac_of_plain_kernel")
+    # both fused passes at every level width b = 1..8 on the same gradients (not part of `value`):
+    # time, algorithmic GB/s, fraction of the HBM peak and of the plain kernel at that b's own mix
+    big = M * dp * 4 >= (1 << 28)
+    per_b = {}
+    for b in range(1, 9):
+        pk_b = packed[:, :plan.packed_bytes(b)]
+        tq = timed_loop(lambda: dq.quantize_pack(plan, grads, norms_dev, b, wl.QUANT_SEED, T, pk_b), 3)
+        tr = timed_loop(lambda: dq.unpack_dequant_reduce(plan, pk_b, norms_dev, b, out), 3)
+        q, r = rl(M * dp * (4 + (b + 1) / 8), tq), rl(dp * (M * (b + 1) / 8 + 4), tr)
+        row = {"quantize_pack_ms": q["avg_ms"], "quantize_pack_GBps": q["achieved"], "quantize_pack_frac": q["frac"],
+               "reduce_ms": r["avg_ms"], "reduce_GBps": r["achieved"], "reduce_frac": r["frac"]}
+        if big:
+            cq = plain_kernel_ceiling((b + 1) / 32.0, 3)
+            cr = plain_kernel_ceiling(min(1.0, 4.0 / (M * (b + 1) / 8.0)), 3)
+            if cq:
+                row["quantize_pack_frac_of_plain_kernel"] = round(q["achieved"] / cq, 4)
+            if cr:
+                row["reduce_frac_of_plain_kernel"] = round(r["achieved"] / cr, 4)
+        per_b[str(b)] = row
+    result["per_b"] = per_b
+    # put the messages and the average of the last timed step back
+    dq.quantize_pack(plan, grads, norms_dev, b_last, wl.QUANT_SEED, T - 1, pk_last)
+    dq.unpack_dequant_reduce(plan, pk_last, norms_dev, b_last, out)
+    torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         b_mode = max(set(bits), key=bits.count)
         result["cpu_baseline"] = cpu_baseline(seg_len, grads, b_mode, 1 << args.cpu_sample_log2,

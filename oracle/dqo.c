@@ -289,9 +289,11 @@ static int quantize_range(const int64_t *seg_len, int32_t n_seg, const float *gr
             const float N = norms[(int64_t)i * n_seg + l];
             const int usable = norm_is_usable(N);
             const float scale = usable ? s / N : 0.0f; /* one binary32 division per segment */
-            for (int64_t j = 0; j < seg_len[l]; ++j) {
+            /* the tensor's elements that lie in [p_begin, p_end) */
+            const int64_t j_lo = p_begin > start ? p_begin - start : 0;
+            const int64_t j_hi = p_end - start < seg_len[l] ? p_end - start : seg_len[l];
+            for (int64_t j = j_lo; j < j_hi; ++j) {
                 const int64_t P = start + j;
-                if (P < p_begin || P >= p_end) continue;
                 const int64_t q = P - p_begin;
                 const float x = g[q];
                 uint32_t bits;
@@ -411,11 +413,12 @@ static int dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uin
     for (int64_t q = 0; q < span; ++q) out[q] = 0.0f;
     int64_t start = 0;
     for (int32_t l = 0; l < n_seg; ++l) {
-        const int64_t len = seg_len[l];
+        /* the tensor's elements that lie in [p_begin, p_end) */
+        const int64_t j_lo = p_begin > start ? p_begin - start : 0;
+        const int64_t j_hi = p_end - start < seg_len[l] ? p_end - start : seg_len[l];
 #pragma omp parallel for schedule(static)
-        for (int64_t j = 0; j < len; ++j) {
+        for (int64_t j = j_lo; j < j_hi; ++j) {
             const int64_t P = start + j;
-            if (P < p_begin || P >= p_end) continue;
             const int64_t q = P - p_begin;
             double acc = 0.0;
             for (int32_t i = 0; i < M; ++i) {
@@ -429,7 +432,7 @@ static int dequant_reduce_range(const int64_t *seg_len, int32_t n_seg, const uin
             }
             out[q] = (float)(acc / (double)M);
         }
-        start += padded_len(len);
+        start += padded_len(seg_len[l]);
     }
     return DQO_OK;
 }

@@ -263,3 +263,28 @@ def test_norm_smaller_than_an_element_still_clamps(oracle):
         _, level = oracle.quantize([3], g, np.array([[0.5]], dtype=np.float32), b, SEED, 0)
         assert level[0, 0] == s and level[0, 1] == s
         assert level[0, 2] in (s // 2, s // 2 + 1)
+
+
+@pytest.mark.parametrize("center", [1 << 32, 1 << 34, (1 << 36) + (1 << 34)])
+def test_python_twin_agrees_beyond_32_bit_indices(oracle, center):
+    """Padded indices past 2^32 (the index no longer fits a 32-bit word) and past 2^34 (the quad
+    index P>>2 reaches the counter's second word): the oracle's codes for a window around the
+    boundary equal the Python twin's, element by element."""
+    rng = np.random.default_rng(center % 1000003)
+    seg = [center + 4096]
+    p0, p1 = center - 128, center + 128
+    M = 2
+    g = (rng.standard_normal((M, p1 - p0)) * 0.05).astype(np.float32)
+    norms = np.array([[1.0], [0.75]], dtype=np.float32)
+    for b in (1, 4, 8):
+        sign, level = oracle.quantize_range(seg, g, norms, b, SEED, 3, p0, p1, worker_base=4)
+        for i in range(M):
+            for j in range(p1 - p0):
+                sg, lv = pyref.quantize_element(g[i, j], norms[i, 0], b, p0 + j, 4 + i, 3, SEED)
+                assert (sign[i, j], level[i, j]) == (sg, lv), (b, i, p0 + j)
+    # the two sides of the 2^34 boundary really draw from different counters
+    if center == 1 << 34:
+        lo = pyref.element_random_word(center - 4, 0, 0, SEED)
+        assert pyref.philox4x32_10([(center - 4) >> 2 & 0xFFFFFFFF, 0, 0, 0], [SEED & 0xFFFFFFFF, SEED >> 32])[0] == lo
+        assert pyref.element_random_word(center, 0, 0, SEED) == \
+            pyref.philox4x32_10([0, 1, 0, 0], [SEED & 0xFFFFFFFF, SEED >> 32])[0]
