@@ -345,7 +345,14 @@ def main() -> None:
             "dq_sign_reduce_scaled": rl(dp * (M / 8 + 4), t_ss),
         },
     }
-    result["roofline"]["traffic"] = profiled_traffic("k_quantize_pack")
+    # `traffic`: HBM bytes per launch (a number, like `achieved`'s numerator); where they come from beside it
+    tr = profiled_traffic("k_quantize_pack")
+    result["roofline"]["traffic"] = tr["bytes"] if tr else None
+    result["roofline"]["traffic_detail"] = tr
+    for entry, tag in (("dq_quantize_pack", "k_quantize_pack"), ("dq_unpack_dequant_reduce", "k_unpack_dequant_reduce"),
+                       ("dq_norm", "k_norm_partial")):
+        tk = profiled_traffic(tag)
+        result["kernels"][entry]["traffic"] = tk["bytes"] if tk else None
     # f_Q of Eq. (7) for the timed steps: what the M workers would have put on the wire
     sent = sum(dq.comm_cost_bits(M, D, b, n_seg, 32) for b in bits)
     result["comm_cost"] = {"bits_sent": sent, "bits_uncompressed": len(bits) * dq.comm_cost_bits(M, D, 31, 0, 32),

@@ -32,6 +32,8 @@ def test_short_run_prints_the_json_line():
     assert r["value"] > 0 and r["ms_per_step"] > 0 and "workload" in r["config"]
     rf = r["roofline"]
     assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+    assert rf["traffic"] is None or isinstance(rf["traffic"], int)   # bytes per launch, null off the profiled workload
+    assert set(r["per_b"]) == {str(b) for b in range(1, 9)}
     cb = r["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
     for name in ("dq_norm", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_norm_quantize_pack"):
