@@ -276,6 +276,36 @@ int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, co
                             uint32_t worker_base, float* norms_dev, uint8_t* packed_dev,
                             int64_t packed_worker_stride_bytes, void* hip_stream);
 
+/* One pass over the gradient for ANY plan, given a bracket for every norm and a bit-width that is
+ * already known (Algorithm 1: the worker received b_t with x_t; the bracket is, say, the previous
+ * iteration's norm give or take a margin).  Computes the l2 norms (Eq. (5), p = 2) and the
+ * messages of dq_quantize_pack for exactly those norms.
+ *
+ * Why one pass can be exact: for a fixed element and random number the level of Eq. (5)-(6) never
+ * grows with the norm (s/N, its product with |g| and floor(a) + [u < a - floor(a)] are all monotone,
+ * roundings included), so an element that gets the same level at both ends of the bracket gets it
+ * for every norm inside.  The first kernel reads the gradient once, quantizes with both ends,
+ * writes what is decided and records the few undecided elements (index and value); after the
+ * norms are known a second kernel settles the recorded elements.  A chunk of 4096 elements with
+ * more than 31 undecided elements, a tensor whose bracket is unusable (not lo >= DQ_MIN_NORM,
+ * lo <= hi, hi finite) or whose norm falls outside its bracket is quantized again from the
+ * gradient: the result is the same for any bracket, only the time differs (a wrong bracket
+ * costs about the two separate passes).
+ *   norm_lo_dev, norm_hi_dev  [M][n_seg] float, read
+ *   norms_dev      [M][n_seg] float, written (within 1 ulp of dq_norm's: same squares, summed chunk-wise)
+ *   packed_dev     as dq_quantize_pack
+ *   workspace_dev  dq_bracketed_workspace_bytes(plan, M) bytes, 16-byte aligned; contents on entry
+ *                  are ignored
+ *   stats_dev      NULL, or two int64 (8-byte aligned), written: [0] elements settled by the second
+ *                  kernel, [1] chunks quantized again in full
+ * Errors as dq_quantize_pack. */
+int64_t dq_bracketed_workspace_bytes(const dq_plan_t* plan, int M); /* -1 on bad arguments */
+int dq_norm_quantize_pack_bracketed(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                                    int M, const float* norm_lo_dev, const float* norm_hi_dev, int b,
+                                    uint64_t seed, uint32_t step, uint32_t worker_base, float* norms_dev,
+                                    uint8_t* packed_dev, int64_t packed_worker_stride_bytes, void* workspace_dev,
+                                    int64_t* stats_dev, void* hip_stream);
+
 /* Eq. (24), the practical estimate of the convergence factor: alpha_est = (F(x_t)/F(x_0))^(1/t).
  * Host code.  Returns -1 unless t >= 1, F_t > 0 and F_0 > 0. */
 double dq_alpha_est(double F_t, double F_0, int64_t t);

@@ -26,6 +26,7 @@ EXPORTS = (
     "dq_select_bits_per_tensor", "dq_select_bits_per_worker", "dq_select_bits_device", "dq_widths_create",
     "dq_widths_create_per_worker", "dq_widths_destroy", "dq_widths_set", "dq_widths_packed_bytes",
     "dq_widths_worker_packed_bytes", "dq_quantize_pack_v", "dq_norm_quantize_pack_v", "dq_unpack_dequant_reduce_v",
+    "dq_bracketed_workspace_bytes", "dq_norm_quantize_pack_bracketed",
     "dq_unpack_dequant_reduce_update_v",
     # sign-only baseline
     "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority",
@@ -126,6 +127,11 @@ def load_library():
     L.dq_norm_quantize_pack_v.argtypes = [vp, vp, vp, i64, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
                                           vp, vp, i64, vp]
     L.dq_norm_quantize_pack_v.restype = C.c_int
+    L.dq_bracketed_workspace_bytes.argtypes = [vp, C.c_int]
+    L.dq_bracketed_workspace_bytes.restype = i64
+    L.dq_norm_quantize_pack_bracketed.argtypes = [vp, vp, i64, C.c_int, vp, vp, C.c_int, C.c_uint64, C.c_uint32,
+                                                  C.c_uint32, vp, vp, i64, vp, vp, vp]
+    L.dq_norm_quantize_pack_bracketed.restype = C.c_int
     L.dq_unpack_dequant_reduce_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, vp, vp]
     L.dq_unpack_dequant_reduce_v.restype = C.c_int
     L.dq_unpack_dequant_reduce_update_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, C.c_float, vp, vp, vp]
@@ -262,6 +268,26 @@ def norm_quantize_pack(plan: Plan, grads, b: int, seed: int, step: int, norms_ou
            load_library().dq_norm_quantize_pack(plan.handle, grads.data_ptr(), stride, M, 1 if linf else 0, b, seed,
                                                 step, worker_base, norms_out.data_ptr(), packed_out.data_ptr(),
                                                 int(packed_out.stride(0)), _stream_handle(stream)))
+
+
+def bracketed_workspace_bytes(plan: Plan, M: int) -> int:
+    return int(load_library().dq_bracketed_workspace_bytes(plan.handle, M))
+
+
+def norm_quantize_pack_bracketed(plan: Plan, grads, norm_lo, norm_hi, b: int, seed: int, step: int, norms_out,
+                                 packed_out, workspace, worker_base: int = 0, stats=None, stream=None) -> None:
+    """One pass over the gradient for any plan, given a bracket [norm_lo, norm_hi] (CUDA float32
+    [M][n_seg]) for every norm: norms (written to norms_out) and the messages of quantize_pack for
+    them.  workspace: uint8 CUDA tensor of bracketed_workspace_bytes(plan, M); stats: optional CUDA
+    int64 [2] (elements settled afterwards, chunks quantized again)."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    if workspace.numel() * workspace.element_size() < bracketed_workspace_bytes(plan, M):
+        raise ValueError("workspace too small: see bracketed_workspace_bytes")
+    _check("dq_norm_quantize_pack_bracketed",
+           load_library().dq_norm_quantize_pack_bracketed(
+               plan.handle, grads.data_ptr(), stride, M, norm_lo.data_ptr(), norm_hi.data_ptr(), b, seed, step,
+               worker_base, norms_out.data_ptr(), packed_out.data_ptr(), int(packed_out.stride(0)),
+               workspace.data_ptr(), stats.data_ptr() if stats is not None else None, _stream_handle(stream)))
 
 
 def quantize_pack(plan: Plan, grads, norms, b: int, seed: int, step: int, packed_out,

@@ -110,10 +110,11 @@ __device__ __forceinline__ double dq_chunk_combine(double a, double b)
 // a segmented scan over the granules -- four shift-and-combine steps inside each 16-lane row, then
 // the second row takes over what the first row's last granule has gathered when a tensor spans
 // both -- after which the lane of a tensor's last granule holds the tensor's total and calls
-// emit(local tensor index, norm).  A fixed combination order, the same wherever this is used.
+// emit(local tensor index, total): the sum of squares (or the maximum) of the tensor's elements in
+// this chunk, in binary64.  A fixed combination order, the same wherever this is used.
 template <bool LINF, typename Emit>
-__device__ __forceinline__ void dq_chunk_tensor_norms(int g, int n_granules, const double* lds_gsum,
-                                                      const int32_t* lds_glocal, Emit&& emit)
+__device__ __forceinline__ void dq_chunk_tensor_totals(int g, int n_granules, const double* lds_gsum,
+                                                       const int32_t* lds_glocal, Emit&& emit)
 {
     const bool used = g < n_granules;
     double v = used ? lds_gsum[g] : 0.0;
@@ -131,6 +132,15 @@ __device__ __forceinline__ void dq_chunk_tensor_norms(int g, int n_granules, con
     const int tail_t = __builtin_amdgcn_readlane(t, 15);
     const double tail = __longlong_as_double(static_cast<long long>((static_cast<uint64_t>(tail_hi) << 32) | tail_lo));
     if (g >= 16 && t == tail_t) v = dq_chunk_combine<LINF>(tail, v);
-    if (used && (g == n_granules - 1 || lds_glocal[g + 1] + 1 != t))
-        emit(t - 1, LINF ? static_cast<float>(v) : static_cast<float>(sqrt(v)));
+    if (used && (g == n_granules - 1 || lds_glocal[g + 1] + 1 != t)) emit(t - 1, v);
+}
+
+// The same for chunk-local plans, where the chunk holds whole tensors: emit(local tensor index, norm).
+template <bool LINF, typename Emit>
+__device__ __forceinline__ void dq_chunk_tensor_norms(int g, int n_granules, const double* lds_gsum,
+                                                      const int32_t* lds_glocal, Emit&& emit)
+{
+    dq_chunk_tensor_totals<LINF>(g, n_granules, lds_gsum, lds_glocal, [&](int j, double total) {
+        emit(j, LINF ? static_cast<float>(total) : static_cast<float>(sqrt(total)));
+    });
 }

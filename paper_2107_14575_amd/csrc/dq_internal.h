@@ -29,6 +29,7 @@ struct dq_plan {
     int32_t* d_granule_cseg;       // [D'/128]  compact segment index of each 128-element granule
     int32_t* d_cseg_seg;           // [n_nonempty] segment l of compact index c
     int64_t* d_cseg_valid_end;     // [n_nonempty] P_l + len_l: first padded index past the data
+    int64_t* d_cseg_start;         // [n_nonempty] P_l
     dq_norm_item* d_items;         // [n_items]
     int32_t* d_seg_item_begin;     // [n_seg + 1] items of segment l are [begin[l], begin[l+1])
     int32_t* d_finish_seg;         // [n_finish] segments whose norm needs the finishing kernel: all but
@@ -55,6 +56,28 @@ struct dq_widths {
     int64_t* worker_bytes;   // [n_workers] message size of each row
     int32_t* b_host;         // [n_workers][n_seg] widths last set
 };
+
+// Workspace of dq_norm_quantize_pack_bracketed.  First the partial sums of squares, one binary64
+// slot per (worker, chunk, tensor in the chunk) at index chunk + c (c = the tensor's compact
+// index: both grow along the layout, so the sum is unique and a tensor's slots are contiguous);
+// then one 256-byte block per (worker, chunk) with the elements whose level the bracket could not
+// decide.
+constexpr int DQ_BRACKET_CAP = 31; // records per block
+struct dq_bracket_block {
+    uint32_t count; // undecided elements found (may exceed DQ_BRACKET_CAP: then the chunk is redone)
+    uint32_t flags; // != 0: a tensor in the chunk had no usable bracket, nothing was quantized
+    uint2 rec[DQ_BRACKET_CAP]; // .x = element index inside the chunk, .y = the gradient value's bits
+};
+static_assert(sizeof(dq_bracket_block) == 256, "one block per (worker, chunk), 256 bytes");
+
+static inline int64_t dq_bracket_slots(const dq_plan* plan)
+{
+    return (plan->padded_elems + 4095) / 4096 + plan->n_cseg;
+}
+static inline int64_t dq_bracket_partial_bytes(const dq_plan* plan, int M)
+{
+    return (static_cast<int64_t>(M) * dq_bracket_slots(plan) * 8 + 255) / 256 * 256;
+}
 
 static inline bool dq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -1,0 +1,156 @@
+"""GPU parity for dq_norm_quantize_pack_bracketed: one pass over the gradient for any layout, given
+a bracket for every norm.  Whatever the bracket (tight, wide, wrong, unusable) the norms must be
+the l2 norms (1 ulp of the oracle's) and the messages must be the oracle's for those norms, bit for
+bit; the statistics say which route the chunks took."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2107_14575_amd import workloads as wl
+from tests.test_gpu_parity import SEED, dq, gpu_norm  # noqa: F401  (dq is a fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(dq, oracle, seg_len, grads, b, lo_factor, hi_factor, step=3, worker_base=2, check_norm=True):
+    """-> (exceptions settled, chunks redone, number of (worker, chunk) pairs)"""
+    plan = dq.Plan(seg_len)
+    M = grads.shape[0]
+    g_host = np.ascontiguousarray(grads.numpy())
+    g_dev = grads.cuda()
+    ref = gpu_norm(dq, plan, g_dev)
+    lo = (ref * lo_factor).contiguous()
+    hi = (ref * hi_factor).contiguous()
+    norms_dev = torch.full((M, plan.n_seg), float("nan"), dtype=torch.float32, device="cuda")
+    nbytes = plan.packed_bytes(b)
+    packed = torch.full((M, nbytes + 32), 0xA5, dtype=torch.uint8, device="cuda")
+    ws = torch.full((dq.bracketed_workspace_bytes(plan, M),), 0xEE, dtype=torch.uint8, device="cuda")  # stale contents
+    stats = torch.full((2,), -7, dtype=torch.int64, device="cuda")
+    dq.norm_quantize_pack_bracketed(plan, g_dev, lo, hi, b, SEED, step, norms_dev, packed, ws,
+                                    worker_base=worker_base, stats=stats)
+    torch.cuda.synchronize()
+    norms = norms_dev.cpu().numpy()
+    if check_norm:
+        want_n = oracle.norm(seg_len, g_host)
+        assert np.all(np.abs(norms.astype(np.float64) - want_n.astype(np.float64)) <= np.spacing(want_n))
+    want = oracle.quantize_pack(seg_len, g_host, norms, b, SEED, step, worker_base)
+    got = packed.cpu().numpy()
+    assert np.array_equal(got[:, :nbytes], want), f"b={b} bracket x[{lo_factor}, {hi_factor}]"
+    assert np.all(got[:, nbytes:] == 0xA5)
+    n_chunks = (plan.padded_elems + 4095) // 4096
+    plan.close()
+    s = stats.cpu().numpy()
+    assert s[0] >= 0 and 0 <= s[1] <= n_chunks * M
+    return int(s[0]), int(s[1]), n_chunks * M
+
+
+def _flat(D, M, seed, sigma=1e-3):
+    gen = torch.Generator().manual_seed(seed)
+    return [D], torch.randn((M, (D + 127) // 128 * 128), generator=gen) * sigma
+
+
+@pytest.mark.parametrize("b", range(1, 9))
+def test_flat_gradient_tight_bracket(dq, oracle, b):
+    """one tensor over 257 chunks and a ragged tail, bracket +-1 %.  The undecided elements per
+    chunk number about 4096 * (hi - lo)/N * E[s|g|/N] (16 at b = 8 for this size): almost every
+    chunk is finished by settling its few records, hardly any is quantized twice"""
+    seg_len, g = _flat((1 << 20) + 1000, 2, 40 + b)
+    settled, redone, total = _run(dq, oracle, seg_len, g, b, 0.99, 1.01)
+    assert redone <= total // 50
+    assert settled > 0
+
+
+@pytest.mark.parametrize("b", [1, 2, 5, 8])
+def test_flat_gradient_loose_bracket(dq, oracle, b):
+    """13 chunks, bracket +-12.5 %: few undecided elements at small b, more than a chunk's 31
+    records at large b -- exact either way"""
+    seg_len, g = _flat(12 * 4096 + 1000, 3, 60 + b)
+    settled, redone, total = _run(dq, oracle, seg_len, g, b, 0.875, 1.125)
+    if b <= 2:
+        assert redone == 0 and settled > 0
+    if b == 8:
+        assert redone == total
+
+
+def test_exact_bracket_settles_nothing(dq, oracle):
+    seg_len, g = _flat(5 * 4096, 4, 51)
+    # lo = hi = the norm the other kernels compute; the path's own norm may differ from it in the
+    # last place, and then every chunk of that worker is redone -- both outcomes are exact
+    settled, redone, total = _run(dq, oracle, seg_len, g, 4, 1.0, 1.0)
+    assert settled == 0 or redone > 0
+    settled, redone, total = _run(dq, oracle, seg_len, g, 4, 1.0 - 2.0 ** -20, 1.0 + 2.0 ** -20)
+    assert redone == 0
+
+
+@pytest.mark.parametrize("factors", [(4.0, 8.0), (0.01, 0.02)])
+def test_wrong_bracket_redoes_every_chunk(dq, oracle, factors):
+    seg_len, g = _flat(7 * 4096 + 128, 2, 52)
+    settled, redone, total = _run(dq, oracle, seg_len, g, 5, *factors)
+    assert redone == total and settled == 0
+
+
+def test_wide_bracket_overflows_some_chunks(dq, oracle):
+    """d = 4096 per tensor: a = s|g|/N is large, a bracket of 1/8..8 leaves most elements undecided,
+    far more than a chunk's 31 records"""
+    seg_len = [4096] * 6
+    gen = torch.Generator().manual_seed(53)
+    g = torch.randn((3, 6 * 4096), generator=gen)
+    settled, redone, total = _run(dq, oracle, seg_len, g, 6, 0.125, 8.0)
+    assert redone >= total // 2
+    # a mild bracket and few levels on the same data: a handful of undecided elements per chunk
+    settled, redone, total = _run(dq, oracle, seg_len, g, 2, 0.99, 1.01)
+    assert settled > 0 and redone == 0
+
+
+def test_unusable_brackets(dq, oracle):
+    """zero tensors (lo = 0), norms below the floor, and a layout with empty tensors"""
+    seg_len = [5000, 0, 300, 4096, 77]
+    starts, dp = wl.seg_starts(seg_len)
+    gen = torch.Generator().manual_seed(54)
+    g = torch.randn((3, dp), generator=gen) * 1e-2
+    g[:, starts[2]:starts[2] + 300] = 0.0          # a zero tensor
+    g[1, starts[3]:starts[3] + 4096] *= 1e-34      # below DQ_MIN_NORM for worker 1
+    settled, redone, total = _run(dq, oracle, seg_len, g, 3, 0.9, 1.1)
+    assert redone > 0
+
+
+def test_nan_and_reversed_brackets(dq, oracle):
+    seg_len, g = _flat(3 * 4096, 2, 55)
+    for lo_f, hi_f in ((float("nan"), 1.1), (0.9, float("nan")), (1.1, 0.9), (0.9, float("inf"))):
+        settled, redone, total = _run(dq, oracle, seg_len, g, 4, lo_f, hi_f)
+        assert redone == total
+
+
+@pytest.mark.parametrize("M", [1, 5, 64])
+def test_ragged_layout(dq, oracle, M):
+    seg_len, g = wl.ragged_mix(M=M)
+    for b in (2, 7):
+        _run(dq, oracle, seg_len, g, b, 0.8, 1.25, step=b, worker_base=9)
+
+
+def test_heavy_tails_and_sparse_rows(dq, oracle):
+    """the value kinds of the benchmark configurations at a size of a few chunks"""
+    seg_len, g = wl.flat_student_t(D=1 << 16, M=4, device="cpu")
+    settled, redone, total = _run(dq, oracle, seg_len, g, 4, 0.98, 1.02)
+    assert redone <= 1 and settled > 0
+    seg_len, g = wl.transformer_like(M=2, device="cpu")
+    _run(dq, oracle, seg_len, g, 4, 0.875, 1.125)
+
+
+def test_argument_checks(dq):
+    plan = dq.Plan([4096 * 2])
+    M = 2
+    g = torch.zeros((M, 8192), device="cuda")
+    lo = torch.ones((M, 1), device="cuda")
+    norms = torch.empty((M, 1), device="cuda")
+    packed = torch.empty((M, plan.packed_bytes(4)), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(dq.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device="cuda")
+    with pytest.raises(dq.DQError):
+        dq.norm_quantize_pack_bracketed(plan, g, lo, lo, 9, 1, 0, norms, packed, ws)
+    with pytest.raises(dq.DQError):
+        short = torch.empty((M, 96), dtype=torch.uint8, device="cuda")
+        dq.norm_quantize_pack_bracketed(plan, g, lo, lo, 4, 1, 0, norms, short, ws)
+    with pytest.raises(ValueError):
+        dq.norm_quantize_pack_bracketed(plan, g, lo, lo, 4, 1, 0, norms, packed, ws[:64])
+    assert dq.bracketed_workspace_bytes(plan, 0) == -1
+    plan.close()
