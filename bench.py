@@ -251,6 +251,29 @@ def main() -> None:
         one_pass = (t_fused, t_bred, ms_lagged, bplan.n_seg)
         bplan.close()
         del bnorms
+    # The same protocol on the benchmark's own layout (one norm for the whole gradient): norms and
+    # messages in ONE pass given a bracket for every norm -- here the norms of the step before, give or
+    # take 12.5 % -- then the reduce.  Elements the bracket leaves open are settled afterwards.
+    wsb = torch.empty(dq.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device="cuda")
+    br_stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+    br_norms = torch.empty_like(norms_dev)
+    br_lo, br_hi = norms_dev * 0.875, norms_dev * 1.125
+    t_br = timed_loop(lambda: dq.norm_quantize_pack_bracketed(plan, grads, br_lo, br_hi, b_last, wl.QUANT_SEED, T,
+                                                              br_norms, pk_last, wsb, stats=br_stats))
+
+    def bracketed_step(t):
+        dq.norm_quantize_pack_bracketed(plan, grads, br_lo, br_hi, b_last, wl.QUANT_SEED, t, br_norms, pk_last, wsb)
+        dq.unpack_dequant_reduce(plan, pk_last, br_norms, b_last, out)
+
+    bracketed_step(0)
+    torch.cuda.synchronize()
+    t0_b = time.perf_counter()
+    for t in range(args.steps):
+        bracketed_step(t)
+    torch.cuda.synchronize()
+    ms_bracketed = (time.perf_counter() - t0_b) / args.steps * 1e3
+    br_counts = [int(v) for v in br_stats.tolist()]
+    del wsb
     # leave packed/out as the last step left them for anything that follows
     dq.quantize_pack(plan, grads, norms_dev, b_last, wl.QUANT_SEED, T - 1, pk_last)
     dq.unpack_dequant_reduce(plan, pk_last, norms_dev, b_last, out)
@@ -366,6 +389,13 @@ def main() -> None:
             "buckets": n_buckets, "b": b_last, "ms_per_step": round(ms_lagged, 4),
             "value": round(in_bytes / (ms_lagged * 1e-3) / 1e9, 2), "unit": "GB/s of fp32 input",
             "reduce_ms": round(t_bred, 4)}
+    result["kernels"]["dq_norm_quantize_pack_bracketed"] = rl(M * dp * (4 + (b_last + 1) / 8), t_br)
+    result["bracketed_step"] = {
+        "what": "the benchmark's own layout, b known beforehand, every norm known to +-12.5 % (the step before): "
+                "dq_norm_quantize_pack_bracketed reads the gradient once, then dq_unpack_dequant_reduce",
+        "b": b_last, "ms_per_step": round(ms_bracketed, 4),
+        "value": round(in_bytes / (ms_bracketed * 1e-3) / 1e9, 2), "unit": "GB/s of fp32 input",
+        "elements_settled_afterwards": br_counts[0], "chunks_quantized_again": br_counts[1]}
     result["device_rule_step"] = {
         "what": "the same step with dq_select_bits_device and the per-tensor-width kernels: no host round trip",
         "ms_per_step": round(ms_device_rule, 4), "value": round(in_bytes / (ms_device_rule * 1e-3) / 1e9, 2),

@@ -1,0 +1,437 @@
+// dq_norm_quantize_pack_bracketed: norms and messages in one pass over the gradient for ANY plan,
+// given a bracket [lo, hi] for every norm (say, last iteration's norm give or take a margin) and a
+// bit-width that is known beforehand (Algorithm 1: the worker received b_t with x_t).
+//
+// For a fixed element and random number the level of Eq. (5)-(6) never grows with the norm:
+// s/N rounded to binary32 does not grow with N, |g| * scale rounded does not grow when the scale
+// shrinks, and a -> floor(a) + [u < a - floor(a)] never decreases in a (inside one integer interval
+// the indicator can only switch on; across intervals floor(a) + 1 <= floor(a')).  So an element
+// whose level is the same at both ends of the bracket has that level for every norm inside it.
+//
+//   k_quantize_pack_bracketed  reads the gradient once: adds up each tensor's squares chunk by
+//       chunk (binary64 partial sums, one slot per chunk and tensor), quantizes with the low end
+//       of the bracket (the largest levels), looks at the non-zero levels again with the high end,
+//       writes the levels that agree, leaves the others' fields zero and records those elements
+//       (index and value) in the chunk's block of the workspace.
+//   k_bracket_norm_finish      adds a tensor's partial sums in a fixed order: the norms, and
+//       whether each came out inside its bracket.
+//   k_bracket_settle           one lane per chunk: quantizes the chunk's recorded elements with the
+//       true norm and ORs their levels into the zero fields; a chunk with too many records, with
+//       no usable bracket, or with a norm outside its bracket gets a bit in the redo map instead.
+//   k_bracket_redo             quantizes the chunks of the redo map again in full from the
+//       gradient (the only case that reads it twice); a few thousand workgroups walk the map, so
+//       an empty map costs next to nothing.
+// The messages are exactly those of dq_quantize_pack for the norms this path computes.
+#include "dq_quantize_core.h"
+
+namespace {
+
+// One element again with another scale: the level of quantize4 for element value v and word r.
+template <int B>
+__device__ __forceinline__ uint32_t level_of(float v, float scale, uint32_t r)
+{
+    constexpr float S = static_cast<float>((1 << B) - 1);
+    const float a = fminf(fabsf(v) * scale, S);
+    const float p = __builtin_amdgcn_fractf(a);
+    const float u = static_cast<float>(r >> 8) * 0x1p-24f;
+    return static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
+}
+
+template <int B>
+__global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
+    const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norm_lo,
+    const float* __restrict__ norm_hi, int32_t n_seg, const int32_t* __restrict__ granule_cseg,
+    const int32_t* __restrict__ cseg_seg, const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems,
+    uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
+    int64_t packed_stride, double* __restrict__ partials, int64_t n_slots, dq_bracket_block* __restrict__ blocks,
+    int64_t n_chunks)
+{
+    constexpr int TILES = 2;
+    constexpr int CHUNK = DQ_CHUNK;
+    constexpr float S = static_cast<float>((1 << B) - 1);
+    constexpr uint64_t FIELD = (static_cast<uint64_t>(1) << B) - 1u;
+
+    __shared__ float lds_scale_hi[DQ_CHUNK_GRANULES]; // s / lo: the larger scale
+    __shared__ float lds_scale_lo[DQ_CHUNK_GRANULES]; // s / hi
+    __shared__ int32_t lds_valid_end[DQ_CHUNK_GRANULES];
+    __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
+    __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
+    __shared__ uint32_t lds_count;
+    __shared__ __align__(16) uint8_t lds_sign[TILES * QP_THREADS];
+    __shared__ __align__(16) uint8_t lds_level[TILES * QP_THREADS * B];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t w = blockIdx.y;
+    const int64_t chunk0 = static_cast<int64_t>(blockIdx.x) * CHUNK;
+    const uint32_t n_elems = static_cast<uint32_t>(padded_elems - chunk0 < CHUNK ? padded_elems - chunk0 : CHUNK);
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride + chunk0;
+    const int32_t* gseg = granule_cseg + (chunk0 >> 7);
+    dq_bracket_block* blk = blocks + static_cast<int64_t>(w) * n_chunks + blockIdx.x;
+
+    float4 x[TILES][2];
+    int32_t seg[TILES];
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        e = e < n_elems ? e : n_elems - QP_PER_LANE; // clamped: always in bounds, result unused
+        x[it][0] = *reinterpret_cast<const float4*>(g + e);
+        x[it][1] = *reinterpret_cast<const float4*>(g + e + 4);
+        seg[it] = gseg[e >> 7];
+    }
+
+    const int32_t seg_first = gseg[0];
+    const int32_t seg_last = gseg[(n_elems - 1) >> 7];
+    if (tid == 0) lds_count = 0;
+    int unusable = 0;
+    if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
+        const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid];
+        const float lo = norm_lo[at], hi = norm_hi[at];
+        // the zero path (norm below DQ_MIN_NORM) is not monotone against the rest: no bracket across it
+        const bool ok = lo >= DQ_MIN_NORM && hi >= lo && hi <= 3.0e38f; // false for NaN
+        lds_scale_hi[tid] = ok ? S / lo : 0.0f;
+        lds_scale_lo[tid] = ok ? S / hi : 0.0f;
+        unusable = ok ? 0 : 1;
+        const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+        lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+    }
+    const int skip = __syncthreads_or(unusable); // also the barrier after the tables
+
+    // partial sums of squares of the chunk's tensors
+    int valid[TILES], local[TILES];
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        local[it] = seg[it] - seg_first;
+        valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
+    }
+    dq_chunk_granule_sums<false>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+    __syncthreads();
+    if (tid < DQ_CHUNK_GRANULES)
+        dq_chunk_tensor_totals<false>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+                                      [&](int j, double total) {
+                                          partials[static_cast<int64_t>(w) * n_slots + blockIdx.x + seg_first + j] = total;
+                                      });
+    if (skip) { // uniform: the redo kernel quantizes this chunk from the gradient
+        if (tid == 0) {
+            blk->count = 0;
+            blk->flags = 1;
+        }
+        return;
+    }
+
+    const uint32_t quad_lo0 = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 2);
+    const uint32_t quad_hi = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 34);
+    const uint32_t worker = worker_base + w;
+
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        if (e < n_elems) {
+            const uint32_t quad = quad_lo0 + (e >> 2);
+            uint32_t r0[4], r1[4];
+            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
+            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
+
+            // levels at the low end of the bracket: the largest any norm inside it can give
+            uint32_t sign = 0, lv_lo, lv_hi;
+            quantize4<B>(x[it][1], lds_scale_hi[local[it]], r1, sign, lv_hi);
+            quantize4<B>(x[it][0], lds_scale_hi[local[it]], r0, sign, lv_lo);
+            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * B));
+            const int nv = valid[it] >= QP_PER_LANE ? QP_PER_LANE : (valid[it] > 0 ? valid[it] : 0);
+            if (nv < QP_PER_LANE) {
+                sign &= (1u << nv) - 1u;
+                level &= (static_cast<uint64_t>(1) << (nv * B)) - 1u;
+            }
+            if (level != 0) { // a zero at the low end is a zero everywhere in the bracket
+                const float scale_lo = lds_scale_lo[local[it]];
+                const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
+                                     x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
+                const uint32_t r[8] = { r0[0], r0[1], r0[2], r0[3], r1[0], r1[1], r1[2], r1[3] };
+#pragma unroll
+                for (int k = 0; k < QP_PER_LANE; ++k) {
+                    const uint32_t top = static_cast<uint32_t>(level >> (k * B)) & static_cast<uint32_t>(FIELD);
+                    if (top != 0 && level_of<B>(v[k], scale_lo, r[k]) != top) {
+                        const uint32_t slot = atomicAdd(&lds_count, 1u);
+                        if (slot < DQ_BRACKET_CAP) blk->rec[slot] = make_uint2(e + k, __float_as_uint(v[k]));
+                        level &= ~(FIELD << (k * B)); // left zero for the settle kernel
+                    }
+                }
+            }
+            lds_sign[it * QP_THREADS + tid] = static_cast<uint8_t>(sign);
+            stage_bytes<B>(&lds_level[(it * QP_THREADS + tid) * B], level);
+        }
+    }
+    __syncthreads();
+
+    uint8_t* msg = packed + static_cast<int64_t>(w) * packed_stride;
+    {
+        uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
+        const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+    }
+    {
+        uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + (chunk0 >> 3) * B);
+        const uint4* src = reinterpret_cast<const uint4*>(lds_level);
+        for (uint32_t i = tid; i < n_elems / 128 * B; i += QP_THREADS) dst[i] = src[i];
+    }
+    if (tid == 0) {
+        blk->count = lds_count;
+        blk->flags = 0;
+    }
+}
+
+// grid (n_cseg, M): the norm of tensor c of worker w from its partial sums, slots
+// [first chunk + c, last chunk + c]: eight lane-strided running sums per lane, combined in a fixed
+// order, then a fixed tree over the lanes.  Also notes whether the norm lies inside its bracket.
+__global__ __launch_bounds__(256) void k_bracket_norm_finish(
+    const double* __restrict__ partials, int64_t n_slots, const int64_t* __restrict__ cseg_start,
+    const int64_t* __restrict__ cseg_valid_end, const int32_t* __restrict__ cseg_seg, int32_t n_seg, int32_t n_cseg,
+    const float* __restrict__ norm_lo, const float* __restrict__ norm_hi, float* __restrict__ norms,
+    uint8_t* __restrict__ inside)
+{
+    __shared__ double part[256];
+    const int tid = threadIdx.x;
+    const int32_t c = blockIdx.x;
+    const int w = blockIdx.y;
+    const int64_t first = cseg_start[c] / DQ_CHUNK;
+    const int64_t last = (cseg_valid_end[c] - 1) / DQ_CHUNK;
+    const double* p = partials + static_cast<int64_t>(w) * n_slots + first + c;
+    const int64_t n = last - first + 1;
+    double acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = 0.0;
+    int64_t i = tid;
+    for (; i + 7 * 256 < n; i += 8 * 256) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] += p[i + k * 256];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) // fewer than eight are left
+        if (i + k * 256 < n) acc[k] += p[i + k * 256];
+    part[tid] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+    __syncthreads();
+    for (int off = 128; off >= 1; off >>= 1) {
+        if (tid < off) part[tid] += part[tid + off];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[c];
+        const float N = static_cast<float>(sqrt(part[0]));
+        norms[at] = N;
+        inside[static_cast<int64_t>(w) * n_cseg + c] = (N >= norm_lo[at] && N <= norm_hi[at]) ? 1 : 0;
+    }
+}
+
+// grid (ceil(n_chunks / 256), M), one lane per chunk.
+template <int B>
+__global__ __launch_bounds__(256) void k_bracket_settle(
+    const float* __restrict__ norms, int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ granule_cseg,
+    const int32_t* __restrict__ cseg_seg, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
+    uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride, dq_bracket_block* __restrict__ blocks,
+    int64_t n_chunks, const uint8_t* __restrict__ inside, unsigned long long* __restrict__ redo_map, int64_t n_words)
+{
+    constexpr float S = static_cast<float>((1 << B) - 1);
+    const uint32_t w = blockIdx.y;
+    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const bool active = chunk < n_chunks;
+    bool again = false;
+    if (active) {
+        dq_bracket_block* blk = blocks + static_cast<int64_t>(w) * n_chunks + chunk;
+        const uint32_t count = blk->count, flags = blk->flags;
+        const int64_t chunk0 = chunk * DQ_CHUNK;
+        const int64_t last_granule = ((chunk0 + DQ_CHUNK < padded_elems ? chunk0 + DQ_CHUNK : padded_elems) - 1) >> 7;
+        const int32_t c_first = granule_cseg[chunk0 >> 7], c_last = granule_cseg[last_granule];
+        again = flags != 0 || count > DQ_BRACKET_CAP;
+        for (int32_t c = c_first; c <= c_last; ++c) again = again || inside[static_cast<int64_t>(w) * n_cseg + c] == 0;
+        if (again) {
+            blk->flags = flags | 2u;
+        } else {
+            uint32_t* plane = reinterpret_cast<uint32_t*>(packed + static_cast<int64_t>(w) * packed_stride +
+                                                          (padded_elems >> 3));
+            for (uint32_t k = 0; k < count; ++k) {
+                const uint2 rec = blk->rec[k];
+                const uint32_t e = rec.x; // < 4096 and inside the layout: written by the first kernel for this chunk
+                const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[granule_cseg[(chunk0 >> 7) + (e >> 7)]]];
+                const float scale = N >= DQ_MIN_NORM ? S / N : 0.0f;
+                const uint64_t P = static_cast<uint64_t>(chunk0) + e;
+                uint32_t r[4];
+                dq_philox4x32_10(static_cast<uint32_t>(P >> 2), static_cast<uint32_t>(P >> 34), worker_base + w, step,
+                                 key0, key1, r);
+                const uint32_t word = (P & 2u) ? ((P & 1u) ? r[3] : r[2]) : ((P & 1u) ? r[1] : r[0]);
+                const uint32_t level = level_of<B>(__uint_as_float(rec.y), scale, word);
+                if (level != 0) {
+                    // the field was left zero; fields of other elements in the same words are not touched
+                    const uint64_t bit = P * B;
+                    const uint32_t sh = static_cast<uint32_t>(bit & 31u);
+                    atomicOr(plane + (bit >> 5), level << sh);
+                    if (sh + B > 32) atomicOr(plane + (bit >> 5) + 1, level >> (32 - sh));
+                }
+            }
+        }
+    }
+    // 64 consecutive chunks per wavefront: one word of the redo map (blockDim is a multiple of 64)
+    const unsigned long long bits = __ballot(active && again);
+    if ((threadIdx.x & 63) == 0 && (chunk >> 6) < n_words) redo_map[static_cast<int64_t>(w) * n_words + (chunk >> 6)] = bits;
+}
+
+// grid (ceil(n_words / REDO_WORDS), M): each workgroup walks REDO_WORDS words of the redo map and
+// quantizes the chunks whose bit is set.
+constexpr int REDO_WORDS = 8;
+
+template <int B>
+__global__ __launch_bounds__(QP_THREADS) void k_bracket_redo(
+    const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
+    const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
+    uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride,
+    const unsigned long long* __restrict__ redo_map, int64_t n_words)
+{
+    const int64_t word0 = static_cast<int64_t>(blockIdx.x) * REDO_WORDS;
+    const unsigned long long* map = redo_map + static_cast<int64_t>(blockIdx.y) * n_words;
+    for (int k = 0; k < REDO_WORDS && word0 + k < n_words; ++k) {
+        // the same value in every lane (one address), made scalar so that the loop below is uniform
+        const unsigned long long loaded = map[word0 + k];
+        unsigned long long bits =
+            (static_cast<unsigned long long>(__builtin_amdgcn_readfirstlane(static_cast<int>(loaded >> 32))) << 32) |
+            static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(loaded)));
+        while (bits != 0) {
+            const int bit = __builtin_ctzll(bits);
+            bits &= bits - 1;
+            quantize_pack_chunk<B, 2, 0>(grads, worker_stride, norms, n_seg, granule_cseg, cseg_seg, cseg_valid_end,
+                                         padded_elems, key0, key1, step, worker_base, packed, packed_stride, nullptr,
+                                         static_cast<uint32_t>((word0 + k) * 64 + bit));
+            __syncthreads(); // the chunk's staging in LDS is reused by the next one
+        }
+    }
+}
+
+// Statistics of one call, from the blocks: elements settled afterwards and chunks quantized again.
+// 256 workgroups at most add their totals to the two counters.
+constexpr int BS_PER_LANE = 16;
+
+__global__ __launch_bounds__(256) void k_bracket_stats(const dq_bracket_block* __restrict__ blocks, int64_t n_blocks,
+                                                       unsigned long long* __restrict__ stats)
+{
+    __shared__ unsigned long long part[2][256];
+    const int tid = threadIdx.x;
+    unsigned long long settled = 0, again = 0;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + tid; i < n_blocks;
+         i += static_cast<int64_t>(gridDim.x) * 256) {
+        const uint32_t count = blocks[i].count, flags = blocks[i].flags;
+        if (flags & 2u)
+            ++again;
+        else
+            settled += count;
+    }
+    part[0][tid] = settled;
+    part[1][tid] = again;
+    __syncthreads();
+    for (int off = 128; off >= 1; off >>= 1) {
+        if (tid < off) {
+            part[0][tid] += part[0][tid + off];
+            part[1][tid] += part[1][tid + off];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (part[0][0]) atomicAdd(&stats[0], part[0][0]);
+        if (part[1][0]) atomicAdd(&stats[1], part[1][0]);
+    }
+}
+
+__global__ void k_zero_two(unsigned long long* __restrict__ stats)
+{
+    stats[threadIdx.x] = 0;
+}
+
+template <int B>
+int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_stride, int M, const float* norm_lo,
+                     const float* norm_hi, uint64_t seed, uint32_t step, uint32_t worker_base, float* norms,
+                     uint8_t* packed, int64_t packed_stride, void* workspace, unsigned long long* stats,
+                     hipStream_t stream)
+{
+    const dq_bracket_layout L = dq_bracket_layout_of(plan, M);
+    if (L.n_chunks > INT32_MAX) return DQ_ERR_INVALID_ARG;
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    double* partials = reinterpret_cast<double*>(ws);
+    dq_bracket_block* blocks = reinterpret_cast<dq_bracket_block*>(ws + L.blocks_at);
+    uint8_t* inside = ws + L.inside_at;
+    unsigned long long* redo_map = reinterpret_cast<unsigned long long*>(ws + L.redo_at);
+    const dim3 grid(static_cast<unsigned>(L.n_chunks), M), block(QP_THREADS);
+    const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
+    hipLaunchKernelGGL(k_quantize_pack_bracketed<B>, grid, block, 0, stream, grads, worker_stride, norm_lo, norm_hi,
+                       plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems,
+                       key0, key1, step, worker_base, packed, packed_stride, partials, L.n_slots, blocks, L.n_chunks);
+    hipLaunchKernelGGL(k_bracket_norm_finish, dim3(plan->n_cseg, M), dim3(256), 0, stream, partials, L.n_slots,
+                       plan->d_cseg_start, plan->d_cseg_valid_end, plan->d_cseg_seg, plan->n_seg, plan->n_cseg, norm_lo,
+                       norm_hi, norms, inside);
+    hipLaunchKernelGGL(k_bracket_settle<B>, dim3(static_cast<unsigned>((L.n_chunks + 255) / 256), M), dim3(256), 0,
+                       stream, norms, plan->n_seg, plan->n_cseg, plan->d_granule_cseg, plan->d_cseg_seg,
+                       plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, blocks, L.n_chunks,
+                       inside, redo_map, L.n_words);
+    hipLaunchKernelGGL(k_bracket_redo<B>, dim3(static_cast<unsigned>((L.n_words + REDO_WORDS - 1) / REDO_WORDS), M),
+                       block, 0, stream, grads, worker_stride, norms, plan->n_seg, plan->d_granule_cseg,
+                       plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, key0, key1, step, worker_base,
+                       packed, packed_stride, redo_map, L.n_words);
+    if (stats) {
+        const int64_t n_blocks = static_cast<int64_t>(M) * L.n_chunks;
+        const int64_t wgs = (n_blocks + 256 * BS_PER_LANE - 1) / (256 * BS_PER_LANE);
+        hipLaunchKernelGGL(k_zero_two, dim3(1), dim3(2), 0, stream, stats);
+        hipLaunchKernelGGL(k_bracket_stats, dim3(static_cast<unsigned>(wgs < 256 ? wgs : 256)), dim3(256), 0, stream,
+                           blocks, n_blocks, stats);
+    }
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
+} // namespace
+
+extern "C" int64_t dq_bracketed_workspace_bytes(const dq_plan_t* plan, int M)
+{
+    if (!plan || M < 1 || M > DQ_MAX_WORKERS) return -1;
+    return dq_bracket_layout_of(plan, M).total;
+}
+
+extern "C" int dq_norm_quantize_pack_bracketed(const dq_plan_t* plan, const float* grads_dev,
+                                               int64_t worker_stride_elems, int M, const float* norm_lo_dev,
+                                               const float* norm_hi_dev, int b, uint64_t seed, uint32_t step,
+                                               uint32_t worker_base, float* norms_dev, uint8_t* packed_dev,
+                                               int64_t packed_worker_stride_bytes, void* workspace_dev,
+                                               int64_t* stats_dev, void* hip_stream)
+{
+    if (!plan || !grads_dev || !norm_lo_dev || !norm_hi_dev || !norms_dev || !packed_dev || !workspace_dev)
+        return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS || b < 1 || b > 8) return DQ_ERR_INVALID_ARG;
+    if (worker_stride_elems < plan->padded_elems || (worker_stride_elems & 3)) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < dq_packed_bytes(plan, b) || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(grads_dev) || !dq_aligned16(packed_dev) || !dq_aligned16(workspace_dev)) return DQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(norm_lo_dev) & 3u) || (reinterpret_cast<uintptr_t>(norm_hi_dev) & 3u) ||
+        (reinterpret_cast<uintptr_t>(norms_dev) & 3u) || (reinterpret_cast<uintptr_t>(stats_dev) & 7u))
+        return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (plan->n_cseg < plan->n_seg) { // tensors without elements: norm zero
+        const int zrc = dq_zero_floats(norms_dev, static_cast<int64_t>(M) * plan->n_seg, stream);
+        if (zrc != DQ_OK) return zrc;
+    }
+    if (plan->padded_elems == 0) return DQ_OK;
+    unsigned long long* stats = reinterpret_cast<unsigned long long*>(stats_dev);
+#define DQ_BRACKETED(B)                                                                                              \
+    case B:                                                                                                          \
+        return launch_bracketed<B>(plan, grads_dev, worker_stride_elems, M, norm_lo_dev, norm_hi_dev, seed, step,   \
+                                   worker_base, norms_dev, packed_dev, packed_worker_stride_bytes, workspace_dev,   \
+                                   stats, stream)
+    switch (b) {
+        DQ_BRACKETED(1);
+        DQ_BRACKETED(2);
+        DQ_BRACKETED(3);
+        DQ_BRACKETED(4);
+        DQ_BRACKETED(5);
+        DQ_BRACKETED(6);
+        DQ_BRACKETED(7);
+    default:
+        DQ_BRACKETED(8);
+    }
+#undef DQ_BRACKETED
+}

@@ -57,26 +57,38 @@ struct dq_widths {
     int32_t* b_host;         // [n_workers][n_seg] widths last set
 };
 
-// Workspace of dq_norm_quantize_pack_bracketed.  First the partial sums of squares, one binary64
-// slot per (worker, chunk, tensor in the chunk) at index chunk + c (c = the tensor's compact
-// index: both grow along the layout, so the sum is unique and a tensor's slots are contiguous);
-// then one 256-byte block per (worker, chunk) with the elements whose level the bracket could not
-// decide.
+// Workspace of dq_norm_quantize_pack_bracketed, four parts, each starting on a multiple of 256 bytes:
+//   partial sums of squares, one binary64 slot per (worker, chunk, tensor in the chunk) at index
+//     chunk + c (c = the tensor's compact index: both grow along the layout, so the sum is unique
+//     and a tensor's slots are contiguous);
+//   one 256-byte block per (worker, chunk) with the elements whose level the bracket left open;
+//   one byte per (worker, non-empty tensor): 1 if the norm came out inside its bracket;
+//   one bit per (worker, chunk), 64 chunks to a word: chunks that have to be quantized again.
 constexpr int DQ_BRACKET_CAP = 31; // records per block
 struct dq_bracket_block {
-    uint32_t count; // undecided elements found (may exceed DQ_BRACKET_CAP: then the chunk is redone)
-    uint32_t flags; // != 0: a tensor in the chunk had no usable bracket, nothing was quantized
+    uint32_t count; // open elements found (may exceed DQ_BRACKET_CAP: then the chunk is redone)
+    uint32_t flags; // bit 0: a tensor in the chunk had no usable bracket, nothing was quantized;
+                    // bit 1: the chunk was quantized again in full
     uint2 rec[DQ_BRACKET_CAP]; // .x = element index inside the chunk, .y = the gradient value's bits
 };
 static_assert(sizeof(dq_bracket_block) == 256, "one block per (worker, chunk), 256 bytes");
 
-static inline int64_t dq_bracket_slots(const dq_plan* plan)
+struct dq_bracket_layout {
+    int64_t n_chunks, n_slots, n_words;
+    int64_t blocks_at, inside_at, redo_at, total; // byte offsets into the workspace
+};
+static inline dq_bracket_layout dq_bracket_layout_of(const dq_plan* plan, int M)
 {
-    return (plan->padded_elems + 4095) / 4096 + plan->n_cseg;
-}
-static inline int64_t dq_bracket_partial_bytes(const dq_plan* plan, int M)
-{
-    return (static_cast<int64_t>(M) * dq_bracket_slots(plan) * 8 + 255) / 256 * 256;
+    auto up = [](int64_t v) { return (v + 255) / 256 * 256; };
+    dq_bracket_layout L;
+    L.n_chunks = (plan->padded_elems + 4095) / 4096;
+    L.n_slots = L.n_chunks + plan->n_cseg;
+    L.n_words = (L.n_chunks + 63) / 64;
+    L.blocks_at = up(static_cast<int64_t>(M) * L.n_slots * 8);
+    L.inside_at = L.blocks_at + static_cast<int64_t>(M) * L.n_chunks * 256;
+    L.redo_at = L.inside_at + up(static_cast<int64_t>(M) * plan->n_cseg);
+    L.total = L.redo_at + up(static_cast<int64_t>(M) * L.n_words * 8);
+    return L;
 }
 
 static inline bool dq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -1,0 +1,183 @@
+// The quantize+pack work of one 4096-element chunk (Eq. (5)-(6) and the message layout), shared by
+// the kernels of dq_quantize_pack.hip and dq_bracketed.hip.
+#pragma once
+#include "dq_chunk_norm.h"
+#include "dq_internal.h"
+
+namespace {
+
+#ifndef DQ_QP_TILES
+#define DQ_QP_TILES 2 // tiles of 2048 elements per workgroup
+#endif
+
+constexpr int QP_THREADS = 256;
+constexpr int QP_PER_LANE = 8;
+constexpr int QP_TILE = QP_THREADS * QP_PER_LANE; // 2048 elements
+
+// Writes the low B bytes of v at dst (LDS, byte offset a multiple of B) with naturally aligned
+// stores only.
+template <int B>
+__device__ __forceinline__ void stage_bytes(uint8_t* dst, uint64_t v)
+{
+    if constexpr (B == 8) {
+        *reinterpret_cast<uint64_t*>(dst) = v;
+    } else if constexpr (B == 4) {
+        *reinterpret_cast<uint32_t*>(dst) = static_cast<uint32_t>(v);
+    } else if constexpr (B % 2 == 0) {
+#pragma unroll
+        for (int k = 0; k < B / 2; ++k) reinterpret_cast<uint16_t*>(dst)[k] = static_cast<uint16_t>(v >> (16 * k));
+    } else {
+#pragma unroll
+        for (int k = 0; k < B; ++k) dst[k] = static_cast<uint8_t>(v >> (8 * k));
+    }
+}
+
+// Four elements (one Philox block): sign bits into bits 0..3 of `sign` (shifted in from the top
+// element down), levels into a 4*B-bit little-endian field.
+template <int B>
+__device__ __forceinline__ void quantize4(const float4 x, const float scale, const uint32_t (&r)[4],
+                                          uint32_t& sign, uint32_t& level)
+{
+    constexpr float S = static_cast<float>((1 << B) - 1);
+    const float v[4] = { x.x, x.y, x.z, x.w };
+    level = 0;
+#pragma unroll
+    for (int k = 3; k >= 0; --k) {
+        sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31); // (sign << 1) | sign bit
+        const float a = fminf(fabsf(v[k]) * scale, S);                     // s|g|/N, one rounding, clamped
+        const float p = __builtin_amdgcn_fractf(a);                         // a - floor(a), exact
+        const float u = static_cast<float>(r[k] >> 8) * 0x1p-24f;           // exact, in [0,1)
+        level = (level << B) + static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
+    }
+}
+
+// NORM = 0: the norms are an input.  NORM = 1 (l2) or 2 (max): chunk-local plans only; the kernel
+// computes the norms of its chunk's tensors itself, writes them to norms_out and quantizes from
+// the registers it already holds -- one read of the gradient instead of two.
+template <int B, int TILES, int NORM>
+__device__ __forceinline__ void quantize_pack_chunk(
+    const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
+    const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems,
+    uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
+    int64_t packed_stride, float* __restrict__ norms_out, uint32_t chunk_index)
+{
+    constexpr int CHUNK = QP_TILE * TILES;
+    constexpr int MAX_LOCAL_SEG = CHUNK / DQ_GRANULE;
+    constexpr float S = static_cast<float>((1 << B) - 1);
+    static_assert(NORM == 0 || CHUNK == DQ_CHUNK, "the fused norm works on 4096-element chunks");
+
+    __shared__ float lds_scale[MAX_LOCAL_SEG];
+    __shared__ int32_t lds_valid_end[MAX_LOCAL_SEG]; // relative to the chunk, clamped to CHUNK
+    __shared__ __align__(16) uint8_t lds_sign[TILES * QP_THREADS];
+    __shared__ __align__(16) uint8_t lds_level[TILES * QP_THREADS * B];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t w = blockIdx.y;
+    const int64_t chunk0 = static_cast<int64_t>(chunk_index) * CHUNK;
+    // elements of this chunk that exist (a multiple of 128, at least 128)
+    const uint32_t n_elems = static_cast<uint32_t>(padded_elems - chunk0 < CHUNK ? padded_elems - chunk0 : CHUNK);
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride + chunk0; // uniform base
+    const int32_t* gseg = granule_cseg + (chunk0 >> 7);
+
+    // This lane's inputs first, so the loads are in flight while the segment table is built.
+    // Lanes past the end of a ragged last chunk re-read its last eight elements (always in
+    // bounds); what they compute is never stored.
+    float4 x[TILES][2];
+    int32_t seg[TILES];
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        e = e < n_elems ? e : n_elems - QP_PER_LANE;
+        x[it][0] = *reinterpret_cast<const float4*>(g + e);
+        x[it][1] = *reinterpret_cast<const float4*>(g + e + 4);
+        seg[it] = gseg[e >> 7];
+    }
+
+    // compact segment indices grow by at most one per granule, so the chunk's segments fit the table
+    const int32_t seg_first = gseg[0];
+    const int32_t seg_last = gseg[(n_elems - 1) >> 7];
+    if constexpr (NORM == 0) {
+        if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
+            const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]];
+            lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f; // zero, tiny or NaN norm: every level 0
+            const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+            lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+        }
+        __syncthreads();
+    } else {
+        __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
+        __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
+        if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
+            const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+            lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+        }
+        __syncthreads();
+        int valid[TILES], local[TILES];
+#pragma unroll
+        for (int it = 0; it < TILES; ++it) {
+            const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+            local[it] = seg[it] - seg_first;
+            valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
+        }
+        dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+        __syncthreads();
+        if (tid < DQ_CHUNK_GRANULES)
+            dq_chunk_tensor_norms<NORM == 2>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+                                             [&](int j, float N) {
+                                                 norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
+                                                 lds_scale[j] = N >= DQ_MIN_NORM ? S / N : 0.0f;
+                                             });
+        __syncthreads();
+    }
+
+    // Philox counter words: quad index P>>2 (low word varies per lane, high word is uniform because
+    // a chunk never straddles a multiple of 2^34 elements), worker, step
+    const uint32_t quad_lo0 = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 2);
+    const uint32_t quad_hi = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 34);
+    const uint32_t worker = worker_base + w;
+
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        if (e < n_elems) {
+            const int local = seg[it] - seg_first;
+            const float scale = lds_scale[local];
+            const int32_t n_valid = lds_valid_end[local] - static_cast<int32_t>(e); // may be <= 0 or > 8
+
+            const uint32_t quad = quad_lo0 + (e >> 2); // even; quad + 1 cannot carry
+            uint32_t r0[4], r1[4];
+            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
+            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
+
+            uint32_t sign = 0, lv_lo, lv_hi;
+            quantize4<B>(x[it][1], scale, r1, sign, lv_hi); // elements 4..7 first: element 0 ends in bit 0
+            quantize4<B>(x[it][0], scale, r0, sign, lv_lo);
+            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * B));
+            if (n_valid < QP_PER_LANE) { // the tensor ends inside (or before) this lane's eight elements
+                const int nv = n_valid > 0 ? n_valid : 0;
+                sign &= (1u << nv) - 1u;
+                level &= (static_cast<uint64_t>(1) << (nv * B)) - 1u;
+            }
+            lds_sign[it * QP_THREADS + tid] = static_cast<uint8_t>(sign);
+            stage_bytes<B>(&lds_level[(it * QP_THREADS + tid) * B], level);
+        }
+    }
+    __syncthreads();
+
+    // 16-byte stores; every plane of a chunk is a whole number of 16-byte pieces because the
+    // chunk holds a multiple of 128 elements
+    uint8_t* msg = packed + static_cast<int64_t>(w) * packed_stride;
+    {
+        uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
+        const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+    }
+    {
+        uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + (chunk0 >> 3) * B);
+        const uint4* src = reinterpret_cast<const uint4*>(lds_level);
+        for (uint32_t i = tid; i < n_elems / 128 * B; i += QP_THREADS) dst[i] = src[i];
+    }
+}
+
+} // namespace

@@ -36,5 +36,6 @@ def test_short_run_prints_the_json_line():
     assert set(r["per_b"]) == {str(b) for b in range(1, 9)}
     cb = r["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
-    for name in ("dq_norm", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_norm_quantize_pack"):
+    for name in ("dq_norm", "dq_quantize_pack", "dq_unpack_dequant_reduce", "dq_norm_quantize_pack",
+                 "dq_norm_quantize_pack_bracketed"):
         assert r["kernels"][name]["avg_ms"] > 0

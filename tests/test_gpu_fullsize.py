@@ -224,6 +224,25 @@ def test_config5_other_entry_points_sampled(dq, oracle):
     assert torch.equal(out.view(torch.int32), out_v.view(torch.int32))
     del packed_v
 
+    # norms and messages in one pass with a bracket of +-12.5 % around the norms: same norms, same bytes
+    wsb = torch.empty(dq.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device="cuda")
+    stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+    norms_b = torch.empty_like(norms_dev)
+    packed_b = torch.zeros_like(packed)
+    dq.norm_quantize_pack_bracketed(plan, g, norms_dev * 0.875, norms_dev * 1.125, b, SEED, step, norms_b, packed_b,
+                                    wsb, stats=stats)
+    torch.cuda.synchronize()
+    assert float(((norms_b.double() - norms_dev.double()).abs() / norms_dev.double()).max()) <= 2.0 ** -23
+    if torch.equal(norms_b, norms_dev):
+        assert torch.equal(packed_b, packed)
+    else:  # a norm differs in the last place: compare through the two-pass route with these norms
+        dq.quantize_pack(plan, g, norms_b, b, SEED, step, packed)
+        torch.cuda.synchronize()
+        assert torch.equal(packed_b, packed)
+        dq.quantize_pack(plan, g, norms_dev, b, SEED, step, packed)
+    assert int(stats[1]) == 0 and 0 < int(stats[0]) < M * D // 1000   # a few settled elements, no chunk redone
+    del packed_b, wsb
+
     # fused update: x - eta*g_hat with one rounding, against torch on the device
     eta = 0.125
     x = torch.randn(D, device="cuda")

@@ -107,3 +107,49 @@ def test_one_pass_lagged_step_in_a_graph(dq):
         dq.norm(plan, B["g"], torch.empty_like(B["norms"]), B["ws"])
         torch.cuda.synchronize()
     plan.close()
+
+
+def test_bracketed_step_in_a_graph(dq):
+    """norms and messages in one pass with a bracket from the previous norms, then the fused update;
+    the statistics counters are part of the graph (a zeroing kernel, no memset)"""
+    seg_len = [3 * 4096 + 700, 100, 9000]
+    M, b, eta = 3, 3, 0.05
+    plan, B = _setup(dq, seg_len, M, 112)
+    pk = B["packed"][:, :plan.packed_bytes(b)]
+    dq.norm(plan, B["g"], B["norms"], B["ws"])
+    torch.cuda.synchronize()
+    lo, hi = B["norms"] * 0.9, B["norms"] * 1.1
+    wsb = torch.empty(dq.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device="cuda")
+    stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+    norms2 = torch.empty_like(B["norms"])
+
+    def step():
+        dq.norm_quantize_pack_bracketed(plan, B["g"], lo, hi, b, SEED, 7, norms2, pk, wsb, stats=stats)
+        dq.unpack_dequant_reduce_update(plan, pk, norms2, b, eta, B["x"])
+
+    want = []
+    for _ in range(3):
+        step()
+        torch.cuda.synchronize()
+        want.append(B["x"].clone())
+    want_stats = stats.clone()
+    assert int(want_stats[0]) > 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    B["x"].zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for k in range(3):
+        stats.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(B["x"].view(torch.int32), want[k].view(torch.int32)), f"replay {k}"
+        assert torch.equal(stats, want_stats)
+        dq.norm(plan, B["g"], torch.empty_like(B["norms"]), B["ws"])
+        torch.cuda.synchronize()
+    plan.close()

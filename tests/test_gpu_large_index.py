@@ -107,6 +107,26 @@ def test_codes_and_average_in_windows(dq, oracle, big, b):
     torch.cuda.synchronize()
     assert torch.equal(sp[0], pk[0, :DP // 8])
     del sp
+    # one pass with a bracket: records and fix-ups past index 2^32, partial-sum slots past 2^22 chunks
+    wsb = torch.empty(dq.bracketed_workspace_bytes(plan, 1), dtype=torch.uint8, device="cuda")
+    pk_b = torch.empty_like(pk)
+    norms_b = torch.empty_like(norms_dev)
+    stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+    dq.norm_quantize_pack_bracketed(plan, g, norms_dev * 0.9, norms_dev * 1.1, b, SEED, STEP, norms_b, pk_b, wsb,
+                                    worker_base=WORKER, stats=stats)
+    torch.cuda.synchronize()
+    if torch.equal(norms_b, norms_dev):
+        assert torch.equal(pk_b, pk)
+    else:
+        assert abs(float(norms_b[0, 0]) - float(norms_dev[0, 0])) <= np.spacing(np.float32(norms_dev[0, 0].item()))
+        dq.quantize_pack(plan, g, norms_b, b, SEED, STEP, pk, worker_base=WORKER)
+        torch.cuda.synchronize()
+        assert torch.equal(pk_b, pk)
+        dq.quantize_pack(plan, g, norms_dev, b, SEED, STEP, pk, worker_base=WORKER)
+        torch.cuda.synchronize()
+    assert int(stats[0]) > 0
+    del pk_b, wsb
+    torch.cuda.empty_cache()
     table = dq.Widths(plan, [b])
     pk_v = torch.empty_like(pk)
     dq.quantize_pack_v(plan, table, g, norms_dev, SEED, STEP, pk_v, worker_base=WORKER)
