@@ -63,10 +63,18 @@ __device__ __forceinline__ void dq_chunk_granule_sums(const float4 (&x)[2][2], c
             granule = static_cast<double>(m);
         } else {
             double acc = 0.0;
+            if (valid[it] >= 8) { // all eight belong to the tensor (almost every lane): no masking
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const double e = static_cast<double>(k < valid[it] ? v[k] : 0.0f);
-                acc = __builtin_fma(e, e, acc);
+                for (int k = 0; k < 8; ++k) {
+                    const double e = static_cast<double>(v[k]);
+                    acc = __builtin_fma(e, e, acc);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const double e = static_cast<double>(k < valid[it] ? v[k] : 0.0f);
+                    acc = __builtin_fma(e, e, acc);
+                }
             }
             acc += dq_row_ror<8>(acc);
             acc += dq_row_ror<4>(acc);
