@@ -288,3 +288,44 @@ def test_python_twin_agrees_beyond_32_bit_indices(oracle, center):
         assert pyref.philox4x32_10([(center - 4) >> 2 & 0xFFFFFFFF, 0, 0, 0], [SEED & 0xFFFFFFFF, SEED >> 32])[0] == lo
         assert pyref.element_random_word(center, 0, 0, SEED) == \
             pyref.philox4x32_10([0, 1, 0, 0], [SEED & 0xFFFFFFFF, SEED >> 32])[0]
+
+
+@pytest.mark.parametrize("b", [1, 3, 4, 8])
+def test_level_never_grows_with_the_norm(oracle, b):
+    """For a fixed element, seed, step and worker the level of Eq. (5)-(6) is a non-increasing
+    function of the norm (all roundings included): scale, scaled magnitude, clamp and the stochastic
+    step are each monotone.  Hence a level that is the same for two norms is the level for every
+    norm between them -- what the one-pass path with bracketed norms relies on.  Checked on sweeps of
+    the norm that include neighbouring binary32 values and norms near the largest element."""
+    rng = np.random.default_rng(700 + b)
+    d = 4096
+    g = np.concatenate([rng.standard_normal(d // 2) * 1e-2, rng.standard_t(3, d // 2) * 1e-2]).astype(np.float32)
+    g[:8] = [0.0, -0.0, 1e-30, -1e-30, 5.0, -5.0, np.float32(1e-2), np.float32(-1e-2)]
+    grads = g[None, :]
+    base = float(np.sqrt((g.astype(np.float64) ** 2).sum()))
+    sweep = [np.float32(base * f) for f in (0.01, 0.1, 0.5, 0.875, 0.99, 1.0, 1.01, 1.125, 2.0, 10.0, 1000.0)]
+    for f in (0.5, 1.0, 5.0):                       # runs of neighbouring floats
+        x = np.float32(base * f)
+        for _ in range(12):
+            sweep.append(x)
+            x = np.nextafter(x, np.float32(np.inf))
+    sweep += [np.float32(5.0), np.nextafter(np.float32(5.0), np.float32(0)), np.float32(4.0)]   # |g|/N at and above 1
+    sweep = sorted(set(float(x) for x in sweep))
+    prev = None
+    for N in sweep:
+        _, level = oracle.quantize([d], grads, np.array([[N]], dtype=np.float32), b, SEED, 5, worker_base=3)
+        if prev is not None:
+            assert np.all(level[0] <= prev), N
+        prev = level[0].copy()
+    # equal at both ends => equal inside
+    lo, hi = np.float32(base * 0.875), np.float32(base * 1.125)
+    _, l_lo = oracle.quantize([d], grads, np.array([[lo]], dtype=np.float32), b, SEED, 5, worker_base=3)
+    _, l_hi = oracle.quantize([d], grads, np.array([[hi]], dtype=np.float32), b, SEED, 5, worker_base=3)
+    same = l_lo[0] == l_hi[0]
+    for f in rng.uniform(0.875, 1.125, size=20):
+        N = np.float32(base * f)
+        if not (lo <= N <= hi):
+            continue
+        _, l_mid = oracle.quantize([d], grads, np.array([[N]], dtype=np.float32), b, SEED, 5, worker_base=3)
+        assert np.array_equal(l_mid[0][same], l_lo[0][same])
+        assert np.all((l_mid[0] <= l_lo[0]) & (l_mid[0] >= l_hi[0]))
