@@ -20,6 +20,10 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
     (``plan.chunk_local``: no tensor crosses a multiple of 4096 padded elements, e.g. a gradient
     cut into buckets) the worker side is the single pass ``dq_norm_quantize_pack``; one_pass=False
     keeps the two calls.
+  * norm_margin=m (with the lagged rule, p = 2, base mode): from the second iteration on the worker
+    side is the single pass ``dq_norm_quantize_pack_bracketed`` on any layout, every norm bracketed
+    by the previous iteration's norm times (1 -+ m); the messages are the same as with the two
+    calls whatever m is, a bracket that misses only costs time.
   * per_worker=True: every worker takes Eq. (17) with its own norm (``dq_select_bits_per_worker``;
     with per_tensor=True also one width per tensor); b_t in the result are [M][n_seg] arrays.
   * device_rule=True: the rule runs on the GPU (``dq_select_bits_device``) and the loop never waits
@@ -69,7 +73,8 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         b_min: int = 1, b_max: int = 8, tau: int = 1, lagged: bool = True, seed: int = 0,
         loss_fn: Optional[Callable[["torch.Tensor"], float]] = None, B_pre: int = 32,
         on_step: Optional[Callable] = None, p: Union[int, str] = 2, per_tensor: bool = False,
-        device_rule: bool = False, one_pass: bool = True, per_worker: bool = False) -> DQSGDResult:
+        device_rule: bool = False, one_pass: bool = True, per_worker: bool = False,
+        norm_margin: Optional[float] = None) -> DQSGDResult:
     """grad_fn(t, x, grads_out) fills grads_out[M][D'] (float32, CUDA, padded layout) with the M
     workers' stochastic gradients at x.  on_step(t, b_t, grads, norms_host, packed) is called after
     the quantize pass of every iteration (tests use it to feed the same bytes to the oracle)."""
@@ -108,14 +113,27 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
     b = int(b0)
 
     single_pass = one_pass and lagged and plan.chunk_local
+    bracketed = norm_margin is not None and lagged and p == 2 and not single_pass
+    if bracketed:
+        if not 0.0 <= norm_margin < 1.0:
+            raise ValueError("norm_margin must be in [0, 1)")
+        wsb = torch.empty(_b.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device=dev)
+        prev, lo, hi = (torch.empty_like(norms) for _ in range(3))
     for t in range(T):
         grad_fn(t, x, grads)
         pk = None
         if single_pass:
             pk = packed[:, :plan.packed_bytes(b)]
             _b.norm_quantize_pack(plan, grads, b, seed, t, norms, pk, linf=p != 2)
+        elif bracketed and t > 0:
+            torch.mul(prev, 1.0 - norm_margin, out=lo)   # the caller's guess, an input of the library
+            torch.mul(prev, 1.0 + norm_margin, out=hi)
+            pk = packed[:, :plan.packed_bytes(b)]
+            _b.norm_quantize_pack_bracketed(plan, grads, lo, hi, b, seed, t, norms, pk, wsb)
         else:
             norm_fn(plan, grads, norms, ws)
+        if bracketed:
+            prev.copy_(norms)
         norms_host.copy_(norms, non_blocking=True)
         if not lagged:
             torch.cuda.current_stream().synchronize()

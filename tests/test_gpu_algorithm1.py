@@ -98,6 +98,42 @@ def test_config4_trajectory_matches_the_oracle_loop(dq, oracle, problem):
     plan.close()
 
 
+def test_config4_through_the_bracketed_single_pass(dq, oracle, problem):
+    """The same loop with every norm bracketed by the previous iteration's (+-30 %): from the second
+    iteration on norms and messages come from one pass over the gradient; every b_t and every
+    bitstream still equals the oracle's for the norms of that iteration."""
+    from paper_2107_14575_amd import dqsgd
+    d, M, T, eta, alpha, tau = problem["d"], problem["M"], 120, 0.25, 0.98, 20
+    plan = dq.Plan([d])
+    dp = plan.padded_elems
+    x0 = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    g_probe = torch.zeros((M, dp), dtype=torch.float32, device="cuda")
+    problem["grad_fn"](0, x0, g_probe)
+    gbar0 = float(np.sqrt((oracle.norm([d], g_probe.cpu().numpy()).astype(np.float64) ** 2).mean()))
+    eps_hat = T * (gbar0 / 200.0) ** 2
+    x_or = np.zeros(dp, dtype=np.float32)
+    state = dict(b=2, bits=[])
+
+    def on_step(t, b, grads, norms, packed):
+        g_host = np.ascontiguousarray(grads.cpu().numpy())
+        assert b == state["b"], f"b_t differs at t={t}"
+        want_n = oracle.norm([d], g_host)
+        assert np.all(np.abs(norms.astype(np.float64) - want_n.astype(np.float64)) <= np.spacing(want_n))
+        want = oracle.quantize_pack([d], g_host, norms, b, SEED, t)
+        assert np.array_equal(packed.cpu().numpy(), want), f"bitstream differs at t={t}"
+        oracle.update(x_or, oracle.unpack_dequant_reduce([d], want, norms, b), eta)
+        state["bits"].append(b)
+        if t + 1 < T and (t + 1) % tau == 0:
+            state["b"], _ = oracle.select_bits(norms, t + 1, T, eps_hat, alpha, 2, 8)
+
+    res = dqsgd.run(plan, x0, problem["grad_fn"], M, T, eta, eps_hat, alpha, b0=2, b_min=2, b_max=8,
+                    tau=tau, lagged=True, seed=SEED, on_step=on_step, norm_margin=0.3)
+    assert res.bits == state["bits"]
+    tol = T * (2.0 ** -23 * np.abs(x_or).max() + eta * 1e-6 * 1.0)
+    assert np.abs(res.x.cpu().numpy() - x_or).max() <= tol
+    plan.close()
+
+
 def test_same_step_rule_and_alpha_estimate(dq, oracle, problem):
     """lagged=False computes b_t from iteration t's own norms (checked against the oracle's rule);
     alpha='estimate' uses Eq. (24) with the caller's loss at every update."""
