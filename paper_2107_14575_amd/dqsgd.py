@@ -20,10 +20,12 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
     (``plan.chunk_local``: no tensor crosses a multiple of 4096 padded elements, e.g. a gradient
     cut into buckets) the worker side is the single pass ``dq_norm_quantize_pack``; one_pass=False
     keeps the two calls.
-  * norm_margin=m (with the lagged rule, p = 2, base mode): from the second iteration on the worker
-    side is the single pass ``dq_norm_quantize_pack_bracketed`` on any layout, every norm bracketed
-    by the previous iteration's norm times (1 -+ m); the messages are the same as with the two
-    calls whatever m is, a bracket that misses only costs time.
+  * norm_margin=m (p = 2, base mode): from the second iteration on the worker side is the single
+    pass ``dq_norm_quantize_pack_bracketed`` on any layout, every norm bracketed by the previous
+    iteration's norm times (1 -+ m); the messages are the same as with the two calls whatever m
+    is, a bracket that misses only costs time.  With lagged=False the pass is taken when both ends
+    of the bracket give the same b_t (Eq. (17) is monotone in the norms); b_t is checked against
+    the true norms afterwards and the quantization repeated if it moved.
   * per_worker=True: every worker takes Eq. (17) with its own norm (``dq_select_bits_per_worker``;
     with per_tensor=True also one width per tensor); b_t in the result are [M][n_seg] arrays.
   * device_rule=True: the rule runs on the GPU (``dq_select_bits_device``) and the loop never waits
@@ -36,6 +38,7 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import Callable, List, Optional, Union
 
+import numpy as _np
 import torch
 
 from . import binding as _b
@@ -113,7 +116,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
     b = int(b0)
 
     single_pass = one_pass and lagged and plan.chunk_local
-    bracketed = norm_margin is not None and lagged and p == 2 and not single_pass
+    bracketed = norm_margin is not None and p == 2 and not single_pass
     if bracketed:
         if not 0.0 <= norm_margin < 1.0:
             raise ValueError("norm_margin must be in [0, 1)")
@@ -128,8 +131,19 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         elif bracketed and t > 0:
             torch.mul(prev, 1.0 - norm_margin, out=lo)   # the caller's guess, an input of the library
             torch.mul(prev, 1.0 + norm_margin, out=hi)
-            pk = packed[:, :plan.packed_bytes(b)]
-            _b.norm_quantize_pack_bracketed(plan, grads, lo, hi, b, seed, t, norms, pk, wsb)
+            b_guess = b
+            if not lagged:
+                # Eq. (17) never decreases in any norm, so if both ends of the bracket give the same b,
+                # every set of norms inside it does; norms_host still holds the previous iteration's.
+                n_prev = norms_host.numpy()
+                b_lo = rule(n_prev * _np.float32(1.0 - norm_margin), t, T, eps_hat_q, cur_alpha, b_min, b_max)[0]
+                b_hi = rule(n_prev * _np.float32(1.0 + norm_margin), t, T, eps_hat_q, cur_alpha, b_min, b_max)[0]
+                b_guess = b_lo if b_lo == b_hi else None
+            if b_guess is None:
+                norm_fn(plan, grads, norms, ws)
+            else:
+                pk = packed[:, :plan.packed_bytes(b_guess)]
+                _b.norm_quantize_pack_bracketed(plan, grads, lo, hi, b_guess, seed, t, norms, pk, wsb)
         else:
             norm_fn(plan, grads, norms, ws)
         if bracketed:
@@ -138,6 +152,8 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
         if not lagged:
             torch.cuda.current_stream().synchronize()
             b, gb = rule(norms_host.numpy(), t, T, eps_hat_q, cur_alpha, b_min, b_max)
+            if pk is not None and b != b_guess:   # a norm left its bracket and moved b: quantize again
+                pk = None
         if pk is None:
             pk = packed[:, :plan.packed_bytes(b)]
             _b.quantize_pack(plan, grads, norms, b, seed, t, pk)

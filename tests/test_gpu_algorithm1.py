@@ -134,6 +134,33 @@ def test_config4_through_the_bracketed_single_pass(dq, oracle, problem):
     plan.close()
 
 
+def test_same_step_rule_through_the_bracketed_single_pass(dq, oracle, problem):
+    """b_t from iteration t's own norms (lagged=False) and still one pass: taken whenever the
+    bracket around the previous norms pins b_t; every b_t and bitstream equals the oracle's."""
+    from paper_2107_14575_amd import dqsgd
+    d, M, T, eta, alpha = problem["d"], problem["M"], 80, 0.25, 0.9
+    plan = dq.Plan([d])
+    dp = plan.padded_elems
+    x0 = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    g_probe = torch.zeros((M, dp), dtype=torch.float32, device="cuda")
+    problem["grad_fn"](0, x0, g_probe)
+    gbar0 = float(np.sqrt((oracle.norm([d], g_probe.cpu().numpy()).astype(np.float64) ** 2).mean()))
+    eps_hat = T * (gbar0 / 200.0) ** 2
+    seen = []
+
+    def on_step(t, b, grads, norms, packed):
+        g_host = np.ascontiguousarray(grads.cpu().numpy())
+        want_b, _ = oracle.select_bits(norms, t, T, eps_hat, alpha, 2, 8)
+        assert b == want_b, f"b_t differs at t={t}"
+        assert np.array_equal(packed.cpu().numpy(), oracle.quantize_pack([d], g_host, norms, b, SEED, t)), t
+        seen.append(b)
+
+    res = dqsgd.run(plan, x0, problem["grad_fn"], M, T, eta, eps_hat, alpha, b0=2, b_min=2, b_max=8,
+                    tau=1, lagged=False, seed=SEED, on_step=on_step, norm_margin=0.05)
+    assert res.bits == seen and len(set(seen)) >= 4      # the width really moves during the run
+    plan.close()
+
+
 def test_same_step_rule_and_alpha_estimate(dq, oracle, problem):
     """lagged=False computes b_t from iteration t's own norms (checked against the oracle's rule);
     alpha='estimate' uses Eq. (24) with the caller's loss at every update."""
