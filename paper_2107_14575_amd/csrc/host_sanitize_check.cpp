@@ -67,6 +67,11 @@ int main()
         CHECK(dq_unpack_dequant_reduce(plan, fake8, 16, M, fake, 4, fake, nullptr) == DQ_ERR_INVALID_ARG || dp == 0);
         CHECK(dq_sign_pack(plan, fake, dp, 0, fake8, 1 << 30, nullptr) == DQ_ERR_INVALID_ARG);
         CHECK(dq_quantize_pack_v(plan, nullptr, fake, dp, M, fake, 1, 0, 0, fake8, 1 << 30, nullptr) == DQ_ERR_INVALID_ARG);
+        // one pass with bracketed norms: the workspace covers its four parts; bad arguments are refused
+        CHECK(dq_bracketed_workspace_bytes(plan, M) >= (dp + 4095) / 4096 * 256 * M && dq_bracketed_workspace_bytes(plan, 0) == -1);
+        CHECK(dq_bracketed_workspace_bytes(plan, M) % 256 == 0 && dq_bracketed_workspace_bytes(nullptr, M) == -1);
+        CHECK(dq_norm_quantize_pack_bracketed(plan, fake, dp, M, fake, fake, 9, 1, 0, 0, fake, fake8, 1 << 30, fake8, nullptr, nullptr) == DQ_ERR_INVALID_ARG);
+        CHECK(dq_norm_quantize_pack_bracketed(plan, fake, dp, M, nullptr, fake, 4, 1, 0, 0, fake, fake8, 1 << 30, fake8, nullptr, nullptr) == DQ_ERR_INVALID_ARG);
         dq_plan_destroy(plan);
     }
     dq_plan_t* none = nullptr;
