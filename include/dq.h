@@ -286,8 +286,9 @@ int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, co
  * roundings included), so an element that gets the same level at both ends of the bracket gets it
  * for every norm inside.  The first kernel reads the gradient once, quantizes with both ends,
  * writes what is decided and records the few undecided elements (index and value); after the
- * norms are known a second kernel settles the recorded elements.  A chunk of 4096 elements with
- * more than 31 undecided elements, a tensor whose bracket is unusable (not lo >= DQ_MIN_NORM,
+ * norms are known a second kernel settles the recorded elements.  A tensor that lies inside one
+ * 4096-element chunk needs no bracket (its norm is finished on the spot).  A chunk with
+ * more than 63 undecided elements, a tensor whose bracket is unusable (not lo >= DQ_MIN_NORM,
  * lo <= hi, hi finite) or whose norm falls outside its bracket is quantized again from the
  * gradient: the result is the same for any bracket, only the time differs (a wrong bracket
  * costs about the two separate passes).

@@ -9,13 +9,16 @@
 // whose level is the same at both ends of the bracket has that level for every norm inside it.
 //
 //   k_quantize_pack_bracketed  reads the gradient once: adds up each tensor's squares chunk by
-//       chunk (binary64 partial sums, one slot per chunk and tensor), quantizes with the low end
+//       chunk (binary64 partial sums, one slot per chunk and tensor).  A tensor that lies wholly
+//       inside the chunk needs no bracket: its norm is finished on the spot and used.  For the
+//       others the kernel quantizes with the low end
 //       of the bracket (the largest levels), looks at the non-zero levels again with the high end,
 //       writes the levels that agree, leaves the others' fields zero and records those elements
 //       (index and value) in the chunk's block of the workspace.
 //   k_bracket_norm_finish      adds a tensor's partial sums in a fixed order: the norms, and
 //       whether each came out inside its bracket.
-//   k_bracket_settle           one lane per chunk: quantizes the chunk's recorded elements with the
+//   k_bracket_settle[_wide]    one lane per chunk (large plans) or one wavefront per chunk with a
+//       lane per record (up to 2^18 chunks): quantizes the chunk's recorded elements with the
 //       true norm and ORs their levels into the zero fields; a chunk with too many records, with
 //       no usable bracket, or with a norm outside its bracket gets a bit in the redo map instead.
 //   k_bracket_redo             quantizes the chunks of the redo map again in full from the
@@ -41,10 +44,10 @@ template <int B>
 __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norm_lo,
     const float* __restrict__ norm_hi, int32_t n_seg, const int32_t* __restrict__ granule_cseg,
-    const int32_t* __restrict__ cseg_seg, const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems,
-    uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
-    int64_t packed_stride, double* __restrict__ partials, int64_t n_slots, dq_bracket_block* __restrict__ blocks,
-    int64_t n_chunks)
+    const int32_t* __restrict__ cseg_seg, const int64_t* __restrict__ cseg_start,
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
+    uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride, double* __restrict__ partials,
+    int64_t n_slots, dq_bracket_block* __restrict__ blocks, int64_t n_chunks, float* __restrict__ norms_out)
 {
     constexpr int TILES = 2;
     constexpr int CHUNK = DQ_CHUNK;
@@ -57,6 +60,8 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
     __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
     __shared__ uint32_t lds_count;
+    __shared__ int32_t lds_whole[DQ_CHUNK_GRANULES]; // the tensor lies wholly inside this chunk
+    __shared__ int32_t lds_any_whole;
     __shared__ __align__(16) uint8_t lds_sign[TILES * QP_THREADS];
     __shared__ __align__(16) uint8_t lds_level[TILES * QP_THREADS * B];
 
@@ -81,20 +86,28 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
 
     const int32_t seg_first = gseg[0];
     const int32_t seg_last = gseg[(n_elems - 1) >> 7];
-    if (tid == 0) lds_count = 0;
+    if (tid == 0) {
+        lds_count = 0;
+        lds_any_whole = 0;
+    }
     int unusable = 0;
-    if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
+    if (static_cast<int32_t>(tid) <= seg_last - seg_first) { // lanes of the first wavefront, after lane 0's stores above
         const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid];
+        const int64_t valid_end = cseg_valid_end[seg_first + tid];
+        const bool whole = cseg_start[seg_first + tid] >= chunk0 && valid_end <= chunk0 + CHUNK;
         const float lo = norm_lo[at], hi = norm_hi[at];
         // the zero path (norm below DQ_MIN_NORM) is not monotone against the rest: no bracket across it
         const bool ok = lo >= DQ_MIN_NORM && hi >= lo && hi <= 3.0e38f; // false for NaN
-        lds_scale_hi[tid] = ok ? S / lo : 0.0f;
+        lds_scale_hi[tid] = ok ? S / lo : 0.0f; // replaced below for a tensor that is whole
         lds_scale_lo[tid] = ok ? S / hi : 0.0f;
-        unusable = ok ? 0 : 1;
-        const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+        lds_whole[tid] = whole ? 1 : 0;
+        if (whole) lds_any_whole = 1;
+        unusable = (ok || whole) ? 0 : 1;
+        const int64_t rel = valid_end - chunk0;
         lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
     }
     const int skip = __syncthreads_or(unusable); // also the barrier after the tables
+    const bool any_whole = lds_any_whole != 0;
 
     // partial sums of squares of the chunk's tensors
     int valid[TILES], local[TILES];
@@ -110,7 +123,15 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
         dq_chunk_tensor_totals<false>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
                                       [&](int j, double total) {
                                           partials[static_cast<int64_t>(w) * n_slots + blockIdx.x + seg_first + j] = total;
+                                          if (lds_whole[j]) { // the tensor's norm, as the finishing kernel will find it
+                                              const float N = static_cast<float>(sqrt(total));
+                                              norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
+                                              const float scale = N >= DQ_MIN_NORM ? S / N : 0.0f;
+                                              lds_scale_hi[j] = scale;
+                                              lds_scale_lo[j] = scale;
+                                          }
                                       });
+    if (any_whole) __syncthreads(); // uniform: scales written just above
     if (skip) { // uniform: the redo kernel quantizes this chunk from the gradient
         if (tid == 0) {
             blk->count = 0;
@@ -218,11 +239,85 @@ __global__ __launch_bounds__(256) void k_bracket_norm_finish(
         const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[c];
         const float N = static_cast<float>(sqrt(part[0]));
         norms[at] = N;
-        inside[static_cast<int64_t>(w) * n_cseg + c] = (N >= norm_lo[at] && N <= norm_hi[at]) ? 1 : 0;
+        // a tensor inside one chunk was quantized with this very norm: no bracket involved
+        inside[static_cast<int64_t>(w) * n_cseg + c] = (first == last || (N >= norm_lo[at] && N <= norm_hi[at])) ? 1 : 0;
     }
 }
 
-// grid (ceil(n_chunks / 256), M), one lane per chunk.
+// One recorded element: its level for the true norm, ORed into the zero field the first kernel left.
+template <int B>
+__device__ __forceinline__ void settle_record(uint2 rec, int64_t chunk0, uint32_t w, const float* __restrict__ norms,
+                                              int32_t n_seg, const int32_t* __restrict__ granule_cseg,
+                                              const int32_t* __restrict__ cseg_seg, uint32_t key0, uint32_t key1,
+                                              uint32_t step, uint32_t worker, uint32_t* __restrict__ plane)
+{
+    constexpr float S = static_cast<float>((1 << B) - 1);
+    const uint32_t e = rec.x; // < 4096 and inside the layout: written by the first kernel for this chunk
+    const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[granule_cseg[(chunk0 >> 7) + (e >> 7)]]];
+    const float scale = N >= DQ_MIN_NORM ? S / N : 0.0f;
+    const uint64_t P = static_cast<uint64_t>(chunk0) + e;
+    uint32_t r[4];
+    dq_philox4x32_10(static_cast<uint32_t>(P >> 2), static_cast<uint32_t>(P >> 34), worker, step, key0, key1, r);
+    const uint32_t word = (P & 2u) ? ((P & 1u) ? r[3] : r[2]) : ((P & 1u) ? r[1] : r[0]);
+    const uint32_t level = level_of<B>(__uint_as_float(rec.y), scale, word);
+    if (level != 0) {
+        // fields of other elements in the same words are not touched
+        const uint64_t bit = P * B;
+        const uint32_t sh = static_cast<uint32_t>(bit & 31u);
+        atomicOr(plane + (bit >> 5), level << sh);
+        if (sh + B > 32) atomicOr(plane + (bit >> 5) + 1, level >> (32 - sh));
+    }
+}
+
+// What the settle kernels decide per chunk: true if the chunk has to be quantized again.
+__device__ __forceinline__ bool chunk_needs_redo(uint32_t count, uint32_t flags, int64_t chunk0, int64_t padded_elems,
+                                                 uint32_t w, int32_t n_cseg, const int32_t* __restrict__ granule_cseg,
+                                                 const uint8_t* __restrict__ inside)
+{
+    const int64_t last_granule = ((chunk0 + DQ_CHUNK < padded_elems ? chunk0 + DQ_CHUNK : padded_elems) - 1) >> 7;
+    const int32_t c_first = granule_cseg[chunk0 >> 7], c_last = granule_cseg[last_granule];
+    bool again = flags != 0 || count > DQ_BRACKET_CAP;
+    for (int32_t c = c_first; c <= c_last; ++c) again = again || inside[static_cast<int64_t>(w) * n_cseg + c] == 0;
+    return again;
+}
+
+// grid (ceil(n_chunks / 4), M), one wavefront per chunk and one lane per record: for plans of
+// moderate size, where a launch of that many wavefronts is cheap and a chunk may hold dozens of
+// records.
+template <int B>
+__global__ __launch_bounds__(256) void k_bracket_settle_wide(
+    const float* __restrict__ norms, int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ granule_cseg,
+    const int32_t* __restrict__ cseg_seg, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
+    uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride, dq_bracket_block* __restrict__ blocks,
+    int64_t n_chunks, const uint8_t* __restrict__ inside, unsigned long long* __restrict__ redo_map, int64_t n_words)
+{
+    const uint32_t w = blockIdx.y;
+    const uint32_t lane = threadIdx.x & 63;
+    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (chunk >= n_chunks) return; // the whole wavefront
+    dq_bracket_block* blk = blocks + static_cast<int64_t>(w) * n_chunks + chunk;
+    const uint32_t count = blk->count, flags = blk->flags;
+    const int64_t chunk0 = chunk * DQ_CHUNK;
+    const bool again = chunk_needs_redo(count, flags, chunk0, padded_elems, w, n_cseg, granule_cseg, inside);
+    if (again) {
+        if (lane == 0) {
+            blk->flags = flags | 2u;
+            atomicOr(redo_map + static_cast<int64_t>(w) * n_words + (chunk >> 6), 1ull << (chunk & 63));
+        }
+    } else if (lane < count) {
+        uint32_t* plane = reinterpret_cast<uint32_t*>(packed + static_cast<int64_t>(w) * packed_stride + (padded_elems >> 3));
+        settle_record<B>(blk->rec[lane], chunk0, w, norms, n_seg, granule_cseg, cseg_seg, key0, key1, step,
+                         worker_base + w, plane);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_zero_words(unsigned long long* __restrict__ dst, int64_t n)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) dst[i] = 0;
+}
+
+// grid (ceil(n_chunks / 256), M), one lane per chunk: for large plans with few records per chunk.
 template <int B>
 __global__ __launch_bounds__(256) void k_bracket_settle(
     const float* __restrict__ norms, int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ granule_cseg,
@@ -230,7 +325,6 @@ __global__ __launch_bounds__(256) void k_bracket_settle(
     uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride, dq_bracket_block* __restrict__ blocks,
     int64_t n_chunks, const uint8_t* __restrict__ inside, unsigned long long* __restrict__ redo_map, int64_t n_words)
 {
-    constexpr float S = static_cast<float>((1 << B) - 1);
     const uint32_t w = blockIdx.y;
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const bool active = chunk < n_chunks;
@@ -239,34 +333,15 @@ __global__ __launch_bounds__(256) void k_bracket_settle(
         dq_bracket_block* blk = blocks + static_cast<int64_t>(w) * n_chunks + chunk;
         const uint32_t count = blk->count, flags = blk->flags;
         const int64_t chunk0 = chunk * DQ_CHUNK;
-        const int64_t last_granule = ((chunk0 + DQ_CHUNK < padded_elems ? chunk0 + DQ_CHUNK : padded_elems) - 1) >> 7;
-        const int32_t c_first = granule_cseg[chunk0 >> 7], c_last = granule_cseg[last_granule];
-        again = flags != 0 || count > DQ_BRACKET_CAP;
-        for (int32_t c = c_first; c <= c_last; ++c) again = again || inside[static_cast<int64_t>(w) * n_cseg + c] == 0;
+        again = chunk_needs_redo(count, flags, chunk0, padded_elems, w, n_cseg, granule_cseg, inside);
         if (again) {
             blk->flags = flags | 2u;
         } else {
             uint32_t* plane = reinterpret_cast<uint32_t*>(packed + static_cast<int64_t>(w) * packed_stride +
                                                           (padded_elems >> 3));
-            for (uint32_t k = 0; k < count; ++k) {
-                const uint2 rec = blk->rec[k];
-                const uint32_t e = rec.x; // < 4096 and inside the layout: written by the first kernel for this chunk
-                const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[granule_cseg[(chunk0 >> 7) + (e >> 7)]]];
-                const float scale = N >= DQ_MIN_NORM ? S / N : 0.0f;
-                const uint64_t P = static_cast<uint64_t>(chunk0) + e;
-                uint32_t r[4];
-                dq_philox4x32_10(static_cast<uint32_t>(P >> 2), static_cast<uint32_t>(P >> 34), worker_base + w, step,
-                                 key0, key1, r);
-                const uint32_t word = (P & 2u) ? ((P & 1u) ? r[3] : r[2]) : ((P & 1u) ? r[1] : r[0]);
-                const uint32_t level = level_of<B>(__uint_as_float(rec.y), scale, word);
-                if (level != 0) {
-                    // the field was left zero; fields of other elements in the same words are not touched
-                    const uint64_t bit = P * B;
-                    const uint32_t sh = static_cast<uint32_t>(bit & 31u);
-                    atomicOr(plane + (bit >> 5), level << sh);
-                    if (sh + B > 32) atomicOr(plane + (bit >> 5) + 1, level >> (32 - sh));
-                }
-            }
+            for (uint32_t k = 0; k < count; ++k)
+                settle_record<B>(blk->rec[k], chunk0, w, norms, n_seg, granule_cseg, cseg_seg, key0, key1, step,
+                                 worker_base + w, plane);
         }
     }
     // 64 consecutive chunks per wavefront: one word of the redo map (blockDim is a multiple of 64)
@@ -277,6 +352,9 @@ __global__ __launch_bounds__(256) void k_bracket_settle(
 // grid (ceil(n_words / REDO_WORDS), M): each workgroup walks REDO_WORDS words of the redo map and
 // quantizes the chunks whose bit is set.
 constexpr int REDO_WORDS = 8;
+// up to this many (worker, chunk) pairs the settle kernel runs one wavefront per chunk and the
+// redo kernel one workgroup per chunk
+constexpr int64_t SETTLE_WIDE_MAX = 1 << 18;
 
 template <int B>
 __global__ __launch_bounds__(QP_THREADS) void k_bracket_redo(
@@ -303,6 +381,23 @@ __global__ __launch_bounds__(QP_THREADS) void k_bracket_redo(
             __syncthreads(); // the chunk's staging in LDS is reused by the next one
         }
     }
+}
+
+// grid (n_chunks, M): the same with one workgroup per chunk that looks up its own bit -- for plans of
+// moderate size, where that many workgroups start in a few microseconds and flagged chunks that
+// sit next to each other are then quantized side by side instead of one after the other.
+template <int B>
+__global__ __launch_bounds__(QP_THREADS) void k_bracket_redo_direct(
+    const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
+    const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
+    uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride,
+    const unsigned long long* __restrict__ redo_map, int64_t n_words)
+{
+    const unsigned long long word = redo_map[static_cast<int64_t>(blockIdx.y) * n_words + (blockIdx.x >> 6)];
+    if (((word >> (blockIdx.x & 63)) & 1ull) == 0) return; // uniform: one address for the whole workgroup
+    quantize_pack_chunk<B, 2, 0>(grads, worker_stride, norms, n_seg, granule_cseg, cseg_seg, cseg_valid_end, padded_elems,
+                                 key0, key1, step, worker_base, packed, packed_stride, nullptr, blockIdx.x);
 }
 
 // Statistics of one call, from the blocks: elements settled afterwards and chunks quantized again.
@@ -360,19 +455,35 @@ int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_str
     const dim3 grid(static_cast<unsigned>(L.n_chunks), M), block(QP_THREADS);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
     hipLaunchKernelGGL(k_quantize_pack_bracketed<B>, grid, block, 0, stream, grads, worker_stride, norm_lo, norm_hi,
-                       plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems,
-                       key0, key1, step, worker_base, packed, packed_stride, partials, L.n_slots, blocks, L.n_chunks);
+                       plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_start, plan->d_cseg_valid_end,
+                       plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, partials, L.n_slots,
+                       blocks, L.n_chunks, norms);
     hipLaunchKernelGGL(k_bracket_norm_finish, dim3(plan->n_cseg, M), dim3(256), 0, stream, partials, L.n_slots,
                        plan->d_cseg_start, plan->d_cseg_valid_end, plan->d_cseg_seg, plan->n_seg, plan->n_cseg, norm_lo,
                        norm_hi, norms, inside);
-    hipLaunchKernelGGL(k_bracket_settle<B>, dim3(static_cast<unsigned>((L.n_chunks + 255) / 256), M), dim3(256), 0,
-                       stream, norms, plan->n_seg, plan->n_cseg, plan->d_granule_cseg, plan->d_cseg_seg,
-                       plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, blocks, L.n_chunks,
-                       inside, redo_map, L.n_words);
-    hipLaunchKernelGGL(k_bracket_redo<B>, dim3(static_cast<unsigned>((L.n_words + REDO_WORDS - 1) / REDO_WORDS), M),
-                       block, 0, stream, grads, worker_stride, norms, plan->n_seg, plan->d_granule_cseg,
-                       plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, key0, key1, step, worker_base,
-                       packed, packed_stride, redo_map, L.n_words);
+    if (static_cast<int64_t>(M) * L.n_chunks <= SETTLE_WIDE_MAX) {
+        const int64_t words = static_cast<int64_t>(M) * L.n_words;
+        hipLaunchKernelGGL(k_zero_words, dim3(static_cast<unsigned>((words + 255) / 256)), dim3(256), 0, stream,
+                           redo_map, words);
+        hipLaunchKernelGGL(k_bracket_settle_wide<B>, dim3(static_cast<unsigned>((L.n_chunks + 3) / 4), M), dim3(256), 0,
+                           stream, norms, plan->n_seg, plan->n_cseg, plan->d_granule_cseg, plan->d_cseg_seg,
+                           plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, blocks, L.n_chunks,
+                           inside, redo_map, L.n_words);
+    } else {
+        hipLaunchKernelGGL(k_bracket_settle<B>, dim3(static_cast<unsigned>((L.n_chunks + 255) / 256), M), dim3(256), 0,
+                           stream, norms, plan->n_seg, plan->n_cseg, plan->d_granule_cseg, plan->d_cseg_seg,
+                           plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, blocks, L.n_chunks,
+                           inside, redo_map, L.n_words);
+    }
+    if (static_cast<int64_t>(M) * L.n_chunks <= SETTLE_WIDE_MAX)
+        hipLaunchKernelGGL(k_bracket_redo_direct<B>, grid, block, 0, stream, grads, worker_stride, norms, plan->n_seg,
+                           plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, key0, key1,
+                           step, worker_base, packed, packed_stride, redo_map, L.n_words);
+    else
+        hipLaunchKernelGGL(k_bracket_redo<B>, dim3(static_cast<unsigned>((L.n_words + REDO_WORDS - 1) / REDO_WORDS), M),
+                           block, 0, stream, grads, worker_stride, norms, plan->n_seg, plan->d_granule_cseg,
+                           plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, key0, key1, step, worker_base,
+                           packed, packed_stride, redo_map, L.n_words);
     if (stats) {
         const int64_t n_blocks = static_cast<int64_t>(M) * L.n_chunks;
         const int64_t wgs = (n_blocks + 256 * BS_PER_LANE - 1) / (256 * BS_PER_LANE);

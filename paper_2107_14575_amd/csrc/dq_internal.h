@@ -61,17 +61,17 @@ struct dq_widths {
 //   partial sums of squares, one binary64 slot per (worker, chunk, tensor in the chunk) at index
 //     chunk + c (c = the tensor's compact index: both grow along the layout, so the sum is unique
 //     and a tensor's slots are contiguous);
-//   one 256-byte block per (worker, chunk) with the elements whose level the bracket left open;
+//   one 512-byte block per (worker, chunk) with the elements whose level the bracket left open;
 //   one byte per (worker, non-empty tensor): 1 if the norm came out inside its bracket;
 //   one bit per (worker, chunk), 64 chunks to a word: chunks that have to be quantized again.
-constexpr int DQ_BRACKET_CAP = 31; // records per block
+constexpr int DQ_BRACKET_CAP = 63; // records per block
 struct dq_bracket_block {
     uint32_t count; // open elements found (may exceed DQ_BRACKET_CAP: then the chunk is redone)
     uint32_t flags; // bit 0: a tensor in the chunk had no usable bracket, nothing was quantized;
                     // bit 1: the chunk was quantized again in full
     uint2 rec[DQ_BRACKET_CAP]; // .x = element index inside the chunk, .y = the gradient value's bits
 };
-static_assert(sizeof(dq_bracket_block) == 256, "one block per (worker, chunk), 256 bytes");
+static_assert(sizeof(dq_bracket_block) == 512, "one block per (worker, chunk), 512 bytes");
 
 struct dq_bracket_layout {
     int64_t n_chunks, n_slots, n_words;
@@ -85,7 +85,7 @@ static inline dq_bracket_layout dq_bracket_layout_of(const dq_plan* plan, int M)
     L.n_slots = L.n_chunks + plan->n_cseg;
     L.n_words = (L.n_chunks + 63) / 64;
     L.blocks_at = up(static_cast<int64_t>(M) * L.n_slots * 8);
-    L.inside_at = L.blocks_at + static_cast<int64_t>(M) * L.n_chunks * 256;
+    L.inside_at = L.blocks_at + static_cast<int64_t>(M) * L.n_chunks * static_cast<int64_t>(sizeof(dq_bracket_block));
     L.redo_at = L.inside_at + up(static_cast<int64_t>(M) * plan->n_cseg);
     L.total = L.redo_at + up(static_cast<int64_t>(M) * L.n_words * 8);
     return L;

@@ -90,16 +90,37 @@ def test_wrong_bracket_redoes_every_chunk(dq, oracle, factors):
 
 
 def test_wide_bracket_overflows_some_chunks(dq, oracle):
-    """d = 4096 per tensor: a = s|g|/N is large, a bracket of 1/8..8 leaves most elements undecided,
-    far more than a chunk's 31 records"""
-    seg_len = [4096] * 6
+    """d = 8192 per tensor (two chunks each): a = s|g|/N is large, a bracket of 1/8..8 leaves most
+    elements undecided, far more than a chunk's 63 records"""
+    seg_len = [8192] * 3
     gen = torch.Generator().manual_seed(53)
-    g = torch.randn((3, 6 * 4096), generator=gen)
+    g = torch.randn((3, 3 * 8192), generator=gen)
     settled, redone, total = _run(dq, oracle, seg_len, g, 6, 0.125, 8.0)
     assert redone >= total // 2
     # a mild bracket and few levels on the same data: a handful of undecided elements per chunk
     settled, redone, total = _run(dq, oracle, seg_len, g, 2, 0.99, 1.01)
     assert settled > 0 and redone == 0
+
+
+def test_tensors_inside_one_chunk_need_no_bracket(dq, oracle):
+    """small tensors that do not cross a multiple of 4096: their norms are finished inside the
+    kernel, so even a useless bracket (NaN, or wrong by a factor) neither settles nor redoes anything"""
+    seg_len = [100, 2000, 0, 1000, 700, 50, 4096, 77, 3000]   # padded: 128 + 2048 + 1024 + 768 + 128 | 4096 | 128 + 3072
+    starts, dp = wl.seg_starts(seg_len)
+    gen = torch.Generator().manual_seed(56)
+    g = torch.randn((4, dp), generator=gen) * 1e-2
+    g[2, starts[3]:starts[3] + 1000] = 0.0             # a zero tensor: the zero path, decided on the spot
+    for factors in ((float("nan"), float("nan")), (5.0, 7.0), (0.9, 1.1)):
+        settled, redone, total = _run(dq, oracle, seg_len, g, 5, *factors)
+        assert settled == 0 and redone == 0
+    # mixed with a tensor that does span chunks: only that one depends on its bracket
+    seg_len = [100, 9000, 500]
+    starts, dp = wl.seg_starts(seg_len)
+    g = torch.randn((2, dp), generator=gen) * 1e-2
+    settled, redone, total = _run(dq, oracle, seg_len, g, 3, 0.97, 1.03)
+    assert redone == 0
+    settled, redone, total = _run(dq, oracle, seg_len, g, 3, 2.0, 3.0)
+    assert redone == total                              # every chunk holds a piece of the long tensor
 
 
 def test_unusable_brackets(dq, oracle):
