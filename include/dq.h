@@ -296,7 +296,7 @@ int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, co
  *   norms_dev      [M][n_seg] float, written (within 1 ulp of dq_norm's: same squares, summed chunk-wise)
  *   packed_dev     as dq_quantize_pack
  *   workspace_dev  dq_bracketed_workspace_bytes(plan, M) bytes, 16-byte aligned; contents on entry
- *                  are ignored
+ *                  are ignored; two calls that may run at the same time need a workspace each
  *   stats_dev      NULL, or two int64 (8-byte aligned), written: [0] elements settled by the second
  *                  kernel, [1] chunks quantized again in full
  * Errors as dq_quantize_pack. */
