@@ -241,7 +241,15 @@ def test_config5_other_entry_points_sampled(dq, oracle):
         assert torch.equal(packed_b, packed)
         dq.quantize_pack(plan, g, norms_dev, b, SEED, step, packed)
     assert int(stats[1]) == 0 and 0 < int(stats[0]) < M * D // 1000   # a few settled elements, no chunk redone
-    del packed_b, wsb
+    # a bracket that misses every norm: all 2^20 (worker, chunk) pairs go through the redo map
+    want_bytes = packed_b.clone()
+    packed_b.fill_(0x77)
+    dq.norm_quantize_pack_bracketed(plan, g, norms_dev * 2.0, norms_dev * 3.0, b, SEED, step, norms_b, packed_b,
+                                    wsb, stats=stats)
+    torch.cuda.synchronize()
+    assert torch.equal(packed_b, want_bytes)
+    assert int(stats[0]) == 0 and int(stats[1]) == M * (D // 4096)
+    del packed_b, wsb, want_bytes
 
     # fused update: x - eta*g_hat with one rounding, against torch on the device
     eta = 0.125
