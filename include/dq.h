@@ -301,6 +301,11 @@ int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, co
  *                  kernel, [1] chunks quantized again in full
  * Errors as dq_quantize_pack. */
 int64_t dq_bracketed_workspace_bytes(const dq_plan_t* plan, int M); /* -1 on bad arguments */
+/* The usual bracket: lo = N * (1 - margin), hi = N * (1 + margin) (binary32) for n norms N of an
+ * earlier iteration, 0 <= margin < 1; all three arrays on the device, lo/hi written.  The call runs
+ * on the current device (there is no plan to say which): make the norms' GPU current first. */
+int dq_norm_bracket(const float* norms_dev, int64_t n, float margin, float* norm_lo_dev, float* norm_hi_dev,
+                    void* hip_stream);
 int dq_norm_quantize_pack_bracketed(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
                                     int M, const float* norm_lo_dev, const float* norm_hi_dev, int b,
                                     uint64_t seed, uint32_t step, uint32_t worker_base, float* norms_dev,

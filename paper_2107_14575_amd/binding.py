@@ -26,7 +26,7 @@ EXPORTS = (
     "dq_select_bits_per_tensor", "dq_select_bits_per_worker", "dq_select_bits_device", "dq_widths_create",
     "dq_widths_create_per_worker", "dq_widths_destroy", "dq_widths_set", "dq_widths_packed_bytes",
     "dq_widths_worker_packed_bytes", "dq_quantize_pack_v", "dq_norm_quantize_pack_v", "dq_unpack_dequant_reduce_v",
-    "dq_bracketed_workspace_bytes", "dq_norm_quantize_pack_bracketed",
+    "dq_bracketed_workspace_bytes", "dq_norm_quantize_pack_bracketed", "dq_norm_bracket",
     "dq_unpack_dequant_reduce_update_v",
     # sign-only baseline
     "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority",
@@ -127,6 +127,8 @@ def load_library():
     L.dq_norm_quantize_pack_v.argtypes = [vp, vp, vp, i64, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
                                           vp, vp, i64, vp]
     L.dq_norm_quantize_pack_v.restype = C.c_int
+    L.dq_norm_bracket.argtypes = [vp, i64, C.c_float, vp, vp, vp]
+    L.dq_norm_bracket.restype = C.c_int
     L.dq_bracketed_workspace_bytes.argtypes = [vp, C.c_int]
     L.dq_bracketed_workspace_bytes.restype = i64
     L.dq_norm_quantize_pack_bracketed.argtypes = [vp, vp, i64, C.c_int, vp, vp, C.c_int, C.c_uint64, C.c_uint32,
@@ -268,6 +270,16 @@ def norm_quantize_pack(plan: Plan, grads, b: int, seed: int, step: int, norms_ou
            load_library().dq_norm_quantize_pack(plan.handle, grads.data_ptr(), stride, M, 1 if linf else 0, b, seed,
                                                 step, worker_base, norms_out.data_ptr(), packed_out.data_ptr(),
                                                 int(packed_out.stride(0)), _stream_handle(stream)))
+
+
+def norm_bracket(norms, margin: float, lo_out, hi_out, stream=None) -> None:
+    """lo_out = norms * (1 - margin), hi_out = norms * (1 + margin): CUDA float32 tensors of one shape."""
+    if not (norms.is_contiguous() and lo_out.is_contiguous() and hi_out.is_contiguous()):
+        raise ValueError("contiguous tensors")
+    if lo_out.numel() != norms.numel() or hi_out.numel() != norms.numel():
+        raise ValueError("one bracket per norm")
+    _check("dq_norm_bracket", load_library().dq_norm_bracket(norms.data_ptr(), norms.numel(), margin, lo_out.data_ptr(),
+                                                             hi_out.data_ptr(), _stream_handle(stream)))
 
 
 def bracketed_workspace_bytes(plan: Plan, M: int) -> int:

@@ -496,6 +496,36 @@ int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_str
 
 } // namespace
 
+namespace {
+
+__global__ __launch_bounds__(256) void k_norm_bracket(const float* __restrict__ norms, int64_t n, float below, float above,
+                                                      float* __restrict__ lo, float* __restrict__ hi)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) {
+        const float N = norms[i];
+        lo[i] = N * below;
+        hi[i] = N * above;
+    }
+}
+
+} // namespace
+
+extern "C" int dq_norm_bracket(const float* norms_dev, int64_t n, float margin, float* norm_lo_dev, float* norm_hi_dev,
+                               void* hip_stream)
+{
+    if (!norms_dev || !norm_lo_dev || !norm_hi_dev || n < 0 || n > (INT64_C(1) << 38)) return DQ_ERR_INVALID_ARG;
+    if (!(margin >= 0.0f) || !(margin < 1.0f)) return DQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(norms_dev) & 3u) || (reinterpret_cast<uintptr_t>(norm_lo_dev) & 3u) ||
+        (reinterpret_cast<uintptr_t>(norm_hi_dev) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    if (n == 0) return DQ_OK;
+    hipLaunchKernelGGL(k_norm_bracket, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), norms_dev, n, 1.0f - margin, 1.0f + margin, norm_lo_dev,
+                       norm_hi_dev);
+    return hipGetLastError() == hipSuccess ? DQ_OK : DQ_ERR_HIP;
+}
+
 extern "C" int64_t dq_bracketed_workspace_bytes(const dq_plan_t* plan, int M)
 {
     if (!plan || M < 1 || M > DQ_MAX_WORKERS) return -1;

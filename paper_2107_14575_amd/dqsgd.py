@@ -129,8 +129,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
             pk = packed[:, :plan.packed_bytes(b)]
             _b.norm_quantize_pack(plan, grads, b, seed, t, norms, pk, linf=p != 2)
         elif bracketed and t > 0:
-            torch.mul(prev, 1.0 - norm_margin, out=lo)   # the caller's guess, an input of the library
-            torch.mul(prev, 1.0 + norm_margin, out=hi)
+            _b.norm_bracket(prev, norm_margin, lo, hi)
             b_guess = b
             if not lagged:
                 # Eq. (17) never decreases in any norm, so if both ends of the bracket give the same b,

@@ -175,3 +175,14 @@ def test_argument_checks(dq):
         dq.norm_quantize_pack_bracketed(plan, g, lo, lo, 4, 1, 0, norms, packed, ws[:64])
     assert dq.bracketed_workspace_bytes(plan, 0) == -1
     plan.close()
+
+
+def test_norm_bracket_helper(dq):
+    norms = torch.rand((5, 7), device="cuda") * 3.0
+    lo, hi = torch.empty_like(norms), torch.empty_like(norms)
+    dq.norm_bracket(norms, 0.125, lo, hi)
+    torch.cuda.synchronize()
+    assert torch.equal(lo, norms * 0.875) and torch.equal(hi, norms * 1.125)
+    for bad in (-0.1, 1.0, float("nan")):
+        with pytest.raises(dq.DQError):
+            dq.norm_bracket(norms, bad, lo, hi)
