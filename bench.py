@@ -257,7 +257,8 @@ def main() -> None:
     wsb = torch.empty(dq.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device="cuda")
     br_stats = torch.zeros(2, dtype=torch.int64, device="cuda")
     br_norms = torch.empty_like(norms_dev)
-    br_lo, br_hi = norms_dev * 0.875, norms_dev * 1.125
+    br_lo, br_hi = torch.empty_like(norms_dev), torch.empty_like(norms_dev)
+    dq.norm_bracket(norms_dev, 0.125, br_lo, br_hi)
     t_br = timed_loop(lambda: dq.norm_quantize_pack_bracketed(plan, grads, br_lo, br_hi, b_last, wl.QUANT_SEED, T,
                                                               br_norms, pk_last, wsb, stats=br_stats))
 
