@@ -278,8 +278,9 @@ int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, co
 
 /* One pass over the gradient for ANY plan, given a bracket for every norm and a bit-width that is
  * already known (Algorithm 1: the worker received b_t with x_t; the bracket is, say, the previous
- * iteration's norm give or take a margin).  Computes the l2 norms (Eq. (5), p = 2) and the
- * messages of dq_quantize_pack for exactly those norms.
+ * iteration's norm give or take a margin).  Computes the norms of Eq. (5) -- l2 (linf = 0) or max
+ * (linf != 0), as dq_norm / dq_norm_linf -- and the messages of dq_quantize_pack for exactly those
+ * norms.
  *
  * Why one pass can be exact: for a fixed element and random number the level of Eq. (5)-(6) never
  * grows with the norm (s/N, its product with |g| and floor(a) + [u < a - floor(a)] are all monotone,
@@ -293,7 +294,8 @@ int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, co
  * gradient: the result is the same for any bracket, only the time differs (a wrong bracket
  * costs about the two separate passes).
  *   norm_lo_dev, norm_hi_dev  [M][n_seg] float, read
- *   norms_dev      [M][n_seg] float, written (within 1 ulp of dq_norm's: same squares, summed chunk-wise)
+ *   norms_dev      [M][n_seg] float, written (l2: within 1 ulp of dq_norm's, same squares summed
+ *                  chunk-wise; max: exact)
  *   packed_dev     as dq_quantize_pack
  *   workspace_dev  dq_bracketed_workspace_bytes(plan, M) bytes, 16-byte aligned; contents on entry
  *                  are ignored; two calls that may run at the same time need a workspace each
@@ -307,7 +309,7 @@ int64_t dq_bracketed_workspace_bytes(const dq_plan_t* plan, int M); /* -1 on bad
 int dq_norm_bracket(const float* norms_dev, int64_t n, float margin, float* norm_lo_dev, float* norm_hi_dev,
                     void* hip_stream);
 int dq_norm_quantize_pack_bracketed(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
-                                    int M, const float* norm_lo_dev, const float* norm_hi_dev, int b,
+                                    int M, int linf, const float* norm_lo_dev, const float* norm_hi_dev, int b,
                                     uint64_t seed, uint32_t step, uint32_t worker_base, float* norms_dev,
                                     uint8_t* packed_dev, int64_t packed_worker_stride_bytes, void* workspace_dev,
                                     int64_t* stats_dev, void* hip_stream);

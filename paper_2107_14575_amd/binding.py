@@ -131,7 +131,7 @@ def load_library():
     L.dq_norm_bracket.restype = C.c_int
     L.dq_bracketed_workspace_bytes.argtypes = [vp, C.c_int]
     L.dq_bracketed_workspace_bytes.restype = i64
-    L.dq_norm_quantize_pack_bracketed.argtypes = [vp, vp, i64, C.c_int, vp, vp, C.c_int, C.c_uint64, C.c_uint32,
+    L.dq_norm_quantize_pack_bracketed.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, vp, C.c_int, C.c_uint64, C.c_uint32,
                                                   C.c_uint32, vp, vp, i64, vp, vp, vp]
     L.dq_norm_quantize_pack_bracketed.restype = C.c_int
     L.dq_unpack_dequant_reduce_v.argtypes = [vp, vp, vp, i64, C.c_int, vp, vp, vp]
@@ -287,7 +287,8 @@ def bracketed_workspace_bytes(plan: Plan, M: int) -> int:
 
 
 def norm_quantize_pack_bracketed(plan: Plan, grads, norm_lo, norm_hi, b: int, seed: int, step: int, norms_out,
-                                 packed_out, workspace, worker_base: int = 0, stats=None, stream=None) -> None:
+                                 packed_out, workspace, worker_base: int = 0, stats=None, linf: bool = False,
+                                 stream=None) -> None:
     """One pass over the gradient for any plan, given a bracket [norm_lo, norm_hi] (CUDA float32
     [M][n_seg]) for every norm: norms (written to norms_out) and the messages of quantize_pack for
     them.  workspace: uint8 CUDA tensor of bracketed_workspace_bytes(plan, M); stats: optional CUDA
@@ -297,7 +298,8 @@ def norm_quantize_pack_bracketed(plan: Plan, grads, norm_lo, norm_hi, b: int, se
         raise ValueError("workspace too small: see bracketed_workspace_bytes")
     _check("dq_norm_quantize_pack_bracketed",
            load_library().dq_norm_quantize_pack_bracketed(
-               plan.handle, grads.data_ptr(), stride, M, norm_lo.data_ptr(), norm_hi.data_ptr(), b, seed, step,
+               plan.handle, grads.data_ptr(), stride, M, 1 if linf else 0, norm_lo.data_ptr(), norm_hi.data_ptr(), b,
+               seed, step,
                worker_base, norms_out.data_ptr(), packed_out.data_ptr(), int(packed_out.stride(0)),
                workspace.data_ptr(), stats.data_ptr() if stats is not None else None, _stream_handle(stream)))
 

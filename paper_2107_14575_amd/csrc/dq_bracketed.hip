@@ -40,7 +40,7 @@ __device__ __forceinline__ uint32_t level_of(float v, float scale, uint32_t r)
     return static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
 }
 
-template <int B>
+template <int B, bool LINF> // LINF: the max norm (p = infinity in Eq. (5)) instead of the l2 norm
 __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norm_lo,
     const float* __restrict__ norm_hi, int32_t n_seg, const int32_t* __restrict__ granule_cseg,
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     const int skip = __syncthreads_or(unusable); // also the barrier after the tables
     const bool any_whole = lds_any_whole != 0;
 
-    // partial sums of squares of the chunk's tensors
+    // partial sums of squares (or maxima) of the chunk's tensors
     int valid[TILES], local[TILES];
 #pragma unroll
     for (int it = 0; it < TILES; ++it) {
@@ -117,14 +117,14 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
         local[it] = seg[it] - seg_first;
         valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
     }
-    dq_chunk_granule_sums<false>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+    dq_chunk_granule_sums<LINF>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
     __syncthreads();
     if (tid < DQ_CHUNK_GRANULES)
-        dq_chunk_tensor_totals<false>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+        dq_chunk_tensor_totals<LINF>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
                                       [&](int j, double total) {
                                           partials[static_cast<int64_t>(w) * n_slots + blockIdx.x + seg_first + j] = total;
                                           if (lds_whole[j]) { // the tensor's norm, as the finishing kernel will find it
-                                              const float N = static_cast<float>(sqrt(total));
+                                              const float N = LINF ? static_cast<float>(total) : static_cast<float>(sqrt(total));
                                               norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
                                               const float scale = N >= DQ_MIN_NORM ? S / N : 0.0f;
                                               lds_scale_hi[j] = scale;
@@ -201,9 +201,10 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     }
 }
 
-// grid (n_cseg, M): the norm of tensor c of worker w from its partial sums, slots
+// grid (n_cseg, M): the norm of tensor c of worker w from its partial sums (or maxima), slots
 // [first chunk + c, last chunk + c]: eight lane-strided running sums per lane, combined in a fixed
 // order, then a fixed tree over the lanes.  Also notes whether the norm lies inside its bracket.
+template <bool LINF>
 __global__ __launch_bounds__(256) void k_bracket_norm_finish(
     const double* __restrict__ partials, int64_t n_slots, const int64_t* __restrict__ cseg_start,
     const int64_t* __restrict__ cseg_valid_end, const int32_t* __restrict__ cseg_seg, int32_t n_seg, int32_t n_cseg,
@@ -224,20 +225,22 @@ __global__ __launch_bounds__(256) void k_bracket_norm_finish(
     int64_t i = tid;
     for (; i + 7 * 256 < n; i += 8 * 256) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc[k] += p[i + k * 256];
+        for (int k = 0; k < 8; ++k) acc[k] = dq_chunk_combine<LINF>(acc[k], p[i + k * 256]);
     }
 #pragma unroll
     for (int k = 0; k < 8; ++k) // fewer than eight are left
-        if (i + k * 256 < n) acc[k] += p[i + k * 256];
-    part[tid] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+        if (i + k * 256 < n) acc[k] = dq_chunk_combine<LINF>(acc[k], p[i + k * 256]);
+    part[tid] = dq_chunk_combine<LINF>(
+        dq_chunk_combine<LINF>(dq_chunk_combine<LINF>(acc[0], acc[1]), dq_chunk_combine<LINF>(acc[2], acc[3])),
+        dq_chunk_combine<LINF>(dq_chunk_combine<LINF>(acc[4], acc[5]), dq_chunk_combine<LINF>(acc[6], acc[7])));
     __syncthreads();
     for (int off = 128; off >= 1; off >>= 1) {
-        if (tid < off) part[tid] += part[tid + off];
+        if (tid < off) part[tid] = dq_chunk_combine<LINF>(part[tid], part[tid + off]);
         __syncthreads();
     }
     if (tid == 0) {
         const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[c];
-        const float N = static_cast<float>(sqrt(part[0]));
+        const float N = LINF ? static_cast<float>(part[0]) : static_cast<float>(sqrt(part[0]));
         norms[at] = N;
         // a tensor inside one chunk was quantized with this very norm: no bracket involved
         inside[static_cast<int64_t>(w) * n_cseg + c] = (first == last || (N >= norm_lo[at] && N <= norm_hi[at])) ? 1 : 0;
@@ -439,7 +442,7 @@ __global__ void k_zero_two(unsigned long long* __restrict__ stats)
     stats[threadIdx.x] = 0;
 }
 
-template <int B>
+template <int B, bool LINF>
 int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_stride, int M, const float* norm_lo,
                      const float* norm_hi, uint64_t seed, uint32_t step, uint32_t worker_base, float* norms,
                      uint8_t* packed, int64_t packed_stride, void* workspace, unsigned long long* stats,
@@ -454,11 +457,11 @@ int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_str
     unsigned long long* redo_map = reinterpret_cast<unsigned long long*>(ws + L.redo_at);
     const dim3 grid(static_cast<unsigned>(L.n_chunks), M), block(QP_THREADS);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
-    hipLaunchKernelGGL(k_quantize_pack_bracketed<B>, grid, block, 0, stream, grads, worker_stride, norm_lo, norm_hi,
+    hipLaunchKernelGGL((k_quantize_pack_bracketed<B, LINF>), grid, block, 0, stream, grads, worker_stride, norm_lo, norm_hi,
                        plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_start, plan->d_cseg_valid_end,
                        plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, partials, L.n_slots,
                        blocks, L.n_chunks, norms);
-    hipLaunchKernelGGL(k_bracket_norm_finish, dim3(plan->n_cseg, M), dim3(256), 0, stream, partials, L.n_slots,
+    hipLaunchKernelGGL(k_bracket_norm_finish<LINF>, dim3(plan->n_cseg, M), dim3(256), 0, stream, partials, L.n_slots,
                        plan->d_cseg_start, plan->d_cseg_valid_end, plan->d_cseg_seg, plan->n_seg, plan->n_cseg, norm_lo,
                        norm_hi, norms, inside);
     if (static_cast<int64_t>(M) * L.n_chunks <= SETTLE_WIDE_MAX) {
@@ -533,7 +536,7 @@ extern "C" int64_t dq_bracketed_workspace_bytes(const dq_plan_t* plan, int M)
 }
 
 extern "C" int dq_norm_quantize_pack_bracketed(const dq_plan_t* plan, const float* grads_dev,
-                                               int64_t worker_stride_elems, int M, const float* norm_lo_dev,
+                                               int64_t worker_stride_elems, int M, int linf, const float* norm_lo_dev,
                                                const float* norm_hi_dev, int b, uint64_t seed, uint32_t step,
                                                uint32_t worker_base, float* norms_dev, uint8_t* packed_dev,
                                                int64_t packed_worker_stride_bytes, void* workspace_dev,
@@ -560,9 +563,12 @@ extern "C" int dq_norm_quantize_pack_bracketed(const dq_plan_t* plan, const floa
     unsigned long long* stats = reinterpret_cast<unsigned long long*>(stats_dev);
 #define DQ_BRACKETED(B)                                                                                              \
     case B:                                                                                                          \
-        return launch_bracketed<B>(plan, grads_dev, worker_stride_elems, M, norm_lo_dev, norm_hi_dev, seed, step,   \
-                                   worker_base, norms_dev, packed_dev, packed_worker_stride_bytes, workspace_dev,   \
-                                   stats, stream)
+        return linf ? launch_bracketed<B, true>(plan, grads_dev, worker_stride_elems, M, norm_lo_dev, norm_hi_dev,  \
+                                                seed, step, worker_base, norms_dev, packed_dev,                      \
+                                                packed_worker_stride_bytes, workspace_dev, stats, stream)            \
+                    : launch_bracketed<B, false>(plan, grads_dev, worker_stride_elems, M, norm_lo_dev, norm_hi_dev, \
+                                                 seed, step, worker_base, norms_dev, packed_dev,                     \
+                                                 packed_worker_stride_bytes, workspace_dev, stats, stream)
     switch (b) {
         DQ_BRACKETED(1);
         DQ_BRACKETED(2);

@@ -12,13 +12,13 @@ from tests.test_gpu_parity import SEED, dq, gpu_norm  # noqa: F401  (dq is a fix
 pytestmark = pytest.mark.gpu
 
 
-def _run(dq, oracle, seg_len, grads, b, lo_factor, hi_factor, step=3, worker_base=2, check_norm=True):
+def _run(dq, oracle, seg_len, grads, b, lo_factor, hi_factor, step=3, worker_base=2, check_norm=True, linf=False):
     """-> (exceptions settled, chunks redone, number of (worker, chunk) pairs)"""
     plan = dq.Plan(seg_len)
     M = grads.shape[0]
     g_host = np.ascontiguousarray(grads.numpy())
     g_dev = grads.cuda()
-    ref = gpu_norm(dq, plan, g_dev)
+    ref = gpu_norm(dq, plan, g_dev, linf)
     lo = (ref * lo_factor).contiguous()
     hi = (ref * hi_factor).contiguous()
     norms_dev = torch.full((M, plan.n_seg), float("nan"), dtype=torch.float32, device="cuda")
@@ -27,10 +27,12 @@ def _run(dq, oracle, seg_len, grads, b, lo_factor, hi_factor, step=3, worker_bas
     ws = torch.full((dq.bracketed_workspace_bytes(plan, M),), 0xEE, dtype=torch.uint8, device="cuda")  # stale contents
     stats = torch.full((2,), -7, dtype=torch.int64, device="cuda")
     dq.norm_quantize_pack_bracketed(plan, g_dev, lo, hi, b, SEED, step, norms_dev, packed, ws,
-                                    worker_base=worker_base, stats=stats)
+                                    worker_base=worker_base, stats=stats, linf=linf)
     torch.cuda.synchronize()
     norms = norms_dev.cpu().numpy()
-    if check_norm:
+    if linf:
+        assert np.array_equal(norms.view(np.uint32), oracle.norm_linf(seg_len, g_host).view(np.uint32))
+    elif check_norm:
         want_n = oracle.norm(seg_len, g_host)
         assert np.all(np.abs(norms.astype(np.float64) - want_n.astype(np.float64)) <= np.spacing(want_n))
     want = oracle.quantize_pack(seg_len, g_host, norms, b, SEED, step, worker_base)
@@ -147,6 +149,21 @@ def test_ragged_layout(dq, oracle, M):
     seg_len, g = wl.ragged_mix(M=M)
     for b in (2, 7):
         _run(dq, oracle, seg_len, g, b, 0.8, 1.25, step=b, worker_base=9)
+        _run(dq, oracle, seg_len, g, b, 0.8, 1.25, step=b, worker_base=9, linf=True)
+
+
+@pytest.mark.parametrize("b", [1, 4, 8])
+def test_max_norm(dq, oracle, b):
+    """p = infinity: norms are exact.  With the max norm s|g|/N is of order s/4, so a +-1 % bracket
+    leaves few elements open only for the smallest b; for the others most chunks are done again"""
+    seg_len, g = _flat((1 << 18) + 500, 3, 80 + b)
+    settled, redone, total = _run(dq, oracle, seg_len, g, b, 0.99, 1.01, linf=True)
+    if b == 1:
+        assert redone <= total // 10 and settled > 0
+    settled, redone, total = _run(dq, oracle, seg_len, g, b, 1.0, 1.0, linf=True)   # maxima are exact: lo = hi = N works
+    assert settled == 0 and redone == 0
+    settled, redone, total = _run(dq, oracle, seg_len, g, b, 3.0, 4.0, linf=True)
+    assert redone == total
 
 
 def test_heavy_tails_and_sparse_rows(dq, oracle):

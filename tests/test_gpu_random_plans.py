@@ -166,24 +166,26 @@ def test_random_layout(dq, oracle, case):
         assert torch.equal(n2.view(torch.int32), norms_dev.view(torch.int32))
         assert torch.equal(pk2, packed)
 
-    # ---- norms and messages in one pass given a bracket for every norm (p = 2 only): any bracket
-    # must give the messages of the two-pass route for the norms the call computes
-    if not linf:
-        margin = float(rng.choice([0.0, 1e-3, 0.05, 0.5]))
-        lo_dev, hi_dev = norms_dev * (1.0 - margin), norms_dev * (1.0 + margin)
-        if case % 5 == 0:
-            lo_dev, hi_dev = norms_dev * 2.0, norms_dev * 3.0        # wrong: every chunk is done again
-        n3 = torch.full((M, n_seg), float("nan"), dtype=torch.float32, device="cuda")
-        pk3 = torch.full_like(packed, 0xA5)
-        wsb = torch.full((dq.bracketed_workspace_bytes(plan, M),), 0x5A, dtype=torch.uint8, device="cuda")
-        dq.norm_quantize_pack_bracketed(plan, g_dev, lo_dev, hi_dev, b, seed, step, n3, pk3, wsb,
-                                        worker_base=worker_base)
-        torch.cuda.synchronize()
-        n3_host = n3.cpu().numpy()
+    # ---- norms and messages in one pass given a bracket for every norm: any bracket must give the
+    # messages of the two-pass route for the norms the call computes
+    margin = float(rng.choice([0.0, 1e-3, 0.05, 0.5]))
+    lo_dev, hi_dev = norms_dev * (1.0 - margin), norms_dev * (1.0 + margin)
+    if case % 5 == 0:
+        lo_dev, hi_dev = norms_dev * 2.0, norms_dev * 3.0        # wrong: every chunk with a long tensor is done again
+    n3 = torch.full((M, n_seg), float("nan"), dtype=torch.float32, device="cuda")
+    pk3 = torch.full_like(packed, 0xA5)
+    wsb = torch.full((dq.bracketed_workspace_bytes(plan, M),), 0x5A, dtype=torch.uint8, device="cuda")
+    dq.norm_quantize_pack_bracketed(plan, g_dev, lo_dev, hi_dev, b, seed, step, n3, pk3, wsb,
+                                    worker_base=worker_base, linf=linf)
+    torch.cuda.synchronize()
+    n3_host = n3.cpu().numpy()
+    if linf:
+        assert np.array_equal(n3_host.view(np.uint32), norms.view(np.uint32))
+    else:
         assert np.all(np.abs(n3_host.astype(np.float64) - want_n.astype(np.float64)) <= np.spacing(want_n))
-        got3 = pk3.cpu().numpy()
-        assert np.array_equal(got3[:, :nbytes], oracle.quantize_pack(seg_len, g_host, n3_host, b, seed, step, worker_base))
-        assert np.all(got3[:, nbytes:] == 0xA5)
+    got3 = pk3.cpu().numpy()
+    assert np.array_equal(got3[:, :nbytes], oracle.quantize_pack(seg_len, g_host, n3_host, b, seed, step, worker_base))
+    assert np.all(got3[:, nbytes:] == 0xA5)
 
     # ---- one width per tensor
     b_seg = rng.integers(1, 9, size=n_seg).astype(np.int32)
