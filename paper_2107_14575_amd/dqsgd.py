@@ -20,7 +20,7 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
     (``plan.chunk_local``: no tensor crosses a multiple of 4096 padded elements, e.g. a gradient
     cut into buckets) the worker side is the single pass ``dq_norm_quantize_pack``; one_pass=False
     keeps the two calls.
-  * norm_margin=m (p = 2, base mode): from the second iteration on the worker side is the single
+  * norm_margin=m (base mode): from the second iteration on the worker side is the single
     pass ``dq_norm_quantize_pack_bracketed`` on any layout, every norm bracketed by the previous
     iteration's norm times (1 -+ m); the messages are the same as with the two calls whatever m
     is, a bracket that misses only costs time.  With lagged=False the pass is taken when both ends
@@ -116,7 +116,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
     b = int(b0)
 
     single_pass = one_pass and lagged and plan.chunk_local
-    bracketed = norm_margin is not None and p == 2 and not single_pass
+    bracketed = norm_margin is not None and not single_pass
     if bracketed:
         if not 0.0 <= norm_margin < 1.0:
             raise ValueError("norm_margin must be in [0, 1)")
@@ -142,7 +142,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
                 norm_fn(plan, grads, norms, ws)
             else:
                 pk = packed[:, :plan.packed_bytes(b_guess)]
-                _b.norm_quantize_pack_bracketed(plan, grads, lo, hi, b_guess, seed, t, norms, pk, wsb)
+                _b.norm_quantize_pack_bracketed(plan, grads, lo, hi, b_guess, seed, t, norms, pk, wsb, linf=p != 2)
         else:
             norm_fn(plan, grads, norms, ws)
         if bracketed:
