@@ -291,8 +291,8 @@ int dq_norm_quantize_pack_v(const dq_plan_t* plan, const dq_widths_t* widths, co
  * 4096-element chunk needs no bracket (its norm is finished on the spot).  A chunk with
  * more than 63 undecided elements, a tensor whose bracket is unusable (not lo >= DQ_MIN_NORM,
  * lo <= hi, hi finite) or whose norm falls outside its bracket is quantized again from the
- * gradient: the result is the same for any bracket, only the time differs (a wrong bracket
- * costs about the two separate passes).
+ * gradient: the result is the same for any bracket, only the time differs (a bracket that misses
+ * every norm costs about a third more than the two separate calls).
  *   norm_lo_dev, norm_hi_dev  [M][n_seg] float, read
  *   norms_dev      [M][n_seg] float, written (l2: within 1 ulp of dq_norm's, same squares summed
  *                  chunk-wise; max: exact)
