@@ -87,3 +87,46 @@ def test_other_entry_points_follow_the_stream_argument(dq):
         assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
     s["table"].close()
     plan.close()
+
+
+def test_bracketed_passes_on_two_streams_with_a_workspace_each(dq):
+    """two single-pass calls in flight at once, each with its own workspace, bracket and statistics"""
+    cases = [_make(dq, [3 * 4096 + 700, 100, 9000], 3, 153), _make(dq, [20000, 512, 512], 5, 154)]
+    for s in cases:
+        dq.norm(s["plan"], s["g"], s["norms"], s["ws"])
+        s["lo"], s["hi"] = torch.empty_like(s["norms"]), torch.empty_like(s["norms"])
+        s["wsb"] = torch.empty(dq.bracketed_workspace_bytes(s["plan"], s["M"]), dtype=torch.uint8, device="cuda")
+        s["stats"] = torch.zeros(2, dtype=torch.int64, device="cuda")
+        s["n2"] = torch.zeros_like(s["norms"])
+        s["pk"] = s["packed"][:, :s["plan"].packed_bytes(3)]
+    torch.cuda.synchronize()
+
+    def call(s, t, stream):
+        dq.norm_bracket(s["norms"], 0.05, s["lo"], s["hi"], stream=stream)
+        dq.norm_quantize_pack_bracketed(s["plan"], s["g"], s["lo"], s["hi"], 3, SEED, t, s["n2"], s["pk"], s["wsb"],
+                                        stats=s["stats"], stream=stream)
+        dq.unpack_dequant_reduce_update(s["plan"], s["pk"], s["n2"], 3, 0.1, s["x"], stream=stream)
+
+    for t in range(3):
+        for s in cases:
+            call(s, t, None)
+    torch.cuda.synchronize()
+    want = [(s["x"].clone(), s["pk"].clone(), s["stats"].clone()) for s in cases]
+    for s in cases:
+        s["x"].zero_()
+        s["packed"].zero_()
+        s["stats"].zero_()
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for t in range(3):
+        for s, st in zip(cases, streams):
+            call(s, t, st)
+    for st in streams:
+        st.synchronize()
+    for s, (x, pk, stats) in zip(cases, want):
+        assert torch.equal(s["x"].view(torch.int32), x.view(torch.int32))
+        assert torch.equal(s["pk"], pk) and torch.equal(s["stats"], stats)
+        assert int(stats[0]) > 0
+    for s in cases:
+        s["table"].close()
+        s["plan"].close()
