@@ -15,8 +15,8 @@
 //       of the bracket (the largest levels), looks at the non-zero levels again with the high end,
 //       writes the levels that agree, leaves the others' fields zero and records those elements
 //       (index and value) in the chunk's block of the workspace.
-//   k_bracket_norm_finish      adds a tensor's partial sums in a fixed order: the norms, and
-//       whether each came out inside its bracket.
+//   k_bracket_norm_finish      for the tensors that cross a chunk boundary: adds the partial sums in
+//       a fixed order: the norms, and whether each came out inside its bracket.
 //   k_bracket_settle[_wide]    one lane per chunk (large plans) or one wavefront per chunk with a
 //       lane per record (up to 2^18 chunks): quantizes the chunk's recorded elements with the
 //       true norm and ORs their levels into the zero fields; a chunk with too many records, with
@@ -47,7 +47,8 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     const int32_t* __restrict__ cseg_seg, const int64_t* __restrict__ cseg_start,
     const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
     uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride, double* __restrict__ partials,
-    int64_t n_slots, dq_bracket_block* __restrict__ blocks, int64_t n_chunks, float* __restrict__ norms_out)
+    int64_t n_slots, dq_bracket_block* __restrict__ blocks, int64_t n_chunks, float* __restrict__ norms_out,
+    uint8_t* __restrict__ inside, int32_t n_cseg)
 {
     constexpr int TILES = 2;
     constexpr int CHUNK = DQ_CHUNK;
@@ -123,9 +124,10 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
         dq_chunk_tensor_totals<LINF>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
                                       [&](int j, double total) {
                                           partials[static_cast<int64_t>(w) * n_slots + blockIdx.x + seg_first + j] = total;
-                                          if (lds_whole[j]) { // the tensor's norm, as the finishing kernel will find it
+                                          if (lds_whole[j]) { // all of the tensor is here: this is its norm, no bracket involved
                                               const float N = LINF ? static_cast<float>(total) : static_cast<float>(sqrt(total));
                                               norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
+                                              inside[static_cast<int64_t>(w) * n_cseg + seg_first + j] = 1;
                                               const float scale = N >= DQ_MIN_NORM ? S / N : 0.0f;
                                               lds_scale_hi[j] = scale;
                                               lds_scale_lo[j] = scale;
@@ -201,19 +203,20 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     }
 }
 
-// grid (n_cseg, M): the norm of tensor c of worker w from its partial sums (or maxima), slots
+// grid (n_span, M), the tensors that cross a chunk boundary (the others are finished by the first
+// kernel): the norm of tensor c of worker w from its partial sums (or maxima), slots
 // [first chunk + c, last chunk + c]: eight lane-strided running sums per lane, combined in a fixed
 // order, then a fixed tree over the lanes.  Also notes whether the norm lies inside its bracket.
 template <bool LINF>
 __global__ __launch_bounds__(256) void k_bracket_norm_finish(
     const double* __restrict__ partials, int64_t n_slots, const int64_t* __restrict__ cseg_start,
-    const int64_t* __restrict__ cseg_valid_end, const int32_t* __restrict__ cseg_seg, int32_t n_seg, int32_t n_cseg,
-    const float* __restrict__ norm_lo, const float* __restrict__ norm_hi, float* __restrict__ norms,
-    uint8_t* __restrict__ inside)
+    const int64_t* __restrict__ cseg_valid_end, const int32_t* __restrict__ cseg_seg, const int32_t* __restrict__ span_cseg,
+    int32_t n_seg, int32_t n_cseg, const float* __restrict__ norm_lo, const float* __restrict__ norm_hi,
+    float* __restrict__ norms, uint8_t* __restrict__ inside)
 {
     __shared__ double part[256];
     const int tid = threadIdx.x;
-    const int32_t c = blockIdx.x;
+    const int32_t c = span_cseg[blockIdx.x];
     const int w = blockIdx.y;
     const int64_t first = cseg_start[c] / DQ_CHUNK;
     const int64_t last = (cseg_valid_end[c] - 1) / DQ_CHUNK;
@@ -242,8 +245,7 @@ __global__ __launch_bounds__(256) void k_bracket_norm_finish(
         const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[c];
         const float N = LINF ? static_cast<float>(part[0]) : static_cast<float>(sqrt(part[0]));
         norms[at] = N;
-        // a tensor inside one chunk was quantized with this very norm: no bracket involved
-        inside[static_cast<int64_t>(w) * n_cseg + c] = (first == last || (N >= norm_lo[at] && N <= norm_hi[at])) ? 1 : 0;
+        inside[static_cast<int64_t>(w) * n_cseg + c] = (N >= norm_lo[at] && N <= norm_hi[at]) ? 1 : 0;
     }
 }
 
@@ -460,10 +462,11 @@ int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_str
     hipLaunchKernelGGL((k_quantize_pack_bracketed<B, LINF>), grid, block, 0, stream, grads, worker_stride, norm_lo, norm_hi,
                        plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_start, plan->d_cseg_valid_end,
                        plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, partials, L.n_slots,
-                       blocks, L.n_chunks, norms);
-    hipLaunchKernelGGL(k_bracket_norm_finish<LINF>, dim3(plan->n_cseg, M), dim3(256), 0, stream, partials, L.n_slots,
-                       plan->d_cseg_start, plan->d_cseg_valid_end, plan->d_cseg_seg, plan->n_seg, plan->n_cseg, norm_lo,
-                       norm_hi, norms, inside);
+                       blocks, L.n_chunks, norms, inside, plan->n_cseg);
+    if (plan->n_span > 0)
+        hipLaunchKernelGGL(k_bracket_norm_finish<LINF>, dim3(plan->n_span, M), dim3(256), 0, stream, partials, L.n_slots,
+                           plan->d_cseg_start, plan->d_cseg_valid_end, plan->d_cseg_seg, plan->d_span_cseg, plan->n_seg,
+                           plan->n_cseg, norm_lo, norm_hi, norms, inside);
     if (static_cast<int64_t>(M) * L.n_chunks <= SETTLE_WIDE_MAX) {
         const int64_t words = static_cast<int64_t>(M) * L.n_words;
         hipLaunchKernelGGL(k_zero_words, dim3(static_cast<unsigned>((words + 255) / 256)), dim3(256), 0, stream,

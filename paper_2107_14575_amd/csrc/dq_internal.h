@@ -30,6 +30,8 @@ struct dq_plan {
     int32_t* d_cseg_seg;           // [n_nonempty] segment l of compact index c
     int64_t* d_cseg_valid_end;     // [n_nonempty] P_l + len_l: first padded index past the data
     int64_t* d_cseg_start;         // [n_nonempty] P_l
+    int32_t* d_span_cseg;          // [n_span] compact indices of the tensors that cross a multiple of 4096
+    int32_t n_span;                //          padded elements (all others lie inside one chunk)
     dq_norm_item* d_items;         // [n_items]
     int32_t* d_seg_item_begin;     // [n_seg + 1] items of segment l are [begin[l], begin[l+1])
     int32_t* d_finish_seg;         // [n_finish] segments whose norm needs the finishing kernel: all but

@@ -30,6 +30,7 @@ void free_device_tables(dq_plan* p)
     if (p->d_cseg_seg) (void)hipFree(p->d_cseg_seg);
     if (p->d_cseg_valid_end) (void)hipFree(p->d_cseg_valid_end);
     if (p->d_cseg_start) (void)hipFree(p->d_cseg_start);
+    if (p->d_span_cseg) (void)hipFree(p->d_span_cseg);
     if (p->d_items) (void)hipFree(p->d_items);
     if (p->d_seg_item_begin) (void)hipFree(p->d_seg_item_begin);
     if (p->d_finish_seg) (void)hipFree(p->d_finish_seg);
@@ -38,6 +39,7 @@ void free_device_tables(dq_plan* p)
     p->d_cseg_seg = nullptr;
     p->d_cseg_valid_end = nullptr;
     p->d_cseg_start = nullptr;
+    p->d_span_cseg = nullptr;
     p->d_items = nullptr;
     p->d_seg_item_begin = nullptr;
 }
@@ -97,6 +99,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
 
     std::vector<int64_t> cseg_valid_end;
     std::vector<int64_t> cseg_start;
+    std::vector<int32_t> span_cseg;
     std::vector<int32_t> cseg_seg;
     std::vector<int32_t> granule_cseg(static_cast<size_t>(total / DQ_GRANULE));
     std::vector<dq_norm_item> items;
@@ -110,6 +113,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
                 cseg_seg.push_back(l);
                 cseg_valid_end.push_back(p->seg_start[l] + p->seg_len[l]);
                 cseg_start.push_back(p->seg_start[l]);
+                if (p->seg_start[l] / 4096 != (p->seg_start[l] + p->seg_len[l] - 1) / 4096) span_cseg.push_back(c);
                 for (int64_t g = p->seg_start[l] / DQ_GRANULE; g < p->seg_start[l + 1] / DQ_GRANULE; ++g)
                     granule_cseg[static_cast<size_t>(g)] = c;
             }
@@ -132,7 +136,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
     }
 
     const bool ok = upload(&p->d_granule_cseg, granule_cseg) && upload(&p->d_cseg_seg, cseg_seg) &&
-                    upload(&p->d_cseg_valid_end, cseg_valid_end) && upload(&p->d_cseg_start, cseg_start) &&
+                    upload(&p->d_cseg_valid_end, cseg_valid_end) && upload(&p->d_cseg_start, cseg_start) && upload(&p->d_span_cseg, span_cseg) &&
                     upload(&p->d_items, items) && upload(&p->d_seg_item_begin, item_begin) &&
                     upload(&p->d_finish_seg, finish_seg);
     if (!ok) {
@@ -144,6 +148,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
     p->device = dev;
     p->n_cseg = static_cast<int32_t>(cseg_seg.size());
     p->n_finish = static_cast<int32_t>(finish_seg.size());
+    p->n_span = static_cast<int32_t>(span_cseg.size());
     *plan_out = p;
     return DQ_OK;
 }
