@@ -314,6 +314,17 @@ int dq_norm_quantize_pack_bracketed(const dq_plan_t* plan, const float* grads_de
                                     uint8_t* packed_dev, int64_t packed_worker_stride_bytes, void* workspace_dev,
                                     int64_t* stats_dev, void* hip_stream);
 
+/* The same single pass with the widths of `widths` (one per tensor, shared by the workers or one
+ * row per worker): the messages of dq_quantize_pack_v for the norms the call computes.  The table
+ * may have been filled on the GPU (dq_select_bits_device), so a whole iteration -- this call, the
+ * rule for the next iteration, dq_unpack_dequant_reduce_update_v -- needs no host round trip.
+ * packed_worker_stride_bytes >= dq_widths_packed_bytes(widths); everything else as above. */
+int dq_norm_quantize_pack_bracketed_v(const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
+                                      int64_t worker_stride_elems, int M, int linf, const float* norm_lo_dev,
+                                      const float* norm_hi_dev, uint64_t seed, uint32_t step, uint32_t worker_base,
+                                      float* norms_dev, uint8_t* packed_dev, int64_t packed_worker_stride_bytes,
+                                      void* workspace_dev, int64_t* stats_dev, void* hip_stream);
+
 /* Eq. (24), the practical estimate of the convergence factor: alpha_est = (F(x_t)/F(x_0))^(1/t).
  * Host code.  Returns -1 unless t >= 1, F_t > 0 and F_0 > 0. */
 double dq_alpha_est(double F_t, double F_0, int64_t t);

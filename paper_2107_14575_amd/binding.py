@@ -26,7 +26,8 @@ EXPORTS = (
     "dq_select_bits_per_tensor", "dq_select_bits_per_worker", "dq_select_bits_device", "dq_widths_create",
     "dq_widths_create_per_worker", "dq_widths_destroy", "dq_widths_set", "dq_widths_packed_bytes",
     "dq_widths_worker_packed_bytes", "dq_quantize_pack_v", "dq_norm_quantize_pack_v", "dq_unpack_dequant_reduce_v",
-    "dq_bracketed_workspace_bytes", "dq_norm_quantize_pack_bracketed", "dq_norm_bracket",
+    "dq_bracketed_workspace_bytes", "dq_norm_quantize_pack_bracketed", "dq_norm_quantize_pack_bracketed_v",
+    "dq_norm_bracket",
     "dq_unpack_dequant_reduce_update_v",
     # sign-only baseline
     "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority",
@@ -127,6 +128,9 @@ def load_library():
     L.dq_norm_quantize_pack_v.argtypes = [vp, vp, vp, i64, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
                                           vp, vp, i64, vp]
     L.dq_norm_quantize_pack_v.restype = C.c_int
+    L.dq_norm_quantize_pack_bracketed_v.argtypes = [vp, vp, vp, i64, C.c_int, C.c_int, vp, vp, C.c_uint64, C.c_uint32,
+                                                    C.c_uint32, vp, vp, i64, vp, vp, vp]
+    L.dq_norm_quantize_pack_bracketed_v.restype = C.c_int
     L.dq_norm_bracket.argtypes = [vp, i64, C.c_float, vp, vp, vp]
     L.dq_norm_bracket.restype = C.c_int
     L.dq_bracketed_workspace_bytes.argtypes = [vp, C.c_int]
@@ -472,6 +476,21 @@ def select_bits_device(plan: Plan, widths: Widths, norms, t: int, T: int, eps_ha
            load_library().dq_select_bits_device(plan.handle, widths.handle, norms.data_ptr(), int(norms.shape[0]),
                                                 t, T, eps_hat_q, alpha, b_min, b_max, RULES[rule], ptr(b_out),
                                                 ptr(gbar_out), ptr(packed_bytes_out), _stream_handle(stream)))
+
+
+def norm_quantize_pack_bracketed_v(plan: Plan, widths: Widths, grads, norm_lo, norm_hi, seed: int, step: int, norms_out,
+                                   packed_out, workspace, worker_base: int = 0, stats=None, linf: bool = False,
+                                   stream=None) -> None:
+    """norm_quantize_pack_bracketed with the widths of `widths` (per tensor, shared or one row per worker)."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    if workspace.numel() * workspace.element_size() < bracketed_workspace_bytes(plan, M):
+        raise ValueError("workspace too small: see bracketed_workspace_bytes")
+    _check("dq_norm_quantize_pack_bracketed_v",
+           load_library().dq_norm_quantize_pack_bracketed_v(
+               plan.handle, widths.handle, grads.data_ptr(), stride, M, 1 if linf else 0, norm_lo.data_ptr(),
+               norm_hi.data_ptr(), seed, step, worker_base, norms_out.data_ptr(), packed_out.data_ptr(),
+               int(packed_out.stride(0)), workspace.data_ptr(), stats.data_ptr() if stats is not None else None,
+               _stream_handle(stream)))
 
 
 def quantize_pack_v(plan: Plan, widths: Widths, grads, norms, seed: int, step: int, packed_out,

@@ -40,6 +40,15 @@ __device__ __forceinline__ uint32_t level_of(float v, float scale, uint32_t r)
     return static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
 }
 
+// The same with the level count as a value (per-tensor widths).
+__device__ __forceinline__ uint32_t level_of_s(float v, float scale, float S, uint32_t r)
+{
+    const float a = fminf(fabsf(v) * scale, S);
+    const float p = __builtin_amdgcn_fractf(a);
+    const float u = static_cast<float>(r >> 8) * 0x1p-24f;
+    return static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
+}
+
 template <int B, bool LINF> // LINF: the max norm (p = infinity in Eq. (5)) instead of the l2 norm
 __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norm_lo,
@@ -203,6 +212,194 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     }
 }
 
+// The first kernel with per-tensor widths (dq_widths_t: one row shared by the workers or one row per
+// worker): b, the level count and the place of the level bytes of every tensor the chunk touches
+// come from the widths table, as in quantize_pack_chunk_v; everything else as above.
+template <bool LINF>
+__global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed_v(
+    const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norm_lo,
+    const float* __restrict__ norm_hi, int32_t n_seg, const int32_t* __restrict__ granule_cseg,
+    const int32_t* __restrict__ cseg_seg, const int64_t* __restrict__ cseg_start,
+    const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths_table,
+    int32_t widths_worker_stride, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
+    uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride, double* __restrict__ partials,
+    int64_t n_slots, dq_bracket_block* __restrict__ blocks, int64_t n_chunks, float* __restrict__ norms_out,
+    uint8_t* __restrict__ inside, int32_t n_cseg)
+{
+    constexpr int TILES = 2;
+    constexpr int CHUNK = DQ_CHUNK;
+    const dq_cseg_width* __restrict__ widths = widths_table + static_cast<int64_t>(blockIdx.y) * widths_worker_stride;
+
+    __shared__ float lds_scale_hi[DQ_CHUNK_GRANULES];
+    __shared__ float lds_scale_lo[DQ_CHUNK_GRANULES];
+    __shared__ float lds_levels[DQ_CHUNK_GRANULES]; // s = 2^b - 1 of the tensor
+    __shared__ int32_t lds_b[DQ_CHUNK_GRANULES];
+    __shared__ int32_t lds_level_base[DQ_CHUNK_GRANULES];
+    __shared__ int32_t lds_valid_end[DQ_CHUNK_GRANULES];
+    __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
+    __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
+    __shared__ uint32_t lds_count;
+    __shared__ int32_t lds_whole[DQ_CHUNK_GRANULES];
+    __shared__ int32_t lds_any_whole;
+    __shared__ __align__(16) uint8_t lds_sign[TILES * QP_THREADS];
+    __shared__ __align__(16) uint8_t lds_level[TILES * QP_THREADS * 8];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t w = blockIdx.y;
+    const int64_t chunk0 = static_cast<int64_t>(blockIdx.x) * CHUNK;
+    const uint32_t n_elems = static_cast<uint32_t>(padded_elems - chunk0 < CHUNK ? padded_elems - chunk0 : CHUNK);
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride + chunk0;
+    const int32_t* gseg = granule_cseg + (chunk0 >> 7);
+    dq_bracket_block* blk = blocks + static_cast<int64_t>(w) * n_chunks + blockIdx.x;
+
+    float4 x[TILES][2];
+    int32_t seg[TILES];
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        e = e < n_elems ? e : n_elems - QP_PER_LANE;
+        x[it][0] = *reinterpret_cast<const float4*>(g + e);
+        x[it][1] = *reinterpret_cast<const float4*>(g + e + 4);
+        seg[it] = gseg[e >> 7];
+    }
+
+    const int32_t seg_first = gseg[0];
+    const int32_t seg_last = gseg[(n_elems - 1) >> 7];
+    const dq_cseg_width first = widths[seg_first];
+    const int64_t chunk_level0 = first.level_start + ((chunk0 - first.seg_start) >> 3) * first.b;
+    if (tid == 0) {
+        lds_count = 0;
+        lds_any_whole = 0;
+    }
+    int unusable = 0;
+    if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
+        const dq_cseg_width e = widths[seg_first + tid];
+        const float S = static_cast<float>((1 << e.b) - 1);
+        const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid];
+        const int64_t valid_end = cseg_valid_end[seg_first + tid];
+        const bool whole = cseg_start[seg_first + tid] >= chunk0 && valid_end <= chunk0 + CHUNK;
+        const float lo = norm_lo[at], hi = norm_hi[at];
+        const bool ok = lo >= DQ_MIN_NORM && hi >= lo && hi <= 3.0e38f;
+        lds_scale_hi[tid] = ok ? S / lo : 0.0f;
+        lds_scale_lo[tid] = ok ? S / hi : 0.0f;
+        lds_levels[tid] = S;
+        lds_b[tid] = e.b;
+        lds_level_base[tid] = static_cast<int32_t>(e.level_start + ((chunk0 - e.seg_start) >> 3) * e.b - chunk_level0);
+        lds_whole[tid] = whole ? 1 : 0;
+        if (whole) lds_any_whole = 1;
+        unusable = (ok || whole) ? 0 : 1;
+        const int64_t rel = valid_end - chunk0;
+        lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+    }
+    const int skip = __syncthreads_or(unusable);
+    const bool any_whole = lds_any_whole != 0;
+
+    int valid[TILES], local[TILES];
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        local[it] = seg[it] - seg_first;
+        valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
+    }
+    dq_chunk_granule_sums<LINF>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+    __syncthreads();
+    if (tid < DQ_CHUNK_GRANULES)
+        dq_chunk_tensor_totals<LINF>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+                                     [&](int j, double total) {
+                                         partials[static_cast<int64_t>(w) * n_slots + blockIdx.x + seg_first + j] = total;
+                                         if (lds_whole[j]) {
+                                             const float N = LINF ? static_cast<float>(total) : static_cast<float>(sqrt(total));
+                                             norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
+                                             inside[static_cast<int64_t>(w) * n_cseg + seg_first + j] = 1;
+                                             const float scale = N >= DQ_MIN_NORM ? lds_levels[j] / N : 0.0f;
+                                             lds_scale_hi[j] = scale;
+                                             lds_scale_lo[j] = scale;
+                                         }
+                                     });
+    if (any_whole) __syncthreads();
+    if (skip) {
+        if (tid == 0) {
+            blk->count = 0;
+            blk->flags = 1;
+        }
+        return;
+    }
+
+    const uint32_t quad_lo0 = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 2);
+    const uint32_t quad_hi = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 34);
+    const uint32_t worker = worker_base + w;
+
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        if (e < n_elems) {
+            const float S = lds_levels[local[it]];
+            const int b = lds_b[local[it]];
+            const uint64_t field = (static_cast<uint64_t>(1) << b) - 1u;
+            const uint32_t quad = quad_lo0 + (e >> 2);
+            uint32_t r0[4], r1[4];
+            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
+            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
+
+            uint32_t sign = 0, lv_lo, lv_hi;
+            quantize4_v(x[it][1], lds_scale_hi[local[it]], S, b, r1, sign, lv_hi);
+            quantize4_v(x[it][0], lds_scale_hi[local[it]], S, b, r0, sign, lv_lo);
+            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * b));
+            const int nv = valid[it] >= QP_PER_LANE ? QP_PER_LANE : (valid[it] > 0 ? valid[it] : 0);
+            if (nv < QP_PER_LANE) {
+                sign &= (1u << nv) - 1u;
+                level &= (static_cast<uint64_t>(1) << (nv * b)) - 1u;
+            }
+            if (level != 0) {
+                const float scale_lo = lds_scale_lo[local[it]];
+                const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
+                                     x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
+                const uint32_t r[8] = { r0[0], r0[1], r0[2], r0[3], r1[0], r1[1], r1[2], r1[3] };
+#pragma unroll
+                for (int k = 0; k < QP_PER_LANE; ++k) {
+                    const uint32_t top = static_cast<uint32_t>(level >> (k * b)) & static_cast<uint32_t>(field);
+                    if (top != 0 && level_of_s(v[k], scale_lo, S, r[k]) != top) {
+                        const uint32_t slot = atomicAdd(&lds_count, 1u);
+                        if (slot < DQ_BRACKET_CAP) blk->rec[slot] = make_uint2(e + k, __float_as_uint(v[k]));
+                        level &= ~(field << (k * b));
+                    }
+                }
+            }
+            lds_sign[it * QP_THREADS + tid] = static_cast<uint8_t>(sign);
+            uint8_t* dst = &lds_level[lds_level_base[local[it]] + static_cast<int32_t>(e >> 3) * b];
+            switch (b) {
+            case 1: stage_bytes<1>(dst, level); break;
+            case 2: stage_bytes<2>(dst, level); break;
+            case 3: stage_bytes<3>(dst, level); break;
+            case 4: stage_bytes<4>(dst, level); break;
+            case 5: stage_bytes<5>(dst, level); break;
+            case 6: stage_bytes<6>(dst, level); break;
+            case 7: stage_bytes<7>(dst, level); break;
+            default: stage_bytes<8>(dst, level); break;
+            }
+        }
+    }
+    __syncthreads();
+
+    uint8_t* msg = packed + static_cast<int64_t>(w) * packed_stride;
+    {
+        uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
+        const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+    }
+    {
+        const int last = seg_last - seg_first;
+        const uint32_t level_bytes = static_cast<uint32_t>(lds_level_base[last]) + (n_elems >> 3) * lds_b[last];
+        uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + chunk_level0);
+        const uint4* src = reinterpret_cast<const uint4*>(lds_level);
+        for (uint32_t i = tid; i < level_bytes / 16; i += QP_THREADS) dst[i] = src[i];
+    }
+    if (tid == 0) {
+        blk->count = lds_count;
+        blk->flags = 0;
+    }
+}
+
 // grid (n_span, M), the tensors that cross a chunk boundary (the others are finished by the first
 // kernel): the norm of tensor c of worker w from its partial sums (or maxima), slots
 // [first chunk + c, last chunk + c]: eight lane-strided running sums per lane, combined in a fixed
@@ -250,27 +447,42 @@ __global__ __launch_bounds__(256) void k_bracket_norm_finish(
 }
 
 // One recorded element: its level for the true norm, ORed into the zero field the first kernel left.
+// B = 0: per-tensor widths, b and the place of the tensor's level fields come from `widths` (this
+// worker's row of the table).
 template <int B>
 __device__ __forceinline__ void settle_record(uint2 rec, int64_t chunk0, uint32_t w, const float* __restrict__ norms,
                                               int32_t n_seg, const int32_t* __restrict__ granule_cseg,
                                               const int32_t* __restrict__ cseg_seg, uint32_t key0, uint32_t key1,
-                                              uint32_t step, uint32_t worker, uint32_t* __restrict__ plane)
+                                              uint32_t step, uint32_t worker, uint32_t* __restrict__ plane,
+                                              const dq_cseg_width* __restrict__ widths)
 {
-    constexpr float S = static_cast<float>((1 << B) - 1);
     const uint32_t e = rec.x; // < 4096 and inside the layout: written by the first kernel for this chunk
-    const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[granule_cseg[(chunk0 >> 7) + (e >> 7)]]];
-    const float scale = N >= DQ_MIN_NORM ? S / N : 0.0f;
+    const int32_t c = granule_cseg[(chunk0 >> 7) + (e >> 7)];
+    const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[c]];
     const uint64_t P = static_cast<uint64_t>(chunk0) + e;
     uint32_t r[4];
     dq_philox4x32_10(static_cast<uint32_t>(P >> 2), static_cast<uint32_t>(P >> 34), worker, step, key0, key1, r);
     const uint32_t word = (P & 2u) ? ((P & 1u) ? r[3] : r[2]) : ((P & 1u) ? r[1] : r[0]);
-    const uint32_t level = level_of<B>(__uint_as_float(rec.y), scale, word);
+    uint32_t level;
+    uint64_t bit;
+    int b;
+    if constexpr (B == 0) {
+        const dq_cseg_width wd = widths[c];
+        b = wd.b;
+        const float S = static_cast<float>((1 << b) - 1);
+        level = level_of_s(__uint_as_float(rec.y), N >= DQ_MIN_NORM ? S / N : 0.0f, S, word);
+        bit = static_cast<uint64_t>(wd.level_start) * 8u + (P - static_cast<uint64_t>(wd.seg_start)) * static_cast<uint64_t>(b);
+    } else {
+        constexpr float S = static_cast<float>((1 << B) - 1);
+        b = B;
+        level = level_of<B>(__uint_as_float(rec.y), N >= DQ_MIN_NORM ? S / N : 0.0f, word);
+        bit = P * B;
+    }
     if (level != 0) {
         // fields of other elements in the same words are not touched
-        const uint64_t bit = P * B;
         const uint32_t sh = static_cast<uint32_t>(bit & 31u);
         atomicOr(plane + (bit >> 5), level << sh);
-        if (sh + B > 32) atomicOr(plane + (bit >> 5) + 1, level >> (32 - sh));
+        if (sh + b > 32) atomicOr(plane + (bit >> 5) + 1, level >> (32 - sh));
     }
 }
 
@@ -294,8 +506,10 @@ __global__ __launch_bounds__(256) void k_bracket_settle_wide(
     const float* __restrict__ norms, int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ granule_cseg,
     const int32_t* __restrict__ cseg_seg, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
     uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride, dq_bracket_block* __restrict__ blocks,
-    int64_t n_chunks, const uint8_t* __restrict__ inside, unsigned long long* __restrict__ redo_map, int64_t n_words)
+    int64_t n_chunks, const uint8_t* __restrict__ inside, unsigned long long* __restrict__ redo_map, int64_t n_words,
+    const dq_cseg_width* __restrict__ widths_table, int32_t widths_worker_stride)
 {
+    const dq_cseg_width* __restrict__ widths = widths_table + static_cast<int64_t>(blockIdx.y) * widths_worker_stride;
     const uint32_t w = blockIdx.y;
     const uint32_t lane = threadIdx.x & 63;
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
@@ -312,7 +526,7 @@ __global__ __launch_bounds__(256) void k_bracket_settle_wide(
     } else if (lane < count) {
         uint32_t* plane = reinterpret_cast<uint32_t*>(packed + static_cast<int64_t>(w) * packed_stride + (padded_elems >> 3));
         settle_record<B>(blk->rec[lane], chunk0, w, norms, n_seg, granule_cseg, cseg_seg, key0, key1, step,
-                         worker_base + w, plane);
+                         worker_base + w, plane, widths);
     }
 }
 
@@ -328,8 +542,10 @@ __global__ __launch_bounds__(256) void k_bracket_settle(
     const float* __restrict__ norms, int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ granule_cseg,
     const int32_t* __restrict__ cseg_seg, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
     uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride, dq_bracket_block* __restrict__ blocks,
-    int64_t n_chunks, const uint8_t* __restrict__ inside, unsigned long long* __restrict__ redo_map, int64_t n_words)
+    int64_t n_chunks, const uint8_t* __restrict__ inside, unsigned long long* __restrict__ redo_map, int64_t n_words,
+    const dq_cseg_width* __restrict__ widths_table, int32_t widths_worker_stride)
 {
+    const dq_cseg_width* __restrict__ widths = widths_table + static_cast<int64_t>(blockIdx.y) * widths_worker_stride;
     const uint32_t w = blockIdx.y;
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const bool active = chunk < n_chunks;
@@ -346,7 +562,7 @@ __global__ __launch_bounds__(256) void k_bracket_settle(
                                                           (padded_elems >> 3));
             for (uint32_t k = 0; k < count; ++k)
                 settle_record<B>(blk->rec[k], chunk0, w, norms, n_seg, granule_cseg, cseg_seg, key0, key1, step,
-                                 worker_base + w, plane);
+                                 worker_base + w, plane, widths);
         }
     }
     // 64 consecutive chunks per wavefront: one word of the redo map (blockDim is a multiple of 64)
@@ -367,7 +583,8 @@ __global__ __launch_bounds__(QP_THREADS) void k_bracket_redo(
     const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
     const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
     uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride,
-    const unsigned long long* __restrict__ redo_map, int64_t n_words)
+    const unsigned long long* __restrict__ redo_map, int64_t n_words, const dq_cseg_width* __restrict__ widths_table,
+    int32_t widths_worker_stride)
 {
     const int64_t word0 = static_cast<int64_t>(blockIdx.x) * REDO_WORDS;
     const unsigned long long* map = redo_map + static_cast<int64_t>(blockIdx.y) * n_words;
@@ -380,9 +597,15 @@ __global__ __launch_bounds__(QP_THREADS) void k_bracket_redo(
         while (bits != 0) {
             const int bit = __builtin_ctzll(bits);
             bits &= bits - 1;
-            quantize_pack_chunk<B, 2, 0>(grads, worker_stride, norms, n_seg, granule_cseg, cseg_seg, cseg_valid_end,
-                                         padded_elems, key0, key1, step, worker_base, packed, packed_stride, nullptr,
-                                         static_cast<uint32_t>((word0 + k) * 64 + bit));
+            const uint32_t chunk = static_cast<uint32_t>((word0 + k) * 64 + bit);
+            if constexpr (B == 0)
+                quantize_pack_chunk_v<2, 0>(grads, worker_stride, norms, n_seg, granule_cseg, cseg_seg, cseg_valid_end,
+                                            widths_table, widths_worker_stride, padded_elems, key0, key1, step,
+                                            worker_base, packed, packed_stride, nullptr, chunk);
+            else
+                quantize_pack_chunk<B, 2, 0>(grads, worker_stride, norms, n_seg, granule_cseg, cseg_seg, cseg_valid_end,
+                                             padded_elems, key0, key1, step, worker_base, packed, packed_stride, nullptr,
+                                             chunk);
             __syncthreads(); // the chunk's staging in LDS is reused by the next one
         }
     }
@@ -397,12 +620,19 @@ __global__ __launch_bounds__(QP_THREADS) void k_bracket_redo_direct(
     const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
     const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, uint32_t key0, uint32_t key1, uint32_t step,
     uint32_t worker_base, uint8_t* __restrict__ packed, int64_t packed_stride,
-    const unsigned long long* __restrict__ redo_map, int64_t n_words)
+    const unsigned long long* __restrict__ redo_map, int64_t n_words, const dq_cseg_width* __restrict__ widths_table,
+    int32_t widths_worker_stride)
 {
     const unsigned long long word = redo_map[static_cast<int64_t>(blockIdx.y) * n_words + (blockIdx.x >> 6)];
     if (((word >> (blockIdx.x & 63)) & 1ull) == 0) return; // uniform: one address for the whole workgroup
-    quantize_pack_chunk<B, 2, 0>(grads, worker_stride, norms, n_seg, granule_cseg, cseg_seg, cseg_valid_end, padded_elems,
-                                 key0, key1, step, worker_base, packed, packed_stride, nullptr, blockIdx.x);
+    if constexpr (B == 0)
+        quantize_pack_chunk_v<2, 0>(grads, worker_stride, norms, n_seg, granule_cseg, cseg_seg, cseg_valid_end, widths_table,
+                                    widths_worker_stride, padded_elems, key0, key1, step, worker_base, packed,
+                                    packed_stride, nullptr, blockIdx.x);
+    else
+        quantize_pack_chunk<B, 2, 0>(grads, worker_stride, norms, n_seg, granule_cseg, cseg_seg, cseg_valid_end,
+                                     padded_elems, key0, key1, step, worker_base, packed, packed_stride, nullptr,
+                                     blockIdx.x);
 }
 
 // Statistics of one call, from the blocks: elements settled afterwards and chunks quantized again.
@@ -444,11 +674,12 @@ __global__ void k_zero_two(unsigned long long* __restrict__ stats)
     stats[threadIdx.x] = 0;
 }
 
+// B = 0: per-tensor widths from `widths_table` (row stride `widths_row`: 0 when the workers share a row)
 template <int B, bool LINF>
 int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_stride, int M, const float* norm_lo,
                      const float* norm_hi, uint64_t seed, uint32_t step, uint32_t worker_base, float* norms,
                      uint8_t* packed, int64_t packed_stride, void* workspace, unsigned long long* stats,
-                     hipStream_t stream)
+                     hipStream_t stream, const dq_cseg_width* widths_table = nullptr, int32_t widths_row = 0)
 {
     const dq_bracket_layout L = dq_bracket_layout_of(plan, M);
     if (L.n_chunks > INT32_MAX) return DQ_ERR_INVALID_ARG;
@@ -459,10 +690,16 @@ int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_str
     unsigned long long* redo_map = reinterpret_cast<unsigned long long*>(ws + L.redo_at);
     const dim3 grid(static_cast<unsigned>(L.n_chunks), M), block(QP_THREADS);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
-    hipLaunchKernelGGL((k_quantize_pack_bracketed<B, LINF>), grid, block, 0, stream, grads, worker_stride, norm_lo, norm_hi,
-                       plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_start, plan->d_cseg_valid_end,
-                       plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, partials, L.n_slots,
-                       blocks, L.n_chunks, norms, inside, plan->n_cseg);
+    if constexpr (B == 0)
+        hipLaunchKernelGGL(k_quantize_pack_bracketed_v<LINF>, grid, block, 0, stream, grads, worker_stride, norm_lo, norm_hi,
+                           plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_start, plan->d_cseg_valid_end,
+                           widths_table, widths_row, plan->padded_elems, key0, key1, step, worker_base, packed,
+                           packed_stride, partials, L.n_slots, blocks, L.n_chunks, norms, inside, plan->n_cseg);
+    else
+        hipLaunchKernelGGL((k_quantize_pack_bracketed<(B == 0 ? 1 : B), LINF>), grid, block, 0, stream, grads, worker_stride,
+                           norm_lo, norm_hi, plan->n_seg, plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_start,
+                           plan->d_cseg_valid_end, plan->padded_elems, key0, key1, step, worker_base, packed,
+                           packed_stride, partials, L.n_slots, blocks, L.n_chunks, norms, inside, plan->n_cseg);
     if (plan->n_span > 0)
         hipLaunchKernelGGL(k_bracket_norm_finish<LINF>, dim3(plan->n_span, M), dim3(256), 0, stream, partials, L.n_slots,
                            plan->d_cseg_start, plan->d_cseg_valid_end, plan->d_cseg_seg, plan->d_span_cseg, plan->n_seg,
@@ -474,22 +711,22 @@ int launch_bracketed(const dq_plan* plan, const float* grads, int64_t worker_str
         hipLaunchKernelGGL(k_bracket_settle_wide<B>, dim3(static_cast<unsigned>((L.n_chunks + 3) / 4), M), dim3(256), 0,
                            stream, norms, plan->n_seg, plan->n_cseg, plan->d_granule_cseg, plan->d_cseg_seg,
                            plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, blocks, L.n_chunks,
-                           inside, redo_map, L.n_words);
+                           inside, redo_map, L.n_words, widths_table, widths_row);
     } else {
         hipLaunchKernelGGL(k_bracket_settle<B>, dim3(static_cast<unsigned>((L.n_chunks + 255) / 256), M), dim3(256), 0,
                            stream, norms, plan->n_seg, plan->n_cseg, plan->d_granule_cseg, plan->d_cseg_seg,
                            plan->padded_elems, key0, key1, step, worker_base, packed, packed_stride, blocks, L.n_chunks,
-                           inside, redo_map, L.n_words);
+                           inside, redo_map, L.n_words, widths_table, widths_row);
     }
     if (static_cast<int64_t>(M) * L.n_chunks <= SETTLE_WIDE_MAX)
         hipLaunchKernelGGL(k_bracket_redo_direct<B>, grid, block, 0, stream, grads, worker_stride, norms, plan->n_seg,
                            plan->d_granule_cseg, plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, key0, key1,
-                           step, worker_base, packed, packed_stride, redo_map, L.n_words);
+                           step, worker_base, packed, packed_stride, redo_map, L.n_words, widths_table, widths_row);
     else
         hipLaunchKernelGGL(k_bracket_redo<B>, dim3(static_cast<unsigned>((L.n_words + REDO_WORDS - 1) / REDO_WORDS), M),
                            block, 0, stream, grads, worker_stride, norms, plan->n_seg, plan->d_granule_cseg,
                            plan->d_cseg_seg, plan->d_cseg_valid_end, plan->padded_elems, key0, key1, step, worker_base,
-                           packed, packed_stride, redo_map, L.n_words);
+                           packed, packed_stride, redo_map, L.n_words, widths_table, widths_row);
     if (stats) {
         const int64_t n_blocks = static_cast<int64_t>(M) * L.n_chunks;
         const int64_t wgs = (n_blocks + 256 * BS_PER_LANE - 1) / (256 * BS_PER_LANE);
@@ -584,4 +821,41 @@ extern "C" int dq_norm_quantize_pack_bracketed(const dq_plan_t* plan, const floa
         DQ_BRACKETED(8);
     }
 #undef DQ_BRACKETED
+}
+
+extern "C" int dq_norm_quantize_pack_bracketed_v(const dq_plan_t* plan, const dq_widths_t* widths, const float* grads_dev,
+                                                 int64_t worker_stride_elems, int M, int linf, const float* norm_lo_dev,
+                                                 const float* norm_hi_dev, uint64_t seed, uint32_t step,
+                                                 uint32_t worker_base, float* norms_dev, uint8_t* packed_dev,
+                                                 int64_t packed_worker_stride_bytes, void* workspace_dev,
+                                                 int64_t* stats_dev, void* hip_stream)
+{
+    if (!plan || !widths || !grads_dev || !norm_lo_dev || !norm_hi_dev || !norms_dev || !packed_dev || !workspace_dev)
+        return DQ_ERR_INVALID_ARG;
+    if (widths->plan != plan || widths->packed_bytes < 0) return DQ_ERR_INVALID_ARG;
+    if (M < 1 || M > DQ_MAX_WORKERS) return DQ_ERR_INVALID_ARG;
+    if (widths->n_workers != 1 && widths->n_workers != M) return DQ_ERR_INVALID_ARG;
+    const int32_t row_stride = widths->n_workers == 1 ? 0 : plan->n_cseg;
+    if (worker_stride_elems < plan->padded_elems || (worker_stride_elems & 3)) return DQ_ERR_INVALID_ARG;
+    if (packed_worker_stride_bytes < widths->packed_bytes || (packed_worker_stride_bytes & 15))
+        return DQ_ERR_INVALID_ARG;
+    if (!dq_aligned16(grads_dev) || !dq_aligned16(packed_dev) || !dq_aligned16(workspace_dev)) return DQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(norm_lo_dev) & 3u) || (reinterpret_cast<uintptr_t>(norm_hi_dev) & 3u) ||
+        (reinterpret_cast<uintptr_t>(norms_dev) & 3u) || (reinterpret_cast<uintptr_t>(stats_dev) & 7u))
+        return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan);
+    if (rc != DQ_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (plan->n_cseg < plan->n_seg) {
+        const int zrc = dq_zero_floats(norms_dev, static_cast<int64_t>(M) * plan->n_seg, stream);
+        if (zrc != DQ_OK) return zrc;
+    }
+    if (plan->padded_elems == 0) return DQ_OK;
+    unsigned long long* stats = reinterpret_cast<unsigned long long*>(stats_dev);
+    return linf ? launch_bracketed<0, true>(plan, grads_dev, worker_stride_elems, M, norm_lo_dev, norm_hi_dev, seed, step,
+                                            worker_base, norms_dev, packed_dev, packed_worker_stride_bytes, workspace_dev,
+                                            stats, stream, widths->d_table, row_stride)
+                : launch_bracketed<0, false>(plan, grads_dev, worker_stride_elems, M, norm_lo_dev, norm_hi_dev, seed, step,
+                                             worker_base, norms_dev, packed_dev, packed_worker_stride_bytes, workspace_dev,
+                                             stats, stream, widths->d_table, row_stride);
 }

@@ -180,4 +180,169 @@ __device__ __forceinline__ void quantize_pack_chunk(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Per-tensor widths.  Same work split; b, the level count and the place of the level bytes come
+// from the widths table per segment instead of the template argument.  A chunk's level bytes are
+// still one contiguous stretch of the message (every segment's stretch is a whole number of
+// 16-byte pieces per granule), so they are staged and stored the same way.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void quantize4_v(const float4 x, const float scale, const float S, const int b,
+                                            const uint32_t (&r)[4], uint32_t& sign, uint32_t& level)
+{
+    const float v[4] = { x.x, x.y, x.z, x.w };
+    level = 0;
+#pragma unroll
+    for (int k = 3; k >= 0; --k) {
+        sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31);
+        const float a = fminf(fabsf(v[k]) * scale, S);
+        const float p = __builtin_amdgcn_fractf(a);
+        const float u = static_cast<float>(r[k] >> 8) * 0x1p-24f;
+        level = (level << b) + static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
+    }
+}
+
+template <int TILES, int NORM> // NORM as in quantize_pack_chunk
+__device__ __forceinline__ void quantize_pack_chunk_v(
+    const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
+    const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
+    const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths_table,
+    int32_t widths_worker_stride, int64_t padded_elems,
+    uint32_t key0, uint32_t key1, uint32_t step, uint32_t worker_base, uint8_t* __restrict__ packed,
+    int64_t packed_stride, float* __restrict__ norms_out, uint32_t chunk_index)
+{
+    constexpr int CHUNK = QP_TILE * TILES;
+    constexpr int MAX_LOCAL_SEG = CHUNK / DQ_GRANULE;
+    static_assert(NORM == 0 || CHUNK == DQ_CHUNK, "the fused norm works on 4096-element chunks");
+    // this worker's row of the table (stride 0: the workers share one row)
+    const dq_cseg_width* __restrict__ widths = widths_table + static_cast<int64_t>(blockIdx.y) * widths_worker_stride;
+
+    __shared__ float lds_scale[MAX_LOCAL_SEG];
+    __shared__ float lds_levels[MAX_LOCAL_SEG];      // s = 2^b - 1 of the segment
+    __shared__ int32_t lds_b[MAX_LOCAL_SEG];
+    __shared__ int32_t lds_level_base[MAX_LOCAL_SEG]; // byte offset, in the chunk's level bytes, the
+                                                      // segment's fields would have at chunk element 0
+    __shared__ int32_t lds_valid_end[MAX_LOCAL_SEG];
+    __shared__ __align__(16) uint8_t lds_sign[TILES * QP_THREADS];
+    __shared__ __align__(16) uint8_t lds_level[TILES * QP_THREADS * 8];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t w = blockIdx.y;
+    const int64_t chunk0 = static_cast<int64_t>(chunk_index) * CHUNK;
+    const uint32_t n_elems = static_cast<uint32_t>(padded_elems - chunk0 < CHUNK ? padded_elems - chunk0 : CHUNK);
+    const float* g = grads + static_cast<int64_t>(w) * worker_stride + chunk0;
+    const int32_t* gseg = granule_cseg + (chunk0 >> 7);
+
+    float4 x[TILES][2];
+    int32_t seg[TILES];
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        e = e < n_elems ? e : n_elems - QP_PER_LANE;
+        x[it][0] = *reinterpret_cast<const float4*>(g + e);
+        x[it][1] = *reinterpret_cast<const float4*>(g + e + 4);
+        seg[it] = gseg[e >> 7];
+    }
+
+    const int32_t seg_first = gseg[0];
+    const int32_t seg_last = gseg[(n_elems - 1) >> 7];
+    // where the chunk's level bytes start in the level plane (uniform)
+    const dq_cseg_width first = widths[seg_first];
+    const int64_t chunk_level0 = first.level_start + ((chunk0 - first.seg_start) >> 3) * first.b;
+    if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
+        const dq_cseg_width e = widths[seg_first + tid];
+        const float S = static_cast<float>((1 << e.b) - 1);
+        if constexpr (NORM == 0) {
+            const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid]];
+            lds_scale[tid] = N >= DQ_MIN_NORM ? S / N : 0.0f;
+        }
+        lds_levels[tid] = S;
+        lds_b[tid] = e.b;
+        // chunk0 - seg_start is a multiple of 128 of either sign, so the shift is exact
+        lds_level_base[tid] = static_cast<int32_t>(e.level_start + ((chunk0 - e.seg_start) >> 3) * e.b - chunk_level0);
+        const int64_t rel = cseg_valid_end[seg_first + tid] - chunk0;
+        lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+    }
+    __syncthreads();
+    if constexpr (NORM != 0) {
+        __shared__ double lds_gsum[DQ_CHUNK_GRANULES];
+        __shared__ int32_t lds_glocal[DQ_CHUNK_GRANULES];
+        int valid[TILES], local[TILES];
+#pragma unroll
+        for (int it = 0; it < TILES; ++it) {
+            const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+            local[it] = seg[it] - seg_first;
+            valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
+        }
+        dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+        __syncthreads();
+        if (tid < DQ_CHUNK_GRANULES)
+            dq_chunk_tensor_norms<NORM == 2>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+                                             [&](int j, float N) {
+                                                 norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
+                                                 lds_scale[j] = N >= DQ_MIN_NORM ? lds_levels[j] / N : 0.0f;
+                                             });
+        __syncthreads();
+    }
+
+    const uint32_t quad_lo0 = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 2);
+    const uint32_t quad_hi = static_cast<uint32_t>(static_cast<uint64_t>(chunk0) >> 34);
+    const uint32_t worker = worker_base + w;
+
+#pragma unroll
+    for (int it = 0; it < TILES; ++it) {
+        const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
+        if (e < n_elems) {
+            const int local = seg[it] - seg_first;
+            const float scale = lds_scale[local];
+            const float S = lds_levels[local];
+            const int b = lds_b[local];
+            const int32_t n_valid = lds_valid_end[local] - static_cast<int32_t>(e);
+
+            const uint32_t quad = quad_lo0 + (e >> 2);
+            uint32_t r0[4], r1[4];
+            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
+            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
+
+            uint32_t sign = 0, lv_lo, lv_hi;
+            quantize4_v(x[it][1], scale, S, b, r1, sign, lv_hi);
+            quantize4_v(x[it][0], scale, S, b, r0, sign, lv_lo);
+            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * b));
+            if (n_valid < QP_PER_LANE) {
+                const int nv = n_valid > 0 ? n_valid : 0;
+                sign &= (1u << nv) - 1u;
+                level &= (static_cast<uint64_t>(1) << (nv * b)) - 1u;
+            }
+            lds_sign[it * QP_THREADS + tid] = static_cast<uint8_t>(sign);
+            // b bytes at an offset that is a multiple of b past a 16-byte boundary (every tensor's
+            // stretch of a chunk starts on one), so the naturally aligned stores of stage_bytes apply
+            uint8_t* dst = &lds_level[lds_level_base[local] + static_cast<int32_t>(e >> 3) * b];
+            switch (b) {
+            case 1: stage_bytes<1>(dst, level); break;
+            case 2: stage_bytes<2>(dst, level); break;
+            case 3: stage_bytes<3>(dst, level); break;
+            case 4: stage_bytes<4>(dst, level); break;
+            case 5: stage_bytes<5>(dst, level); break;
+            case 6: stage_bytes<6>(dst, level); break;
+            case 7: stage_bytes<7>(dst, level); break;
+            default: stage_bytes<8>(dst, level); break;
+            }
+        }
+    }
+    __syncthreads();
+
+    uint8_t* msg = packed + static_cast<int64_t>(w) * packed_stride;
+    {
+        uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
+        const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+    }
+    {
+        const int last = seg_last - seg_first;
+        const uint32_t level_bytes = static_cast<uint32_t>(lds_level_base[last]) + (n_elems >> 3) * lds_b[last];
+        uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + chunk_level0);
+        const uint4* src = reinterpret_cast<const uint4*>(lds_level);
+        for (uint32_t i = tid; i < level_bytes / 16; i += QP_THREADS) dst[i] = src[i];
+    }
+}
+
 } // namespace

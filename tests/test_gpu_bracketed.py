@@ -203,3 +203,50 @@ def test_norm_bracket_helper(dq):
     for bad in (-0.1, 1.0, float("nan")):
         with pytest.raises(dq.DQError):
             dq.norm_bracket(norms, bad, lo, hi)
+
+
+@pytest.mark.parametrize("per_worker", [False, True])
+def test_per_tensor_widths(dq, oracle, per_worker):
+    """the single pass with a widths table: long tensors bracketed, short ones finished in the kernel,
+    widths 1..8 mixed; tight, loose and wrong brackets give the oracle's messages for the call's norms"""
+    seg_len = [9000, 100, 3 * 4096 + 700, 0, 2000, 40000, 77]
+    starts, dp = wl.seg_starts(seg_len)
+    M = 3
+    gen = torch.Generator().manual_seed(57)
+    g = torch.randn((M, dp), generator=gen) * 1e-2
+    g_host = np.ascontiguousarray(g.numpy())
+    g_dev = g.cuda()
+    plan = dq.Plan(seg_len)
+    rng = np.random.default_rng(58)
+    widths = rng.integers(1, 9, size=(M, len(seg_len)) if per_worker else len(seg_len)).astype(np.int32)
+    table = dq.Widths(plan, widths, workers=M if per_worker else None)
+    ref = gpu_norm(dq, plan, g_dev)
+    wsb = torch.empty(dq.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device="cuda")
+    stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+    seen = []
+    for lo_f, hi_f in ((0.99, 1.01), (0.7, 1.4), (2.0, 3.0), (float("nan"), 1.0)):
+        norms_dev = torch.full((M, plan.n_seg), float("nan"), dtype=torch.float32, device="cuda")
+        packed = torch.zeros((M, table.packed_bytes + 16), dtype=torch.uint8, device="cuda")
+        packed[:, table.packed_bytes:] = 0xA5
+        dq.norm_quantize_pack_bracketed_v(plan, table, g_dev, (ref * lo_f).contiguous(), (ref * hi_f).contiguous(), SEED, 4,
+                                          norms_dev, packed, wsb, worker_base=1, stats=stats)
+        torch.cuda.synchronize()
+        norms = norms_dev.cpu().numpy()
+        want_n = oracle.norm(seg_len, g_host)
+        assert np.all(np.abs(norms.astype(np.float64) - want_n.astype(np.float64)) <= np.spacing(want_n))
+        got = packed.cpu().numpy()
+        if per_worker:
+            want = oracle.quantize_pack_w(seg_len, g_host, norms, widths, SEED, 4, 1)
+            for i in range(M):
+                n = table.worker_packed_bytes(i)
+                assert np.array_equal(got[i, :n], want[i, :n]), (lo_f, i)
+                assert np.all(got[i, n:table.packed_bytes] == 0)
+        else:
+            want = oracle.quantize_pack_v(seg_len, g_host, norms, widths, SEED, 4, 1)
+            assert np.array_equal(got[:, :table.packed_bytes], want), lo_f
+        assert np.all(got[:, table.packed_bytes:] == 0xA5)
+        seen.append(stats.cpu().numpy().copy())
+    assert seen[0][0] > 0                                  # a tight bracket settles a few elements afterwards
+    assert seen[2][1] > 0 and seen[3][1] > 0               # a wrong or unusable one sends chunks through the redo map
+    table.close()
+    plan.close()

@@ -200,6 +200,16 @@ def test_random_layout(dq, oracle, case):
     got_v = pk_v.cpu().numpy()
     assert np.array_equal(got_v[:, :table.packed_bytes], want_v)
     assert np.all(got_v[:, table.packed_bytes:] == 0xA5)
+    # the same messages from the single pass with bracketed norms (any bracket)
+    pk_bv = torch.full_like(pk_v, 0xA5)
+    n_bv = torch.full((M, n_seg), float("nan"), dtype=torch.float32, device="cuda")
+    dq.norm_quantize_pack_bracketed_v(plan, table, g_dev, lo_dev, hi_dev, seed, step, n_bv, pk_bv, wsb,
+                                      worker_base=worker_base, linf=linf)
+    torch.cuda.synchronize()
+    assert torch.equal(n_bv.view(torch.int32), n3.view(torch.int32))
+    assert np.array_equal(pk_bv.cpu().numpy()[:, :table.packed_bytes],
+                          oracle.quantize_pack_v(seg_len, g_host, n3_host, b_seg, seed, step, worker_base))
+    assert np.all(pk_bv.cpu().numpy()[:, table.packed_bytes:] == 0xA5)
     want_out_v = oracle.unpack_dequant_reduce_v(seg_len, want_v, norms, b_seg)
     terms = [oracle.unpack_dequant_reduce_v(seg_len, want_v[i:i + 1], norms[i:i + 1], b_seg) for i in range(M)]
     _check_average(out_v.cpu().numpy(), want_out_v, terms, valid)
@@ -220,6 +230,16 @@ def test_random_layout(dq, oracle, case):
         assert n == oracle.packed_bytes_v(seg_len, b_w[i])
         assert np.array_equal(got_w[i, :n], want_w[i, :n]), i
         assert np.all(got_w[i, n:] == 0)
+    pk_bw = torch.zeros_like(pk_w)
+    dq.norm_quantize_pack_bracketed_v(plan, table, g_dev, lo_dev, hi_dev, seed, step, n_bv, pk_bw, wsb,
+                                      worker_base=worker_base, linf=linf)
+    torch.cuda.synchronize()
+    want_bw = oracle.quantize_pack_w(seg_len, g_host, n3_host, b_w, seed, step, worker_base)
+    got_bw = pk_bw.cpu().numpy()
+    for i in range(M):
+        n = table.worker_packed_bytes(i)
+        assert np.array_equal(got_bw[i, :n], want_bw[i, :n]), i
+        assert np.all(got_bw[i, n:] == 0)
     want_out_w = oracle.unpack_dequant_reduce_w(seg_len, want_w, norms, b_w)
     terms = [oracle.unpack_dequant_reduce_v(seg_len, want_w[i:i + 1, :oracle.packed_bytes_v(seg_len, b_w[i])],
                                             norms[i:i + 1], b_w[i]) for i in range(M)]
