@@ -29,7 +29,9 @@ Protocol (Algorithm 1 with the choices the paper leaves open):
   * per_worker=True: every worker takes Eq. (17) with its own norm (``dq_select_bits_per_worker``;
     with per_tensor=True also one width per tensor); b_t in the result are [M][n_seg] arrays.
   * device_rule=True: the rule runs on the GPU (``dq_select_bits_device``) and the loop never waits
-    for the host; b_t and the cost are read back once at the end.  alpha must be a number.
+    for the host; b_t and the cost are read back once at the end.  alpha must be a number.  With the
+    lagged rule and norm_margin the worker side is ``dq_norm_quantize_pack_bracketed_v``: one pass
+    over the gradient with the widths table the rule left on the GPU.
   * p: 2 or "inf", the norm of Eq. (5) (the paper leaves p open): ``dq_norm``/``dq_select_bits`` or
     ``dq_norm_linf``/``dq_select_bits_linf``.
 """
@@ -95,7 +97,7 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
             raise ValueError("per_tensor uses the tensors' own norms: leave p at 2 or run the max norm without it")
         rule_name = "per_tensor" if per_tensor else ("single" if p == 2 else "single_linf")
         return _run_device_rule(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged,
-                                seed, B_pre, on_step, norm_fn, rule_name)
+                                seed, B_pre, on_step, norm_fn, rule_name, norm_margin)
     if per_tensor:
         return _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged,
                                seed, B_pre, on_step, norm_fn, one_pass and lagged and plan.chunk_local, p != 2)
@@ -223,7 +225,7 @@ def _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b
 
 
 def _run_device_rule(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b_max, tau, lagged, seed, B_pre,
-                     on_step, norm_fn, rule_name) -> DQSGDResult:
+                     on_step, norm_fn, rule_name, norm_margin=None) -> DQSGDResult:
     import numpy as np
     if alpha == "estimate":
         raise ValueError('alpha="estimate" needs the loss on the host: not available with device_rule')
@@ -242,15 +244,32 @@ def _run_device_rule(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, 
     b_cur = torch.from_numpy(np.broadcast_to(np.asarray(b0, dtype=np.int32), (n_seg,)).copy()).to(dev)
     table = _b.Widths(plan, b_cur.cpu().numpy())
     unused = _b.Widths(plan)
+    # With the lagged rule the widths are on the GPU before the gradient exists; with a margin for
+    # the norms as well, norms and messages come from one pass and nothing in the loop waits for the host.
+    bracketed = norm_margin is not None and lagged
+    if bracketed:
+        if not 0.0 <= norm_margin < 1.0:
+            raise ValueError("norm_margin must be in [0, 1)")
+        wsb = torch.empty(_b.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device=dev)
+        prev, lo, hi = (torch.empty_like(norms) for _ in range(3))
     for t in range(T):
         grad_fn(t, x, grads)
-        norm_fn(plan, grads, norms, ws)
+        one_pass = bracketed and t > 0
+        if one_pass:
+            _b.norm_bracket(prev, norm_margin, lo, hi)
+            _b.norm_quantize_pack_bracketed_v(plan, table, grads, lo, hi, seed, t, norms, packed, wsb,
+                                              linf=rule_name == "single_linf")
+        else:
+            norm_fn(plan, grads, norms, ws)
+        if bracketed:
+            prev.copy_(norms)
         if not lagged:
             _b.select_bits_device(plan, table, norms, t, T, eps_hat_q, alpha, b_min, b_max, rule=rule_name,
                                   b_out=b_hist[t], gbar_out=g_hist[t])
         else:
             b_hist[t].copy_(b_cur)
-        _b.quantize_pack_v(plan, table, grads, norms, seed, t, packed)
+        if not one_pass:
+            _b.quantize_pack_v(plan, table, grads, norms, seed, t, packed)
         if on_step is not None:
             torch.cuda.current_stream().synchronize()
             b_now = b_hist[t].cpu().numpy()

@@ -177,3 +177,36 @@ def test_loop_without_host_round_trips_equals_the_host_rule_loop(dq, oracle, mod
     assert lagged or len(checked) == T
     assert float((dev.x - target).norm()) < 0.2 * float(target.norm())
     plan.close()
+
+
+@pytest.mark.parametrize("mode", ["single", "per_tensor"])
+def test_lagged_loop_in_one_pass_per_iteration(dq, oracle, mode):
+    """The lagged loop with the rule on the device and norm_margin: from the second iteration on norms and
+    messages come from dq_norm_quantize_pack_bracketed_v with the widths table the rule left on the GPU --
+    no host round trip, one read of the gradients.  Every iteration's messages equal the oracle's for that
+    iteration's norms and widths; the widths and the model follow the two-pass loop."""
+    from paper_2107_14575_amd import dqsgd
+    seg_len = [9000, 300, 0, 5000, 77]            # two tensors span chunks (bracketed), two lie inside one
+    M, T, eta, alpha, tau, eps_hat = 4, 24, 0.2, 0.9, 4, 0.02
+    dp, target, grad_fn = _least_squares(seg_len, M, T, 96)
+    plan = dq.Plan(seg_len)
+    x0 = torch.zeros(dp, dtype=torch.float32, device="cuda")
+    kw = dict(b0=2, b_min=1, b_max=8, tau=tau, lagged=True, seed=SEED, per_tensor=mode == "per_tensor", device_rule=True)
+    two_pass = dqsgd.run(plan, x0, grad_fn, M, T, eta, eps_hat, alpha, **kw)
+    seen = []
+
+    def on_step(t, b, grads, norms, packed):
+        g_host = np.ascontiguousarray(grads.cpu().numpy())
+        want_n = oracle.norm(seg_len, g_host)
+        assert np.all(np.abs(norms.astype(np.float64) - want_n.astype(np.float64)) <= np.spacing(want_n)), t
+        b_seg = np.asarray(b, dtype=np.int32) if mode == "per_tensor" else np.full(len(seg_len), b, dtype=np.int32)
+        want = oracle.quantize_pack_v(seg_len, g_host, norms, b_seg, SEED, t)
+        assert np.array_equal(packed.cpu().numpy(), want), f"messages differ at t={t}"
+        seen.append(t)
+
+    one_pass = dqsgd.run(plan, x0, grad_fn, M, T, eta, eps_hat, alpha, on_step=on_step, norm_margin=0.5, **kw)
+    assert seen == list(range(T))
+    assert all(np.array_equal(a, c) for a, c in zip(one_pass.bits, two_pass.bits))
+    assert one_pass.cost_bits == two_pass.cost_bits
+    assert float((one_pass.x - two_pass.x).abs().max()) <= 1e-5 * float(two_pass.x.abs().max())
+    plan.close()
