@@ -71,6 +71,7 @@ int main()
         CHECK(dq_bracketed_workspace_bytes(plan, M) >= (dp + 4095) / 4096 * 256 * M && dq_bracketed_workspace_bytes(plan, 0) == -1);
         CHECK(dq_bracketed_workspace_bytes(plan, M) % 256 == 0 && dq_bracketed_workspace_bytes(nullptr, M) == -1);
         CHECK(dq_norm_quantize_pack_bracketed(plan, fake, dp, M, 0, fake, fake, 9, 1, 0, 0, fake, fake8, 1 << 30, fake8, nullptr, nullptr) == DQ_ERR_INVALID_ARG);
+        CHECK(dq_norm_quantize_pack_bracketed_v(plan, nullptr, fake, dp, M, 0, fake, fake, 1, 0, 0, fake, fake8, 1 << 30, fake8, nullptr, nullptr) == DQ_ERR_INVALID_ARG);
         CHECK(dq_norm_quantize_pack_bracketed(plan, fake, dp, M, 1, nullptr, fake, 4, 1, 0, 0, fake, fake8, 1 << 30, fake8, nullptr, nullptr) == DQ_ERR_INVALID_ARG);
         dq_plan_destroy(plan);
     }
