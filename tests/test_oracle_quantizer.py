@@ -317,6 +317,17 @@ def test_level_never_grows_with_the_norm(oracle, b):
         if prev is not None:
             assert np.all(level[0] <= prev), N
         prev = level[0].copy()
+    # every binary32 norm of three runs of 2048 consecutive values, on a short vector
+    short = np.ascontiguousarray(grads[:, :128])
+    for f in (0.31, 1.0, 2.7):
+        x = np.float32(base * f)
+        prev = None
+        for _ in range(2048):
+            _, level = oracle.quantize([128], short, np.array([[x]], dtype=np.float32), b, SEED, 5, worker_base=3)
+            if prev is not None:
+                assert np.all(level[0] <= prev), float(x)
+            prev = level[0].copy()
+            x = np.nextafter(x, np.float32(np.inf))
     # equal at both ends => equal inside
     lo, hi = np.float32(base * 0.875), np.float32(base * 1.125)
     _, l_lo = oracle.quantize([d], grads, np.array([[lo]], dtype=np.float32), b, SEED, 5, worker_base=3)
