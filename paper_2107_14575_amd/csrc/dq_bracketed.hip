@@ -127,10 +127,11 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
         local[it] = seg[it] - seg_first;
         valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
     }
-    dq_chunk_granule_sums<LINF>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+    const int n_scan = dq_chunk_granule_sums<LINF>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal,
+                                                   seg_first == seg_last, static_cast<int>(n_elems >> 7));
     __syncthreads();
     if (tid < DQ_CHUNK_GRANULES)
-        dq_chunk_tensor_totals<LINF>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+        dq_chunk_tensor_totals<LINF>(static_cast<int>(tid), n_scan, lds_gsum, lds_glocal,
                                       [&](int j, double total) {
                                           partials[static_cast<int64_t>(w) * n_slots + blockIdx.x + seg_first + j] = total;
                                           if (lds_whole[j]) { // all of the tensor is here: this is its norm, no bracket involved
@@ -301,10 +302,11 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed_v(
         local[it] = seg[it] - seg_first;
         valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
     }
-    dq_chunk_granule_sums<LINF>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+    const int n_scan = dq_chunk_granule_sums<LINF>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal,
+                                                   seg_first == seg_last, static_cast<int>(n_elems >> 7));
     __syncthreads();
     if (tid < DQ_CHUNK_GRANULES)
-        dq_chunk_tensor_totals<LINF>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+        dq_chunk_tensor_totals<LINF>(static_cast<int>(tid), n_scan, lds_gsum, lds_glocal,
                                      [&](int j, double total) {
                                          partials[static_cast<int64_t>(w) * n_slots + blockIdx.x + seg_first + j] = total;
                                          if (lds_whole[j]) {

@@ -38,11 +38,67 @@ __device__ __forceinline__ double dq_row_ror(double v)
 // local[it] is the index of that tensor among the chunk's tensors.  Leaves the sum (or maximum)
 // of every 128-element granule in lds_gsum[32] and the granule's tensor index in lds_glocal[32].
 // The caller puts a barrier between the two steps.
+//
+// `single` (the same for the whole workgroup): the chunk holds (part of) one tensor only.  Then a
+// lane's two tiles are added first and one reduction serves both: 16 row totals instead of 32
+// granule totals, all of tensor 0.  Returns the number of entries step 2 has to scan.
 template <bool LINF>
-__device__ __forceinline__ void dq_chunk_granule_sums(const float4 (&x)[2][2], const int (&valid)[2],
-                                                      const int (&local)[2], int tid, double* lds_gsum,
-                                                      int32_t* lds_glocal)
+__device__ __forceinline__ int dq_chunk_granule_sums(const float4 (&x)[2][2], const int (&valid)[2],
+                                                     const int (&local)[2], int tid, double* lds_gsum,
+                                                     int32_t* lds_glocal, bool single, int n_granules)
 {
+    if (single) {
+        double row;
+        if constexpr (LINF) {
+            float m = 0.0f;
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
+                                     x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float a = k < valid[it] ? fabsf(v[k]) : 0.0f;
+                    m = a > m ? a : m;
+                }
+            }
+            float o;
+            o = dq_row_ror<8>(m); m = o > m ? o : m;
+            o = dq_row_ror<4>(m); m = o > m ? o : m;
+            o = dq_row_ror<2>(m); m = o > m ? o : m;
+            o = dq_row_ror<1>(m); m = o > m ? o : m;
+            row = static_cast<double>(m);
+        } else {
+            double acc = 0.0;
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
+                                     x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
+                if (valid[it] >= 8) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const double e = static_cast<double>(v[k]);
+                        acc = __builtin_fma(e, e, acc);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const double e = static_cast<double>(k < valid[it] ? v[k] : 0.0f);
+                        acc = __builtin_fma(e, e, acc);
+                    }
+                }
+            }
+            acc += dq_row_ror<8>(acc);
+            acc += dq_row_ror<4>(acc);
+            acc += dq_row_ror<2>(acc);
+            acc += dq_row_ror<1>(acc);
+            row = acc;
+        }
+        if ((tid & 15) == 0) {
+            lds_gsum[tid >> 4] = row;
+            lds_glocal[tid >> 4] = 0;
+        }
+        return 16;
+    }
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
@@ -87,6 +143,7 @@ __device__ __forceinline__ void dq_chunk_granule_sums(const float4 (&x)[2][2], c
             lds_glocal[it * 16 + (tid >> 4)] = local[it];
         }
     }
+    return n_granules;
 }
 
 // value of the lane N places back in the same 16-lane row, 0 for the first N lanes (DPP row_shr:N)

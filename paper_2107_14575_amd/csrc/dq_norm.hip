@@ -227,10 +227,11 @@ __global__ __launch_bounds__(256) void k_norm_chunk(const float* __restrict__ gr
         local[it] = seg[it] - seg_first;
         valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
     }
-    dq_chunk_granule_sums<LINF>(x, valid, local, tid, lds_gsum, lds_glocal);
+    const int n_scan = dq_chunk_granule_sums<LINF>(x, valid, local, tid, lds_gsum, lds_glocal, n_local == 1,
+                                                   static_cast<int>(n_elems >> 7));
     __syncthreads();
     if (tid < DQ_CHUNK_GRANULES)
-        dq_chunk_tensor_norms<LINF>(tid, static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal, [&](int j, float N) {
+        dq_chunk_tensor_norms<LINF>(tid, n_scan, lds_gsum, lds_glocal, [&](int j, float N) {
             norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
         });
 }

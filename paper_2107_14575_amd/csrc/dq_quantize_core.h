@@ -120,10 +120,11 @@ __device__ __forceinline__ void quantize_pack_chunk(
             local[it] = seg[it] - seg_first;
             valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
         }
-        dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+        const int n_scan = dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal,
+                                                            seg_first == seg_last, static_cast<int>(n_elems >> 7));
         __syncthreads();
         if (tid < DQ_CHUNK_GRANULES)
-            dq_chunk_tensor_norms<NORM == 2>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+            dq_chunk_tensor_norms<NORM == 2>(static_cast<int>(tid), n_scan, lds_gsum, lds_glocal,
                                              [&](int j, float N) {
                                                  norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
                                                  lds_scale[j] = N >= DQ_MIN_NORM ? S / N : 0.0f;
@@ -273,10 +274,11 @@ __device__ __forceinline__ void quantize_pack_chunk_v(
             local[it] = seg[it] - seg_first;
             valid[it] = e < n_elems ? lds_valid_end[local[it]] - static_cast<int32_t>(e) : 0;
         }
-        dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal);
+        const int n_scan = dq_chunk_granule_sums<NORM == 2>(x, valid, local, static_cast<int>(tid), lds_gsum, lds_glocal,
+                                                            seg_first == seg_last, static_cast<int>(n_elems >> 7));
         __syncthreads();
         if (tid < DQ_CHUNK_GRANULES)
-            dq_chunk_tensor_norms<NORM == 2>(static_cast<int>(tid), static_cast<int>(n_elems >> 7), lds_gsum, lds_glocal,
+            dq_chunk_tensor_norms<NORM == 2>(static_cast<int>(tid), n_scan, lds_gsum, lds_glocal,
                                              [&](int j, float N) {
                                                  norms_out[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + j]] = N;
                                                  lds_scale[j] = N >= DQ_MIN_NORM ? lds_levels[j] / N : 0.0f;
