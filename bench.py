@@ -117,6 +117,8 @@ def main() -> None:
     torch.cuda.set_device(0)
 
     seg_len, grads, label = make_workload(args.workload, args.workers, args.log2d)
+    if args.fixed_bits:
+        label = label.replace("b_t dynamic in 2..8", f"b = {args.fixed_bits} fixed")
     M, stride = grads.shape
     D = sum(seg_len)
     plan = dq.Plan(seg_len)
