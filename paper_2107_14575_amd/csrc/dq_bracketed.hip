@@ -18,7 +18,7 @@
 //   k_bracket_norm_finish      for the tensors that cross a chunk boundary: adds the partial sums in
 //       a fixed order: the norms, and whether each came out inside its bracket.
 //   k_bracket_settle[_wide]    one lane per chunk (large plans) or one wavefront per chunk with a
-//       lane per record (up to 2^18 chunks): quantizes the chunk's recorded elements with the
+//       lane per record (up to 2^16 chunks): quantizes the chunk's recorded elements with the
 //       true norm and ORs their levels into the zero fields; a chunk with too many records, with
 //       no usable bracket, or with a norm outside its bracket gets a bit in the redo map instead.
 //   k_bracket_redo             quantizes the chunks of the redo map again in full from the
@@ -577,7 +577,7 @@ __global__ __launch_bounds__(256) void k_bracket_settle(
 constexpr int REDO_WORDS = 8;
 // up to this many (worker, chunk) pairs the settle kernel runs one wavefront per chunk and the
 // redo kernel one workgroup per chunk
-constexpr int64_t SETTLE_WIDE_MAX = 1 << 18;
+constexpr int64_t SETTLE_WIDE_MAX = 1 << 16;
 
 template <int B>
 __global__ __launch_bounds__(QP_THREADS) void k_bracket_redo(
