@@ -250,3 +250,30 @@ def test_per_tensor_widths(dq, oracle, per_worker):
     assert seen[2][1] > 0 and seen[3][1] > 0               # a wrong or unusable one sends chunks through the redo map
     table.close()
     plan.close()
+
+
+def test_between_the_two_settle_forms(dq):
+    """81920 (worker, chunk) pairs: past the 2^16 limit of the wavefront-per-chunk settle kernel, so the
+    lane-per-chunk kernel and the map-walking redo kernel run on a plan far smaller than the
+    full-size one.  Compared with the two calls on the device (themselves checked against the oracle)."""
+    D, M, b = (1 << 26) + 4096 * 3 + 500, 5, 3
+    seg_len, g = wl.flat_student_t(D=D, M=M, device="cuda")
+    plan = dq.Plan(seg_len)
+    assert M * ((plan.padded_elems + 4095) // 4096) > (1 << 16)
+    ref = gpu_norm(dq, plan, g)
+    wsb = torch.empty(dq.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device="cuda")
+    stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+    norms = torch.empty_like(ref)
+    packed = torch.empty((M, plan.packed_bytes(b)), dtype=torch.uint8, device="cuda")
+    want = torch.empty_like(packed)
+    for lo_f, hi_f, all_again in ((0.95, 1.05, False), (1.5, 2.0, True)):
+        packed.fill_(0x3C)
+        dq.norm_quantize_pack_bracketed(plan, g, (ref * lo_f).contiguous(), (ref * hi_f).contiguous(), b, SEED, 6, norms,
+                                        packed, wsb, stats=stats)
+        dq.quantize_pack(plan, g, norms, b, SEED, 6, want)
+        torch.cuda.synchronize()
+        assert float(((norms.double() - ref.double()).abs() / ref.double()).max()) <= 2.0 ** -23
+        assert torch.equal(packed, want)
+        n_pairs = M * ((plan.padded_elems + 4095) // 4096)
+        assert (int(stats[1]) == n_pairs) if all_again else (int(stats[1]) == 0 and int(stats[0]) > 0)
+    plan.close()
