@@ -127,22 +127,15 @@ int dqo_norm(const int64_t *seg_len, int32_t n_seg, const float *grads, int64_t 
     return DQO_OK;
 }
 
-/* A worker's squared whole-gradient norm sum_l N_{i,l}^2 in binary64: the tensors are taken in */
-/* blocks of 1024, each block added in index order, then the block sums added in index order.  */
-/* Up to 1024 tensors this is the plain running sum; beyond that it is the same sum with the   */
-/* parentheses moved (the paper says nothing about the order of a sum), chosen so that a       */
-/* gradient cut into tens of thousands of buckets can be summed by many lanes at once.          */
-#define DQO_SUM_BLOCK 1024
+/* A worker's squared whole-gradient norm ||g^(i)||^2 = sum_l N_{i,l}^2 (the term Lemma 1       */
+/* averages over workers into G-bar_t^2): a plain running sum in binary64, tensors in index      */
+/* order.  The squares of binary32 norms are exact in binary64.                                  */
 static double worker_squared_norm(const float *row, int32_t n_seg)
 {
     double total = 0.0;
-    for (int32_t base = 0; base < n_seg; base += DQO_SUM_BLOCK) {
-        double block = 0.0;
-        for (int32_t l = base; l < n_seg && l < base + DQO_SUM_BLOCK; ++l) {
-            double n = (double)row[l];
-            block += n * n;
-        }
-        total += block;
+    for (int32_t l = 0; l < n_seg; ++l) {
+        double n = (double)row[l];
+        total += n * n;
     }
     return total;
 }

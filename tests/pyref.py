@@ -55,3 +55,26 @@ def quantize_element(g, N, b, P, worker, step, seed):
     _, lo, p = scaled_magnitude(g, N, b)
     u = Fraction(element_random_word(P, worker, step, seed) >> 8, 1 << 24)
     return sign, lo + (1 if u < p else 0)
+
+
+def single_width_rule_agrees(got, want, n_seg, factor, b_min, b_max):
+    """Validity check for a (b, G-bar) pair against the oracle's when the two sides may add a worker's
+    sum_l N_l^2 (Lemma 1's G-bar_t^2) in different orders.  Each binary64 sum of n_seg non-negative
+    terms is within (n_seg - 1) * 2^-53 relative of the exact one, so G-bar (a square root: half the
+    relative error, plus the roundings of the mean and the root) agrees to (n_seg + 4) * 2^-53
+    relative.  The widths must be equal unless s* = factor * G-bar lies within that relative distance
+    of a level count 2^b - 1 (Eq. (17) rounded up), where either neighbouring width is correct."""
+    (b_got, g_got), (b_want, g_want) = got, want
+    rel = (n_seg + 4) * 2.0 ** -53
+    if abs(g_got - g_want) > rel * g_want:
+        return False
+    if b_got == b_want:
+        return True
+    lo, hi = sorted((int(b_got), int(b_want)))
+    levels = float((1 << lo) - 1)
+    return hi == lo + 1 and b_min <= lo and hi <= b_max and abs(factor * g_want - levels) <= 2 * rel * levels
+
+
+def rule_factor(t, T, eps_hat_q, alpha):
+    """sqrt(T/eps_hat_q) * alpha^((T-1-t)/2), the factor of Eq. (17) in front of G-bar."""
+    return (T / eps_hat_q) ** 0.5 * alpha ** ((T - 1 - t) / 2.0)

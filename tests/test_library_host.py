@@ -212,16 +212,27 @@ def test_newer_device_entry_points_validate_before_touching_a_gpu(dq):
 
 
 def test_rules_agree_with_the_oracle_beyond_one_summation_block(dq, oracle):
-    """more than 1024 tensors: a worker's squared norm is added block by block; host and oracle agree
-    bit for bit, and the value is the plain sum to rounding"""
+    """more than 1024 tensors: the library adds a worker's squared norm block by block, the oracle in
+    plain index order (Lemma 1's G-bar_t^2 as written).  Up to 1024 tensors the two orders coincide and
+    the results are equal bit for bit; beyond, G-bar agrees to the rounding of a binary64 sum and the
+    width is the same unless s* sits within that distance of a level count (either width is then valid)"""
+    from tests.pyref import rule_factor, single_width_rule_agrees
     rng = np.random.default_rng(9)
     for n_seg in (1024, 1025, 3000, 70000):
         M = 3
         norms = (10 ** rng.uniform(-4, 0, size=(M, n_seg))).astype(np.float32)
         got = dq.select_bits(norms, 2, 9, 1e-3, 0.9, 1, 8)
         want = oracle.select_bits(norms, 2, 9, 1e-3, 0.9, 1, 8)
-        assert got == want
+        if n_seg <= 1024:
+            assert got == want
+        assert single_width_rule_agrees(got, want, n_seg, rule_factor(2, 9, 1e-3, 0.9), 1, 8)
         plain = np.sqrt((norms.astype(np.float64) ** 2).sum() / M)
-        assert abs(got[1] - plain) <= 1e-13 * plain
-        assert np.array_equal(dq.select_bits_per_worker(norms, 2, 9, 1e-3, 0.9, 1, 8),
-                              oracle.select_bits_per_worker(norms, 2, 9, 1e-3, 0.9, 1, 8))
+        assert abs(want[1] - plain) <= 1e-13 * plain
+        b_got = dq.select_bits_per_worker(norms, 2, 9, 1e-3, 0.9, 1, 8)
+        b_want = oracle.select_bits_per_worker(norms, 2, 9, 1e-3, 0.9, 1, 8)
+        for i in range(M):
+            # a worker's own width (Eq. (17) with its own norm): same validity rule, worker by worker
+            n_i = float(np.sqrt((norms[i].astype(np.float64) ** 2).sum()))
+            assert len(set(b_got[i])) == 1 and len(set(b_want[i])) == 1
+            assert single_width_rule_agrees((b_got[i][0], n_i), (b_want[i][0], n_i), n_seg,
+                                            rule_factor(2, 9, 1e-3, 0.9), 1, 8)
