@@ -50,7 +50,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
 {
     if (!plan_out) return DQ_ERR_INVALID_ARG;
     *plan_out = nullptr;
-    if (!seg_len_host || n_seg < 1) return DQ_ERR_INVALID_ARG;
+    if (!seg_len_host || n_seg < 1 || n_seg == INT32_MAX) return DQ_ERR_INVALID_ARG; // tables hold n_seg + 1 entries
     int64_t total = 0;
     for (int32_t l = 0; l < n_seg; ++l) {
         if (seg_len_host[l] < 0 || seg_len_host[l] > (INT64_C(1) << 40)) return DQ_ERR_INVALID_ARG;
@@ -101,11 +101,14 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
     std::vector<int64_t> cseg_start;
     std::vector<int32_t> span_cseg;
     std::vector<int32_t> cseg_seg;
-    std::vector<int32_t> granule_cseg(static_cast<size_t>(total / DQ_GRANULE));
+    std::vector<int32_t> granule_cseg;
     std::vector<dq_norm_item> items;
-    std::vector<int32_t> item_begin(n_seg + 1);
+    std::vector<int32_t> item_begin;
     std::vector<int32_t> finish_seg;
     try {
+        // every allocation of the host tables happens in here: std::bad_alloc never leaves the call
+        granule_cseg.resize(static_cast<size_t>(total / DQ_GRANULE));
+        item_begin.resize(static_cast<size_t>(n_seg) + 1);
         items.reserve(static_cast<size_t>(n_items));
         for (int32_t l = 0; l < n_seg; ++l) {
             if (p->seg_len[l] > 0) {

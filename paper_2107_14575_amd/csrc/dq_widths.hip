@@ -134,7 +134,7 @@ __global__ __launch_bounds__(SB_THREADS) void k_rule_worker_sums(const float* __
 {
     const int tid = threadIdx.x;
     const float* row = norms + static_cast<int64_t>(blockIdx.x) * n_seg;
-    const int32_t n_blocks = (n_seg + DQ_SUM_BLOCK - 1) / DQ_SUM_BLOCK;
+    const int32_t n_blocks = (n_seg - 1) / DQ_SUM_BLOCK + 1;
     double* mine = block_sums + static_cast<int64_t>(blockIdx.x) * n_blocks;
     for (int32_t blk = tid; blk < n_blocks; blk += SB_THREADS) {
         const int32_t begin = blk * DQ_SUM_BLOCK;
@@ -318,7 +318,7 @@ int widths_create(const dq_plan_t* plan, int n_workers, dq_widths_t** widths_out
     ok = ok && hipHostMalloc(reinterpret_cast<void**>(&w->h_stage), bytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&w->uploaded, hipEventDisableTiming) == hipSuccess;
     // per-worker squared norms, followed by the block sums they are made of (multi-launch rules)
-    const size_t n_sum_blocks = static_cast<size_t>((plan->n_seg + DQ_SUM_BLOCK - 1) / DQ_SUM_BLOCK);
+    const size_t n_sum_blocks = static_cast<size_t>((static_cast<int64_t>(plan->n_seg) + DQ_SUM_BLOCK - 1) / DQ_SUM_BLOCK);
     ok = ok && hipMalloc(reinterpret_cast<void**>(&w->d_worker_sq),
                          sizeof(double) * DQ_MAX_WORKERS * (1 + n_sum_blocks)) == hipSuccess;
     if (ok) {
