@@ -94,6 +94,25 @@ int dq_norm(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride
 int dq_norm_linf(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems, int M,
                  float* norms_dev, void* workspace_dev, void* hip_stream);
 
+/* dq_norm (linf = 0) or dq_norm_linf (linf != 0) for callers that cannot allocate device memory --
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc -- and so have
+ * no workspace to hand over.  The partial results live in a fixed array inside the library instead
+ * (DQ_NORM_STATIC_SCRATCH_BYTES of device memory on every GPU the library is loaded on, held until
+ * the process ends); the call allocates and frees nothing and only enqueues the kernels of dq_norm,
+ * so norms_dev receives exactly dq_norm's values.
+ *   limit   dq_workspace_bytes(plan, M) <= DQ_NORM_STATIC_SCRATCH_BYTES, i.e. M * (number of
+ *           4096-element pieces of the tensors) <= 2^20 -- e.g. M = 16 workers of 2^28 elements;
+ *           DQ_ERR_INVALID_ARG beyond it (use dq_norm with a workspace of the caller's then).
+ *   sharing every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two
+ *           streams, two threads) race on it and give wrong norms; order them, or use dq_norm.
+ *           Nothing in the array has to be cleared between calls.
+ * The array's address is looked up when a plan is created on the GPU (at the latest by the first
+ * call), never during later calls.  Other arguments and errors as dq_norm. */
+#define DQ_NORM_STATIC_SCRATCH_BYTES (8 << 20)
+int64_t dq_norm_static_scratch_max_bytes(void);
+int dq_norm_static_scratch(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                           int M, int linf, float* norms_dev, void* hip_stream);
+
 /* The bit rule, Eq. (17), in level-bit convention.  Pure host code, no GPU work.
  *   Gbar^2 = (1/M) sum_i sum_l N[i][l]^2        (mean square of the workers' gradient norms, Lemma 1)
  *   s*     = sqrt(T/eps_hat_q) * alpha^((T-1-t)/2) * Gbar

@@ -20,7 +20,7 @@ EXPORTS = (
     "dq_plan_create", "dq_plan_destroy", "dq_plan_num_segments", "dq_plan_padded_elems", "dq_plan_segment_start",
     "dq_plan_has_device", "dq_plan_is_chunk_local", "dq_packed_bytes", "dq_packed_bytes_v", "dq_workspace_bytes",
     # the path
-    "dq_norm", "dq_norm_linf", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack",
+    "dq_norm", "dq_norm_linf", "dq_norm_static_scratch", "dq_norm_static_scratch_max_bytes", "dq_select_bits", "dq_select_bits_linf", "dq_quantize_pack",
     "dq_unpack_dequant_reduce", "dq_unpack_dequant_reduce_update", "dq_norm_quantize_pack",
     # widths per tensor / per worker, rules on the GPU
     "dq_select_bits_per_tensor", "dq_select_bits_per_worker", "dq_select_bits_device", "dq_widths_create",
@@ -85,6 +85,10 @@ def load_library():
     L.dq_norm.restype = C.c_int
     L.dq_norm_linf.argtypes = [vp, vp, i64, C.c_int, vp, vp, vp]
     L.dq_norm_linf.restype = C.c_int
+    L.dq_norm_static_scratch.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, vp]
+    L.dq_norm_static_scratch.restype = C.c_int
+    L.dq_norm_static_scratch_max_bytes.argtypes = []
+    L.dq_norm_static_scratch_max_bytes.restype = i64
     L.dq_select_bits.argtypes = [f32p, C.c_int, C.c_int, i64, i64, C.c_double, C.c_double,
                                  C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_double)]
     L.dq_select_bits.restype = C.c_int
@@ -242,6 +246,19 @@ def norm_linf(plan: Plan, grads, norms_out, workspace, stream=None) -> None:
     _check("dq_norm_linf", load_library().dq_norm_linf(plan.handle, grads.data_ptr(), stride, M,
                                                        norms_out.data_ptr(), workspace.data_ptr(),
                                                        _stream_handle(stream)))
+
+
+def norm_static_scratch(plan: Plan, grads, norms_out, linf: bool = False, stream=None) -> None:
+    """norm / norm_linf without a workspace: the partial sums live in a fixed array inside the library
+    (plan.workspace_bytes(M) must not exceed norm_static_scratch_max_bytes()); allocates nothing."""
+    M, stride = int(grads.shape[0]), int(grads.stride(0))
+    _check("dq_norm_static_scratch",
+           load_library().dq_norm_static_scratch(plan.handle, grads.data_ptr(), stride, M, 1 if linf else 0,
+                                                 norms_out.data_ptr(), _stream_handle(stream)))
+
+
+def norm_static_scratch_max_bytes() -> int:
+    return int(load_library().dq_norm_static_scratch_max_bytes())
 
 
 def _select_bits(name, norms_host, t, T, eps_hat_q, alpha, b_min, b_max):

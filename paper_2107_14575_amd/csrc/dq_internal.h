@@ -111,6 +111,10 @@ static inline double dq_worker_squared_norm(const float* row, int32_t n_seg)
     return total;
 }
 
+// Looks up this GPU's copy of dq_norm_static_scratch's scratch array (`device` is the current
+// device), so that the entry point itself finds it ready.
+void dq_norm_static_scratch_prepare(int device);
+
 // Fills n floats with +0 (a kernel, not a memset: callers may capture the entry points in a graph).
 int dq_zero_floats(float* dst_dev, int64_t n, hipStream_t stream);
 

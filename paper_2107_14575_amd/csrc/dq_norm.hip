@@ -14,10 +14,36 @@
 //
 // Plans in which no tensor crosses a multiple of 4096 padded elements take k_norm_chunk instead:
 // one workgroup per chunk finishes the norms of all the tensors inside it, one pass.
+#include <atomic>
+
 #include "dq_chunk_norm.h"
 #include "dq_internal.h"
 
+// Scratch of dq_norm_static_scratch: the per-(item, worker) partial sums that dq_norm keeps in the
+// caller's workspace.  Every GPU the library runs on holds its own copy of this array until the
+// process ends.  In host code the name is only a stand-in: the device address of a GPU's copy
+// comes from hipGetSymbolAddress (static_scratch_of below) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[DQ_NORM_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[MAX_DEVICES]; // device address of `scratch` on each GPU, null until asked for
+
+// The current device's copy of `scratch`; `device` must be the current device.  Looked up once per
+// device (two threads that both find it missing look up the same address).
+void* static_scratch_of(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) return nullptr;
+    void* ptr = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (ptr) return ptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch_ptr[device].store(ptr, std::memory_order_release);
+    return ptr;
+}
 
 __device__ __forceinline__ double wave_sum(double v)
 {
@@ -266,6 +292,24 @@ extern "C" int dq_norm_linf(const dq_plan_t* plan, const float* grads_dev, int64
                             int M, float* norms_dev, void* workspace_dev, void* hip_stream)
 {
     return norm_entry(true, plan, grads_dev, worker_stride_elems, M, norms_dev, workspace_dev, hip_stream);
+}
+
+void dq_norm_static_scratch_prepare(int device) { (void)static_scratch_of(device); }
+
+extern "C" int64_t dq_norm_static_scratch_max_bytes(void) { return DQ_NORM_STATIC_SCRATCH_BYTES; }
+
+extern "C" int dq_norm_static_scratch(const dq_plan_t* plan, const float* grads_dev, int64_t worker_stride_elems,
+                                      int M, int linf, float* norms_dev, void* hip_stream)
+{
+    if (!plan) return DQ_ERR_INVALID_ARG;
+    const int64_t need = dq_workspace_bytes(plan, M);
+    if (need < 0 || need > DQ_NORM_STATIC_SCRATCH_BYTES) return DQ_ERR_INVALID_ARG;
+    const int rc = dq_plan_check_device(plan); // makes the plan's GPU current
+    if (rc != DQ_OK) return rc;
+    void* ptr = static_scratch_of(plan->device);
+    if (!ptr) return DQ_ERR_HIP;
+    // every partial a launch reads it has written itself: nothing in the scratch has to start at zero
+    return norm_entry(linf != 0, plan, grads_dev, worker_stride_elems, M, norms_dev, ptr, hip_stream);
 }
 
 namespace {

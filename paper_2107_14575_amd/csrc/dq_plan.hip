@@ -149,6 +149,7 @@ extern "C" int dq_plan_create(const int64_t* seg_len_host, int32_t n_seg, dq_pla
         return DQ_ERR_ALLOC;
     }
     p->device = dev;
+    dq_norm_static_scratch_prepare(dev); // set-up time: the allocation-free entry point then only launches
     p->n_cseg = static_cast<int32_t>(cseg_seg.size());
     p->n_finish = static_cast<int32_t>(finish_seg.size());
     p->n_span = static_cast<int32_t>(span_cseg.size());
