@@ -4,9 +4,16 @@
 //
 // Work split.  One workgroup (256 lanes) owns 8192 consecutive padded elements; a lane owns 32 of
 // them, so per worker it reads one sign dword and B level dwords -- every load is dword aligned
-// for every B -- and keeps 32 binary32 accumulators.  Per (worker, element): convert the level
-// (fields spread one per byte first when B divides 8, so the convert needs no extract), put the
-// sign bit on the worker's unit (shift, v_and_or), one FMA.
+// for every B -- and keeps 32 binary32 accumulators.
+//
+// Arithmetic per (worker, element).  B <= 4: the level fields are spread one per byte word-wise
+// (byte permutes and a shift/mask per four elements), the four sign bits of the word's elements go
+// onto bit 7 of its bytes with one shift and one and-or, and each byte -- (sign << 7) | level --
+// is converted as an 8-bit float, which is exactly +-level * 2^-9: half a conversion instruction
+// and one FMA per element, no sign handling per element (about 2.6-3.4 vector instructions per
+// worker and element against 4.5 with a conversion, a sign shift, a sign merge and an FMA each).
+// B >= 5 (bound by memory): convert the level (one v_cvt_f32_ubyteN at B = 8, a field extract and a
+// convert otherwise), put the sign bit on the worker's unit (shift, v_and_or), one FMA.
 //
 // The 32 results of a lane are consecutive in memory, so storing them directly would be 16-byte
 // pieces 128 bytes apart; they go through LDS (XOR-swizzled 16-byte slots, conflict free both
@@ -18,6 +25,8 @@
 //
 // With a model vector x the epilogue also applies the update of Algorithm 1, x <- x - eta * g_hat
 // (8 more bytes per element, read and written with the same coalesced 16-byte accesses).
+#include <utility>
+
 #include "dq_internal.h"
 
 namespace {
@@ -67,17 +76,96 @@ __device__ __forceinline__ void for_each_level(const uint32_t (&wd)[B], F&& f)
     }
 }
 
-// One worker's contribution to a lane's 32 elements: acc[k] += sgn_k * level_k * unit, from the
-// worker's sign dword and its B level dwords.
+// Widths 1 to 4 take the sign-and-level route below: the byte (sign << 7) | level, level <= 15,
+// read as an 8-bit float (E4M3: 4 exponent bits with bias 7, 3 fraction bits) is exactly
+// +-level * 2^-9 -- its subnormals and its first binade of normal numbers share one spacing -- so
+// one conversion instruction turns two such bytes into two signed binary32 levels, with no
+// separate sign handling per element.  Sums formed this way carry the factor 2^-9; the caller
+// takes it out together with 1/M (UR_FP8_SCALE).
+__host__ __device__ constexpr bool ur_fp8_width(int b) { return b >= 1 && b <= 4; }
+constexpr float UR_FP8_SCALE = 512.0f;
+// workers whose loads are issued together (measured per width at D = 2^28, M = 16)
+__host__ __device__ constexpr int ur_group(int b) { return b == 2 ? 16 : b == 3 ? 8 : 4; }
+
+// bytes of {hi, lo} picked by the four selector bytes of sel: 0..3 = bytes of lo, 4..7 = bytes of hi
+__device__ __forceinline__ uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel)
+{
+    return __builtin_amdgcn_perm(hi, lo, sel);
+}
+
+// t holds the levels (<= 15) of elements e, e+8, e+16, e+24 of the lane, one per byte; the sign bits
+// of those elements are bits e, e+8, e+16, e+24 of sg.  acc[.] += sgn * level * 2^-9 * unit.
+template <int E>
+__device__ __forceinline__ void fma_signed_bytes(uint32_t t, uint32_t sg, float unit, float (&acc)[UR_PER_LANE])
+{
+    const uint32_t coded = ((sg << (7 - E)) & 0x80808080u) | t; // sign bits onto bit 7 of each byte
+    const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(coded), false); // bytes 0, 1
+    const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(coded), true);  // bytes 2, 3
+    acc[E] = __builtin_fmaf(lo[0], unit, acc[E]);
+    acc[E + 8] = __builtin_fmaf(lo[1], unit, acc[E + 8]);
+    acc[E + 16] = __builtin_fmaf(hi[0], unit, acc[E + 16]);
+    acc[E + 24] = __builtin_fmaf(hi[1], unit, acc[E + 24]);
+}
+
+// Width 3: y[i] holds byte i of each of the lane's four 24-bit runs (eight 3-bit fields each); the
+// levels of elements E, E+8, E+16, E+24 one per byte.  Fields 2 and 5 of a run straddle two bytes.
+template <int E>
+__device__ __forceinline__ uint32_t level_bytes_b3(const uint32_t (&y)[3])
+{
+    constexpr int bit = 3 * E, word = bit >> 3, off = bit & 7;
+    if constexpr (off + 3 <= 8) {
+        return (y[word] >> off) & 0x07070707u;
+    } else {
+        constexpr uint32_t lo_mask = ((1u << (8 - off)) - 1u) * 0x01010101u;
+        constexpr uint32_t hi_mask = ((1u << (off + 3 - 8)) - 1u) * 0x01010101u;
+        return ((y[word] >> off) & lo_mask) | ((y[word + 1] & hi_mask) << (8 - off));
+    }
+}
+
+template <int B, int... E>
+__device__ __forceinline__ void accumulate_words_fp8(uint32_t sg, const uint32_t (&wd)[B], float unit,
+                                                     float (&acc)[UR_PER_LANE], std::integer_sequence<int, E...>)
+{
+    static_assert(sizeof...(E) == 8, "eight groups of four elements");
+    if constexpr (B == 1) {
+        // bit e + 8j of the one level dword is bit e of its byte j
+        (fma_signed_bytes<E>((wd[0] >> E) & 0x01010101u, sg, unit, acc), ...);
+    } else if constexpr (B == 2) {
+        // byte r of dword q holds elements 16q + 4r .. + 3: gather bytes r, r+2 of both dwords
+        const uint32_t q[2] = { byte_perm(wd[1], wd[0], 0x06040200u), byte_perm(wd[1], wd[0], 0x07050301u) };
+        (fma_signed_bytes<E>((q[E / 4] >> (2 * (E % 4))) & 0x03030303u, sg, unit, acc), ...);
+    } else if constexpr (B == 3) {
+        // the lane's 96 level bits are four runs of 24 (elements 8j .. 8j+7): gather byte i of every run
+        const uint32_t y[3] = { byte_perm(wd[2], byte_perm(wd[1], wd[0], 0x00060300u), 0x05020100u),
+                                byte_perm(wd[2], byte_perm(wd[1], wd[0], 0x00070401u), 0x06020100u),
+                                byte_perm(wd[2], byte_perm(wd[1], wd[0], 0x00000502u), 0x07040100u) };
+        (fma_signed_bytes<E>(level_bytes_b3<E>(y), sg, unit, acc), ...);
+    } else {
+        // byte r of dword j holds elements 8j + 2r, 8j + 2r + 1: transpose the 4x4 bytes so that word r
+        // holds byte r of every dword
+        const uint32_t ab_lo = byte_perm(wd[1], wd[0], 0x05010400u), ab_hi = byte_perm(wd[1], wd[0], 0x07030602u);
+        const uint32_t cd_lo = byte_perm(wd[3], wd[2], 0x05010400u), cd_hi = byte_perm(wd[3], wd[2], 0x07030602u);
+        const uint32_t p[4] = { byte_perm(cd_lo, ab_lo, 0x05040100u), byte_perm(cd_lo, ab_lo, 0x07060302u),
+                                byte_perm(cd_hi, ab_hi, 0x05040100u), byte_perm(cd_hi, ab_hi, 0x07060302u) };
+        (fma_signed_bytes<E>((p[E / 2] >> (4 * (E % 2))) & 0x0F0F0F0Fu, sg, unit, acc), ...);
+    }
+}
+
+// One worker's contribution to a lane's 32 elements from the worker's sign dword and its B level
+// dwords: acc[k] += sgn_k * level_k * unit, times 2^-9 when ur_fp8_width(B).
 template <int B>
 __device__ __forceinline__ void accumulate_words(uint32_t sg, const uint32_t (&wd)[B], float unit,
                                                  float (&acc)[UR_PER_LANE])
 {
-    for_each_level<B>(wd, [&](int k, float lv) {
-        // sign bit of element k on top of the unit, whose own sign bit is always clear
-        const float su = __uint_as_float(__float_as_uint(unit) | ((sg << (31 - k)) & 0x80000000u));
-        acc[k] = __builtin_fmaf(lv, su, acc[k]);
-    });
+    if constexpr (ur_fp8_width(B)) {
+        accumulate_words_fp8<B>(sg, wd, unit, acc, std::make_integer_sequence<int, 8>{});
+    } else {
+        for_each_level<B>(wd, [&](int k, float lv) {
+            // sign bit of element k on top of the unit, whose own sign bit is always clear
+            const float su = __uint_as_float(__float_as_uint(unit) | ((sg << (31 - k)) & 0x80000000u));
+            acc[k] = __builtin_fmaf(lv, su, acc[k]);
+        });
+    }
 }
 
 // The same from eight loaded dwords of which the first B count (per-worker widths).
@@ -120,22 +208,25 @@ __device__ __forceinline__ void accumulate_lane(const uint8_t* __restrict__ sign
             for (int q = 0; q < B; ++q) wd[q] = lp[q];
         }
     };
-    auto accumulate = [&](uint32_t sg, const uint32_t (&wd)[B], float unit) { accumulate_words<B>(sg, wd, unit, acc); };
-    // workers four at a time, so that four messages' loads are in flight together
-    constexpr int GROUP = 4;
+    // Workers in groups whose loads are all issued before the first is used: the pass is bound by
+    // memory latency once the arithmetic is cheap, so narrow widths (few registers per worker) take
+    // large groups.  Groups halve towards the end, so any M keeps its loads batched; the order of
+    // the additions is worker-ascending whatever the grouping.
+    auto group = [&](auto g, int w) {
+        constexpr int G = decltype(g)::value;
+        uint32_t sg[G], wd[G][B];
+#pragma unroll
+        for (int i = 0; i < G; ++i) load_worker(w + i, sg[i], wd[i]);
+#pragma unroll
+        for (int i = 0; i < G; ++i) accumulate_words<B>(sg[i], wd[i], unit_ptr[w + i], acc);
+    };
+    constexpr int GROUP = ur_group(B);
     int w = 0;
-    for (; w + GROUP <= M; w += GROUP) {
-        uint32_t sg[GROUP], wd[GROUP][B];
-#pragma unroll
-        for (int i = 0; i < GROUP; ++i) load_worker(w + i, sg[i], wd[i]);
-#pragma unroll
-        for (int i = 0; i < GROUP; ++i) accumulate(sg[i], wd[i], unit_ptr[w + i]);
-    }
-    for (; w < M; ++w) {
-        uint32_t sg, wd[B];
-        load_worker(w, sg, wd);
-        accumulate(sg, wd, unit_ptr[w]);
-    }
+    for (; w + GROUP <= M; w += GROUP) group(std::integral_constant<int, GROUP>{}, w);
+    if constexpr (GROUP > 8) if (w + 8 <= M) { group(std::integral_constant<int, 8>{}, w); w += 8; }
+    if constexpr (GROUP > 4) if (w + 4 <= M) { group(std::integral_constant<int, 4>{}, w); w += 4; }
+    if constexpr (GROUP > 2) if (w + 2 <= M) { group(std::integral_constant<int, 2>{}, w); w += 2; }
+    if (w < M) group(std::integral_constant<int, 1>{}, w);
 }
 
 // Scales a lane's sums by 1/M (zero beyond the tensor's end), transposes the workgroup's tile
@@ -220,7 +311,8 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
     if (active)
         accumulate_lane<B>(packed + (P0 >> 3), packed + (padded_elems >> 3) + (P0 >> 3) * B, packed_stride, M,
                            lds_unit + local * M, acc);
-    finish_tile<UPDATE>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
+    finish_tile<UPDATE>(acc, active, n_valid, ur_fp8_width(B) ? inv_M * UR_FP8_SCALE : inv_M, lds_out, tid, tile0,
+                        tile_end, out, x, eta);
 }
 
 // Per-tensor widths: each lane takes its segment's b and the place of its level dwords from the
@@ -285,7 +377,8 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_v(
         default: break; // the host only uploads widths in 1..8
         }
     }
-    finish_tile<UPDATE>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
+    finish_tile<UPDATE>(acc, active, n_valid, ur_fp8_width(b) ? inv_M * UR_FP8_SCALE : inv_M, lds_out, tid, tile0,
+                        tile_end, out, x, eta);
 }
 
 // Per-worker widths: every worker's message has its own layout, so a lane looks up b and the
@@ -323,7 +416,10 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_w(
         const float S = static_cast<float>((1 << e.b) - 1);
         const float N = norms[static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + local]];
         worker_entry we;
-        we.unit = N >= DQ_MIN_NORM ? N / S : 0.0f;
+        // every worker's sum is kept with the factor 2^-9 of the sign-and-level route: the widths that
+        // do not take it get the factor on their unit (exact: a usable norm is at least 2^-100)
+        const float unit = N >= DQ_MIN_NORM ? N / S : 0.0f;
+        we.unit = ur_fp8_width(e.b) ? unit : unit * (1.0f / UR_FP8_SCALE);
         we.b = e.b;
         we.level_base = e.level_start - (e.seg_start >> 3) * e.b; // seg_start is a multiple of 128
         lds_entry[i] = we;
@@ -379,7 +475,7 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_w(
             }
         }
     }
-    finish_tile<UPDATE>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, x, eta);
+    finish_tile<UPDATE>(acc, active, n_valid, inv_M * UR_FP8_SCALE, lds_out, tid, tile0, tile_end, out, x, eta);
 }
 
 // Sign-only messages (the one-bit baseline of the paper's Table 2): the mean of scale * sgn,
