@@ -300,3 +300,100 @@ def test_config5_other_entry_points_sampled(dq, oracle):
         assert torch.equal(results["majority"][c0:c0 + (1 << 26)], torch.sign(votes))
         assert float((results["mean"][c0:c0 + (1 << 26)] - votes / M).abs().max()) <= 1e-6
     plan.close()
+
+
+def test_config5_worker0_in_full_and_slices_of_every_worker(dq, oracle):
+    """Config 5 (D = 2^28, M = 16) against the oracle at depth, for b in {2, 4, 8} and for both
+    dq_quantize_pack and the single-pass dq_norm_quantize_pack_bracketed:
+      * worker 0's whole message (2^28 elements) byte for byte;
+      * a 2^24-element slice of every other worker, each at its own place along the gradient, byte for byte;
+      * the average on a common 2^24-element slice around the middle (codes of all 16 workers from the
+        oracle) element by element at the 1e-6 tolerance;
+      * b_t from dq_select_bits equal to the oracle's for the 20 steps of the benchmark's schedule;
+      * every worker's norm within 1 ulp of the oracle's.
+    Sample = 2^28 + 15 * 2^24 elements of bitstream per width and entry point (about 12 % of the 2^32)."""
+    D, M, SL = 1 << 28, 16, 1 << 24
+    seg_len, g = wl.flat_student_t(D=D, M=M, device="cuda")
+    plan = dq.Plan(seg_len)
+    norms_dev, ws, packed, out = _buffers(plan, M, b_max=8)
+    dq.norm(plan, g, norms_dev, ws)
+    torch.cuda.synchronize()
+    norms = norms_dev.cpu().numpy()
+    for i in range(M):
+        want = oracle.norm(seg_len, np.ascontiguousarray(g[i:i + 1].cpu().numpy()))
+        assert abs(float(norms[i, 0]) - float(want[0, 0])) <= np.spacing(want[0, 0]), i
+
+    # the rule over the benchmark's 20-step schedule (alpha = 0.9, eps_hat placing s* at 0.9 * 15 at the end)
+    T, alpha = 20, 0.9
+    gbar0 = float(np.sqrt((norms.astype(np.float64) ** 2).sum() / M))
+    eps_hat = T * (gbar0 / (0.9 * 15.0)) ** 2
+    seen = set()
+    for t in range(T):
+        got = dq.select_bits(norms, t, T, eps_hat, alpha, 2, 8)
+        assert got == oracle.select_bits(norms, t, T, eps_hat, alpha, 2, 8), t
+        seen.add(got[0])
+    assert len(seen) >= 2
+
+    # where each worker's slice lies: spread over the whole gradient, on 1024-element boundaries
+    own = [0] + [int(i * (D - SL) // (M - 1)) // 1024 * 1024 for i in range(1, M)]
+    mid = (D - SL) // 2
+
+    # jobs (worker, first index): worker 0 in sixteen pieces, one piece of every other worker; the oracle
+    # runs one job per host thread (its own loops are parallel over workers only)
+    jobs = [(0, k * SL) for k in range(D // SL)] + [(i, own[i]) for i in range(1, M)]
+    slices = {job: np.ascontiguousarray(g[job[0]:job[0] + 1, job[1]:job[1] + SL].cpu().numpy()) for job in jobs}
+
+    def check_messages(pk, norms_used, b, step, what):
+        from concurrent.futures import ThreadPoolExecutor
+
+        def expected(job):
+            i, p0 = job
+            sign, level = oracle.quantize_range(seg_len, slices[job], norms_used[i:i + 1], b, SEED, step, p0, p0 + SL,
+                                                worker_base=i)
+            return oracle.pack(sign[0], level[0], b)
+
+        with ThreadPoolExecutor(max_workers=16) as pool:
+            for (i, p0), want in zip(jobs, pool.map(expected, jobs)):
+                lv0 = D // 8 + p0 // 8 * b
+                assert np.array_equal(pk[i, p0 // 8:(p0 + SL) // 8].cpu().numpy(), want[:SL // 8]), (what, b, i, p0, "signs")
+                assert np.array_equal(pk[i, lv0:lv0 + SL // 8 * b].cpu().numpy(), want[SL // 8:]), (what, b, i, p0, "levels")
+
+    wsb = torch.empty(dq.bracketed_workspace_bytes(plan, M), dtype=torch.uint8, device="cuda")
+    lo, hi = torch.empty_like(norms_dev), torch.empty_like(norms_dev)
+    dq.norm_bracket(norms_dev, 0.125, lo, hi)
+    norms2_dev = torch.empty_like(norms_dev)
+    for b, step in ((2, 11), (4, 12), (8, 13)):
+        pk = packed[:, :plan.packed_bytes(b)]
+        dq.quantize_pack(plan, g, norms_dev, b, SEED, step, pk)
+        dq.unpack_dequant_reduce(plan, pk, norms_dev, b, out)
+        torch.cuda.synchronize()
+        check_messages(pk, norms, b, step, "dq_quantize_pack")
+        # the average on the common slice: every worker's codes there from the oracle
+        g_mid = np.ascontiguousarray(g[:, mid:mid + SL].cpu().numpy())
+        sign, level = oracle.quantize_range(seg_len, g_mid, norms, b, SEED, step, mid, mid + SL)
+        for i in range(M):
+            want = oracle.pack(sign[i], level[i], b)
+            lv0 = D // 8 + mid // 8 * b
+            assert np.array_equal(pk[i, mid // 8:(mid + SL) // 8].cpu().numpy(), want[:SL // 8]), (b, i)
+            assert np.array_equal(pk[i, lv0:lv0 + SL // 8 * b].cpu().numpy(), want[SL // 8:]), (b, i)
+        want_out = oracle.dequant_reduce_range(seg_len, sign, level, norms, b, mid, mid + SL)
+        got_out = out[mid:mid + SL].cpu().numpy()
+        s = float((1 << b) - 1)
+        mag = (level.astype(np.float64) * (norms[:, :1].astype(np.float64) / s)).sum(axis=0) / M
+        err = np.abs(got_out.astype(np.float64) - want_out)
+        assert np.all(err <= 1e-6 * mag + 1.5e-45), b
+        assert err.max() <= 1e-6 * np.abs(want_out).max()
+        del sign, level, g_mid
+        # the single pass with every norm bracketed to +-12.5 %: its own norms, the messages for them
+        pk2_full = torch.zeros_like(packed)
+        pk2 = pk2_full[:, :plan.packed_bytes(b)]
+        dq.norm_quantize_pack_bracketed(plan, g, lo, hi, b, SEED, step, norms2_dev, pk2, wsb)
+        torch.cuda.synchronize()
+        norms2 = norms2_dev.cpu().numpy()
+        assert np.all(np.abs(norms2.astype(np.float64) - norms.astype(np.float64)) <= np.spacing(norms))
+        if np.array_equal(norms2.view(np.uint32), norms.view(np.uint32)):
+            assert torch.equal(pk2, pk), ("dq_norm_quantize_pack_bracketed", b)   # same norms: the same messages
+        else:
+            check_messages(pk2, norms2, b, step, "dq_norm_quantize_pack_bracketed")
+        del pk2_full, pk2
+    plan.close()
