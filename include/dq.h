@@ -159,7 +159,11 @@ int dq_norm_quantize_pack(const dq_plan_t* plan, const float* grads_dev, int64_t
                           void* hip_stream);
 
 /* Server side of Algorithm 1: out_P = (1/M) sum_i sgn_{i,P} * level_{i,P} * (N[i][l] / s), every
- * worker's message read once.  The sum runs in binary32 over i ascending, then times 1/M.
+ * worker's message read once.  The sum runs in binary32: workers ascending inside blocks of eight
+ * (fused multiply-adds from zero), the block sums added in block order, then times 1/M -- at most
+ * 7 + ceil(M/8) + 1 roundings for any element, so the result is within (M/8 + 8) * 2^-24 <= 1e-6
+ * of the exact average of the dequantized terms, relative to their mean magnitude, for every
+ * M <= DQ_MAX_WORKERS.
  *   out_dev  [D'] float, written in full (pads +0.0f). */
 int dq_unpack_dequant_reduce(const dq_plan_t* plan, const uint8_t* packed_dev,
                              int64_t packed_worker_stride_bytes, int M, const float* norms_dev,
@@ -353,14 +357,6 @@ double dq_alpha_est(double F_t, double F_0, int64_t t);
  * paper has one norm per gradient; with per-tensor norms n_norms = n_seg).  b = 31 with
  * n_norms = 0 is uncompressed SGD.  Host code.  Returns -1 on a negative or out-of-range argument. */
 int64_t dq_comm_cost_bits(int W, int64_t d, int b, int32_t n_norms, int B_pre);
-
-/* Measurement aid, not a step of the method (for callers that report rooflines): a plain
- * streaming kernel with no arithmetic to speak of.  Each workgroup reads 16 KiB of src_dev with
- * 16-byte loads and writes pieces_per_wg (0..1024) 16-byte pieces derived from them to dst_dev,
- * contiguously; n_wg workgroups.  Reads n_wg*16384 bytes, writes n_wg*pieces_per_wg*16 bytes.
- * Timed by the caller, it gives the bandwidth this GPU reaches for a given read/write mix, the
- * practical ceiling next to the published HBM peak.  Both pointers 16-byte aligned. */
-int dq_probe_stream(const void* src_dev, void* dst_dev, int64_t n_wg, int pieces_per_wg, void* hip_stream);
 
 const char* dq_status_string(int status);
 

@@ -31,7 +31,10 @@
 
 namespace {
 
-constexpr int UR_THREADS = 256;
+#ifndef UR_THREADS_N
+#define UR_THREADS_N 256
+#endif
+constexpr int UR_THREADS = UR_THREADS_N;
 constexpr int UR_PER_LANE = 32;
 constexpr int UR_TILE = UR_THREADS * UR_PER_LANE; // 8192 elements
 constexpr int UR_MAX_LOCAL_SEG = UR_TILE / DQ_GRANULE;
@@ -84,6 +87,10 @@ __device__ __forceinline__ void for_each_level(const uint32_t (&wd)[B], F&& f)
 // takes it out together with 1/M (UR_FP8_SCALE).
 __host__ __device__ constexpr bool ur_fp8_width(int b) { return b >= 1 && b <= 4; }
 constexpr float UR_FP8_SCALE = 512.0f;
+// the 32 KiB output tile in LDS allows four workgroups per CU, i.e. four wavefronts per SIMD: the register
+// budget is held to what keeps that many resident
+constexpr int UR_MIN_WAVES = 4;
+constexpr int UR_SUM_BLOCK = 8; // workers per block of the two-level sum (a power of two)
 // workers whose loads are issued together (measured per width at D = 2^28, M = 16)
 __host__ __device__ constexpr int ur_group(int b) { return b == 2 ? 16 : b == 3 ? 8 : 4; }
 
@@ -179,13 +186,61 @@ __device__ __forceinline__ void accumulate_first_words(uint32_t sg, const uint32
     accumulate_words<B>(sg, wd, unit, acc);
 }
 
+// A lane's eight 16-byte slots of the workgroup's output tile in LDS (XOR-swizzled: conflict free for
+// the lane's own accesses and for the transposed read of finish_tile).  Before that read a lane's
+// slots are its own, so it also keeps the running total of its block sums there.
+struct lane_slots {
+    float4* wave_out; // this wavefront's 512 slots
+    int lane;
+    __device__ __forceinline__ float4& operator[](int q) const { return wave_out[lane * 8 + (q ^ (lane & 7))]; }
+};
+__device__ __forceinline__ lane_slots slots_of(float4* lds_out, int tid)
+{
+    return lane_slots{ lds_out + (tid >> 6) * 512, tid & 63 };
+}
+
+// Sum of blocks, kept without a second set of 32 registers: every block but the last is added to the
+// lane's slots (the first one stored), and the accumulators start the next block from zero.
+struct block_total {
+    lane_slots slots;
+    int n_flushed = 0;
+    __device__ __forceinline__ void flush(float (&acc)[UR_PER_LANE])
+    {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            float4 t = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+            if (n_flushed) {
+                const float4 o = slots[q];
+                t = make_float4(o.x + t.x, o.y + t.y, o.z + t.z, o.w + t.w);
+            }
+            slots[q] = t;
+            acc[4 * q] = acc[4 * q + 1] = acc[4 * q + 2] = acc[4 * q + 3] = 0.0f;
+        }
+        ++n_flushed;
+    }
+    // total of the flushed blocks plus the block still in the accumulators
+    __device__ __forceinline__ void finish(float (&acc)[UR_PER_LANE]) const
+    {
+        if (!n_flushed) return;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const float4 o = slots[q];
+            acc[4 * q] = o.x + acc[4 * q];
+            acc[4 * q + 1] = o.y + acc[4 * q + 1];
+            acc[4 * q + 2] = o.z + acc[4 * q + 2];
+            acc[4 * q + 3] = o.w + acc[4 * q + 3];
+        }
+    }
+};
+
 // The M workers' contributions to a lane's 32 elements: acc[k] += sgn * level * unit, workers in
 // ascending order.  sign_ptr / level_ptr address worker 0's sign dword and B level dwords of the
 // lane; unit_ptr[w] is worker w's N/s for the lane's segment.
 template <int B>
 __device__ __forceinline__ void accumulate_lane(const uint8_t* __restrict__ sign_ptr,
                                                 const uint8_t* __restrict__ level_ptr, int64_t packed_stride,
-                                                int M, const float* unit_ptr, float (&acc)[UR_PER_LANE])
+                                                int M, const float* unit_ptr, float (&acc)[UR_PER_LANE],
+                                                lane_slots slots)
 {
     // one worker's sign dword and B level dwords of this lane
     auto load_worker = [&](int w, uint32_t& sg, uint32_t (&wd)[B]) {
@@ -210,15 +265,29 @@ __device__ __forceinline__ void accumulate_lane(const uint8_t* __restrict__ sign
     };
     // Workers in groups whose loads are all issued before the first is used: the pass is bound by
     // memory latency once the arithmetic is cheap, so narrow widths (few registers per worker) take
-    // large groups.  Groups halve towards the end, so any M keeps its loads batched; the order of
-    // the additions is worker-ascending whatever the grouping.
-    auto group = [&](auto g, int w) {
+    // large groups.  Groups halve towards the end, so any M keeps its loads batched.
+    //
+    // Order of the additions: workers ascending inside blocks of UR_SUM_BLOCK workers (an FMA chain
+    // from zero), the block sums added in block order.  However the loads are grouped, a value
+    // passes through at most 7 + ceil(M/8) roundings: 15 at M = 64, where a single chain over all
+    // workers would take 63 (and measurably leaves the 1e-6 tolerance when one worker's norm
+    // dominates).  Up to eight workers nothing is flushed: the plain chain.
+    block_total total{ slots };
+    auto group = [&](auto g, int w) { // w is a multiple of G
         constexpr int G = decltype(g)::value;
         uint32_t sg[G], wd[G][B];
 #pragma unroll
         for (int i = 0; i < G; ++i) load_worker(w + i, sg[i], wd[i]);
 #pragma unroll
-        for (int i = 0; i < G; ++i) accumulate_words<B>(sg[i], wd[i], unit_ptr[w + i], acc);
+        for (int i = 0; i < G; ++i) {
+            accumulate_words<B>(sg[i], wd[i], unit_ptr[w + i], acc);
+            if constexpr (G >= UR_SUM_BLOCK) {
+                if ((i + 1) % UR_SUM_BLOCK == 0 && w + i + 1 < M) total.flush(acc);
+            }
+        }
+        if constexpr (G < UR_SUM_BLOCK) {
+            if (((w + G) & (UR_SUM_BLOCK - 1)) == 0 && w + G < M) total.flush(acc);
+        }
     };
     constexpr int GROUP = ur_group(B);
     int w = 0;
@@ -227,6 +296,7 @@ __device__ __forceinline__ void accumulate_lane(const uint8_t* __restrict__ sign
     if constexpr (GROUP > 4) if (w + 4 <= M) { group(std::integral_constant<int, 4>{}, w); w += 4; }
     if constexpr (GROUP > 2) if (w + 2 <= M) { group(std::integral_constant<int, 2>{}, w); w += 2; }
     if (w < M) group(std::integral_constant<int, 1>{}, w);
+    total.finish(acc);
 }
 
 // Scales a lane's sums by 1/M (zero beyond the tensor's end), transposes the workgroup's tile
@@ -270,7 +340,7 @@ __device__ __forceinline__ void finish_tile(float (&acc)[UR_PER_LANE], bool acti
 }
 
 template <int B, bool UPDATE>
-__global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
+__global__ __launch_bounds__(UR_THREADS, UR_MIN_WAVES) void k_unpack_dequant_reduce(
     const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
     int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
     const int64_t* __restrict__ cseg_valid_end, int64_t padded_elems, float inv_M, float* __restrict__ out,
@@ -310,7 +380,7 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
 
     if (active)
         accumulate_lane<B>(packed + (P0 >> 3), packed + (padded_elems >> 3) + (P0 >> 3) * B, packed_stride, M,
-                           lds_unit + local * M, acc);
+                           lds_unit + local * M, acc, slots_of(lds_out, tid));
     finish_tile<UPDATE>(acc, active, n_valid, ur_fp8_width(B) ? inv_M * UR_FP8_SCALE : inv_M, lds_out, tid, tile0,
                         tile_end, out, x, eta);
 }
@@ -320,7 +390,7 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce(
 // 128-element granule, hence in one segment; lanes of a wave differ in b only where a wave
 // straddles two tensors.
 template <bool UPDATE>
-__global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_v(
+__global__ __launch_bounds__(UR_THREADS, UR_MIN_WAVES) void k_unpack_dequant_reduce_v(
     const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
     int32_t n_seg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
     const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths, int64_t padded_elems,
@@ -366,14 +436,14 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_v(
         const uint8_t* level_ptr = packed + (padded_elems >> 3) + level_off;
         const float* unit_ptr = lds_unit + local * M;
         switch (b) {
-        case 1: accumulate_lane<1>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
-        case 2: accumulate_lane<2>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
-        case 3: accumulate_lane<3>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
-        case 4: accumulate_lane<4>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
-        case 5: accumulate_lane<5>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
-        case 6: accumulate_lane<6>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
-        case 7: accumulate_lane<7>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
-        case 8: accumulate_lane<8>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc); break;
+        case 1: accumulate_lane<1>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc, slots_of(lds_out, tid)); break;
+        case 2: accumulate_lane<2>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc, slots_of(lds_out, tid)); break;
+        case 3: accumulate_lane<3>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc, slots_of(lds_out, tid)); break;
+        case 4: accumulate_lane<4>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc, slots_of(lds_out, tid)); break;
+        case 5: accumulate_lane<5>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc, slots_of(lds_out, tid)); break;
+        case 6: accumulate_lane<6>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc, slots_of(lds_out, tid)); break;
+        case 7: accumulate_lane<7>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc, slots_of(lds_out, tid)); break;
+        case 8: accumulate_lane<8>(sign_ptr, level_ptr, packed_stride, M, unit_ptr, acc, slots_of(lds_out, tid)); break;
         default: break; // the host only uploads widths in 1..8
         }
     }
@@ -391,7 +461,7 @@ struct worker_entry { // what a lane needs to decode one worker's tensor: 16 byt
 };
 
 template <bool UPDATE>
-__global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_w(
+__global__ __launch_bounds__(UR_THREADS, UR_MIN_WAVES) void k_unpack_dequant_reduce_w(
     const uint8_t* __restrict__ packed, int64_t packed_stride, int M, const float* __restrict__ norms,
     int32_t n_seg, int32_t n_cseg, const int32_t* __restrict__ granule_cseg, const int32_t* __restrict__ cseg_seg,
     const int64_t* __restrict__ cseg_valid_end, const dq_cseg_width* __restrict__ widths, int64_t padded_elems,
@@ -443,6 +513,7 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_w(
         // workers four at a time: sign dwords and up to eight level dwords each are fetched first
         // (loads past a worker's width are skipped), then decoded width by width
         constexpr int GROUP = 4;
+        block_total total{ slots_of(lds_out, tid) }; // the block sums of accumulate_lane: same order of additions
         for (int w0 = 0; w0 < M; w0 += GROUP) {
             uint32_t sg[GROUP], wd[GROUP][8];
             worker_entry we[GROUP];
@@ -473,9 +544,21 @@ __global__ __launch_bounds__(UR_THREADS) void k_unpack_dequant_reduce_w(
                 default: break; // past the last worker, or a width the host never uploads
                 }
             }
+            if (((w0 + GROUP) & (UR_SUM_BLOCK - 1)) == 0 && w0 + GROUP < M) total.flush(acc);
         }
+        total.finish(acc);
     }
     finish_tile<UPDATE>(acc, active, n_valid, inv_M * UR_FP8_SCALE, lds_out, tid, tile0, tile_end, out, x, eta);
+}
+
+// acc[k] += sgn_k * scale for a lane's 32 elements: the scale with its sign flipped where the bit is set.
+// (The conversion route of the quantized average -- (sign << 7) | 0x38 is +-1 as an 8-bit float -- was
+// measured here too: 0.40 ms against 0.35 ms at D = 2^28, M = 16, so the integer form stays.)
+__device__ __forceinline__ void add_signed_scale(uint32_t sg, float scale, float (&acc)[UR_PER_LANE])
+{
+    const uint32_t unit = __float_as_uint(scale);
+#pragma unroll
+    for (int k = 0; k < UR_PER_LANE; ++k) acc[k] += __uint_as_float(unit ^ ((sg << (31 - k)) & 0x80000000u));
 }
 
 // Sign-only messages (the one-bit baseline of the paper's Table 2): the mean of scale * sgn,
@@ -526,19 +609,11 @@ __global__ __launch_bounds__(UR_THREADS) void k_sign_reduce_scaled(
             for (int i = 0; i < GROUP; ++i)
                 sg[i] = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w + i) * packed_stride);
 #pragma unroll
-            for (int i = 0; i < GROUP; ++i) {
-                const uint32_t unit = __float_as_uint(unit_ptr[w + i]);
-#pragma unroll
-                for (int k = 0; k < UR_PER_LANE; ++k) // flip the scale's sign where the element's bit is set
-                    acc[k] += __uint_as_float(unit ^ ((sg[i] << (31 - k)) & 0x80000000u));
-            }
+            for (int i = 0; i < GROUP; ++i) add_signed_scale(sg[i], unit_ptr[w + i], acc);
         }
         for (; w < M; ++w) {
             const uint32_t sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
-            const uint32_t unit = __float_as_uint(unit_ptr[w]);
-#pragma unroll
-            for (int k = 0; k < UR_PER_LANE; ++k)
-                acc[k] += __uint_as_float(unit ^ ((sg << (31 - k)) & 0x80000000u));
+            add_signed_scale(sg, unit_ptr[w], acc);
         }
     }
     finish_tile<false>(acc, active, n_valid, inv_M, lds_out, tid, tile0, tile_end, out, nullptr, 0.0f);
@@ -680,6 +755,19 @@ int reduce_entry_v(const dq_plan_t* plan, const dq_widths_t* widths, const uint8
     const float inv_M = 1.0f / static_cast<float>(M);
     if (widths->n_workers != 1) {
         const size_t lds_w = UR_TILE * sizeof(float) + static_cast<size_t>(UR_MAX_LOCAL_SEG) * M * sizeof(worker_entry);
+        // beyond 64 KiB of LDS per workgroup (M > 32) the kernel has to be told, and the GPU has to have it
+        if (lds_w > 64 * 1024) {
+            int max_lds = 0;
+            if (hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, plan->device) != hipSuccess)
+                return DQ_ERR_HIP;
+            if (lds_w > static_cast<size_t>(max_lds)) return DQ_ERR_INVALID_ARG;
+            const void* fn = x_dev ? reinterpret_cast<const void*>(&k_unpack_dequant_reduce_w<true>)
+                                   : reinterpret_cast<const void*>(&k_unpack_dequant_reduce_w<false>);
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_w)) != hipSuccess) {
+                (void)hipGetLastError();
+                return DQ_ERR_HIP;
+            }
+        }
         if (x_dev)
             hipLaunchKernelGGL(k_unpack_dequant_reduce_w<true>, grid, block, lds_w, stream, packed_dev,
                                packed_worker_stride_bytes, M, norms_dev, plan->n_seg, plan->n_cseg,
