@@ -28,7 +28,6 @@ from .binding import (  # noqa: F401
     norm_quantize_pack_bracketed,
     norm_quantize_pack_bracketed_v,
     norm_quantize_pack_v,
-    probe_stream,
     quantize_pack,
     select_bits,
     select_bits_device,
@@ -41,5 +40,5 @@ from .binding import (  # noqa: F401
 
 __all__ = ["DQError", "Plan", "Widths", "comm_cost_bits_per_tensor", "packed_bytes_v", "quantize_pack_v",
            "select_bits_per_tensor", "select_bits_per_worker", "unpack_dequant_reduce_update_v", "unpack_dequant_reduce_v", "alpha_est", "comm_cost_bits", "library_path", "load_library", "norm", "norm_linf", "norm_static_scratch", "norm_static_scratch_max_bytes", "norm_quantize_pack", "norm_quantize_pack_v", "norm_quantize_pack_bracketed", "norm_quantize_pack_bracketed_v", "bracketed_workspace_bytes", "norm_bracket",
-           "probe_stream", "quantize_pack", "select_bits", "select_bits_device", "select_bits_linf", "sign_majority", "sign_pack", "sign_reduce", "unpack_dequant_reduce",
+           "quantize_pack", "select_bits", "select_bits_device", "select_bits_linf", "sign_majority", "sign_pack", "sign_reduce", "unpack_dequant_reduce",
            "unpack_dequant_reduce_update"]

@@ -32,7 +32,7 @@ EXPORTS = (
     # sign-only baseline
     "dq_sign_pack", "dq_sign_reduce", "dq_sign_majority",
     # accounting and aids
-    "dq_alpha_est", "dq_comm_cost_bits", "dq_comm_cost_bits_per_tensor", "dq_probe_stream", "dq_status_string",
+    "dq_alpha_est", "dq_comm_cost_bits", "dq_comm_cost_bits_per_tensor", "dq_status_string",
 )
 
 
@@ -156,8 +156,6 @@ def load_library():
     L.dq_alpha_est.restype = C.c_double
     L.dq_comm_cost_bits.argtypes = [C.c_int, i64, C.c_int, i32, C.c_int]
     L.dq_comm_cost_bits.restype = i64
-    L.dq_probe_stream.argtypes = [vp, vp, i64, C.c_int, vp]
-    L.dq_probe_stream.restype = C.c_int
     L.dq_status_string.argtypes = [C.c_int]
     L.dq_status_string.restype = C.c_char_p
     _lib = L
@@ -342,16 +340,6 @@ def unpack_dequant_reduce(plan: Plan, packed, norms, b: int, out, stream=None) -
            load_library().dq_unpack_dequant_reduce(plan.handle, packed.data_ptr(), int(packed.stride(0)), M,
                                                    norms.data_ptr(), b, out.data_ptr(),
                                                    _stream_handle(stream)))
-
-
-def probe_stream(src, dst, n_wg: int, pieces_per_wg: int, stream=None) -> None:
-    """Measurement aid: plain streaming kernel, 16 KiB read per workgroup from `src`,
-    `pieces_per_wg` 16-byte pieces written to `dst` (CUDA tensors large enough for both)."""
-    if src.numel() * src.element_size() < n_wg * 16384 or \
-            dst.numel() * dst.element_size() < max(n_wg * pieces_per_wg * 16, 16):
-        raise ValueError("probe buffers too small")
-    _check("dq_probe_stream", load_library().dq_probe_stream(src.data_ptr(), dst.data_ptr(), n_wg,
-                                                             pieces_per_wg, _stream_handle(stream)))
 
 
 def unpack_dequant_reduce_update(plan: Plan, packed, norms, b: int, eta: float, x, ghat=None, stream=None) -> None:

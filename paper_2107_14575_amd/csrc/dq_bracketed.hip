@@ -96,12 +96,8 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
 
     const int32_t seg_first = gseg[0];
     const int32_t seg_last = gseg[(n_elems - 1) >> 7];
-    if (tid == 0) {
-        lds_count = 0;
-        lds_any_whole = 0;
-    }
-    int unusable = 0;
-    if (static_cast<int32_t>(tid) <= seg_last - seg_first) { // lanes of the first wavefront, after lane 0's stores above
+    int unusable = 0, whole_here = 0;
+    if (static_cast<int32_t>(tid) <= seg_last - seg_first) { // at most 32 lanes, all in the first wavefront
         const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid];
         const int64_t valid_end = cseg_valid_end[seg_first + tid];
         const bool whole = cseg_start[seg_first + tid] >= chunk0 && valid_end <= chunk0 + CHUNK;
@@ -111,10 +107,16 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
         lds_scale_hi[tid] = ok ? S / lo : 0.0f; // replaced below for a tensor that is whole
         lds_scale_lo[tid] = ok ? S / hi : 0.0f;
         lds_whole[tid] = whole ? 1 : 0;
-        if (whole) lds_any_whole = 1;
+        whole_here = whole ? 1 : 0;
         unusable = (ok || whole) ? 0 : 1;
         const int64_t rel = valid_end - chunk0;
         lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+    }
+    // one lane writes both words: the first wavefront's vote says whether any tensor is whole
+    const bool first_wave_any_whole = __ballot(whole_here) != 0;
+    if (tid == 0) {
+        lds_count = 0;
+        lds_any_whole = first_wave_any_whole ? 1 : 0;
     }
     const int skip = __syncthreads_or(unusable); // also the barrier after the tables
     const bool any_whole = lds_any_whole != 0;
@@ -268,12 +270,8 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed_v(
     const int32_t seg_last = gseg[(n_elems - 1) >> 7];
     const dq_cseg_width first = widths[seg_first];
     const int64_t chunk_level0 = first.level_start + ((chunk0 - first.seg_start) >> 3) * first.b;
-    if (tid == 0) {
-        lds_count = 0;
-        lds_any_whole = 0;
-    }
-    int unusable = 0;
-    if (static_cast<int32_t>(tid) <= seg_last - seg_first) {
+    int unusable = 0, whole_here = 0;
+    if (static_cast<int32_t>(tid) <= seg_last - seg_first) { // at most 32 lanes, all in the first wavefront
         const dq_cseg_width e = widths[seg_first + tid];
         const float S = static_cast<float>((1 << e.b) - 1);
         const int64_t at = static_cast<int64_t>(w) * n_seg + cseg_seg[seg_first + tid];
@@ -287,10 +285,15 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed_v(
         lds_b[tid] = e.b;
         lds_level_base[tid] = static_cast<int32_t>(e.level_start + ((chunk0 - e.seg_start) >> 3) * e.b - chunk_level0);
         lds_whole[tid] = whole ? 1 : 0;
-        if (whole) lds_any_whole = 1;
+        whole_here = whole ? 1 : 0;
         unusable = (ok || whole) ? 0 : 1;
         const int64_t rel = valid_end - chunk0;
         lds_valid_end[tid] = rel < CHUNK ? static_cast<int32_t>(rel) : CHUNK;
+    }
+    const bool first_wave_any_whole = __ballot(whole_here) != 0;
+    if (tid == 0) {
+        lds_count = 0;
+        lds_any_whole = first_wave_any_whole ? 1 : 0;
     }
     const int skip = __syncthreads_or(unusable);
     const bool any_whole = lds_any_whole != 0;

@@ -135,10 +135,9 @@ def run(plan: _b.Plan, x0: "torch.Tensor", grad_fn: Callable[[int, "torch.Tensor
             b_guess = b
             if not lagged:
                 # Eq. (17) never decreases in any norm, so if both ends of the bracket give the same b,
-                # every set of norms inside it does; norms_host still holds the previous iteration's.
-                n_prev = norms_host.numpy()
-                b_lo = rule(n_prev * _np.float32(1.0 - norm_margin), t, T, eps_hat_q, cur_alpha, b_min, b_max)[0]
-                b_hi = rule(n_prev * _np.float32(1.0 + norm_margin), t, T, eps_hat_q, cur_alpha, b_min, b_max)[0]
+                # every set of norms inside it does; the ends are the ones dq_norm_bracket has just written.
+                b_lo = rule(lo.cpu().numpy(), t, T, eps_hat_q, cur_alpha, b_min, b_max)[0]
+                b_hi = rule(hi.cpu().numpy(), t, T, eps_hat_q, cur_alpha, b_min, b_max)[0]
                 b_guess = b_lo if b_lo == b_hi else None
             if b_guess is None:
                 norm_fn(plan, grads, norms, ws)
@@ -215,7 +214,7 @@ def _run_per_tensor(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b
         res.bits.append(b.copy())
         res.cost_bits += _b.comm_cost_bits_per_tensor(M, plan.seg_len, b, B_pre)
         torch.cuda.current_stream().synchronize()
-        res.gbar.append(float(np.sqrt((norms_host.numpy().astype(np.float64) ** 2).sum() / M)))
+        res.gbar.append(_b.select_bits(norms_host.numpy(), t, T, eps_hat_q, float(alpha), b_min, b_max)[1])  # G-bar_t of Lemma 1
         if lagged and t + 1 < T and (t + 1) % tau == 0:
             b, _ = _b.select_bits_per_tensor(norms_host.numpy(), t + 1, T, eps_hat_q, float(alpha), b_min, b_max)
             table.set(b)
@@ -339,7 +338,7 @@ def _run_per_worker(plan, x0, grad_fn, M, T, eta, eps_hat_q, alpha, b0, b_min, b
         res.bits.append(b.copy())
         res.cost_bits += sum(_b.comm_cost_bits_per_tensor(1, plan.seg_len, b[i], B_pre) for i in range(M))
         torch.cuda.current_stream().synchronize()
-        res.gbar.append(float(np.sqrt((norms_host.numpy().astype(np.float64) ** 2).sum() / M)))
+        res.gbar.append(_b.select_bits(norms_host.numpy(), t, T, eps_hat_q, float(alpha), b_min, b_max)[1])  # G-bar_t of Lemma 1
         if lagged and t + 1 < T and (t + 1) % tau == 0:
             b = _b.select_bits_per_worker(norms_host.numpy(), t + 1, T, eps_hat_q, float(alpha), b_min, b_max,
                                           per_tensor)

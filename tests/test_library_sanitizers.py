@@ -1,6 +1,6 @@
 """The library's host code under AddressSanitizer and UndefinedBehaviorSanitizer: the host pass of
 hipcc is instrumented (the device pass is not: GPU sanitizers are not used), the driver
-csrc/host_sanitize_check.cpp is linked with the library's sources and run on the CPU."""
+tests/host_sanitize_check.cpp is linked with the library's sources and run on the CPU."""
 import glob
 import os
 import subprocess
@@ -20,7 +20,7 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
            "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
            "-Xarch_host", "-fno-sanitize-recover=undefined", "-static-libsan",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           os.path.join(CSRC, "host_sanitize_check.cpp"), *sorted(glob.glob(os.path.join(CSRC, "*.hip"))), "-o", exe]
+           os.path.join(ROOT, "tests", "host_sanitize_check.cpp"), *sorted(glob.glob(os.path.join(CSRC, "*.hip"))), "-o", exe]
     build = subprocess.run(cmd, capture_output=True, text=True)
     assert build.returncode == 0, build.stdout + build.stderr
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", UBSAN_OPTIONS="print_stacktrace=1")

@@ -1,5 +1,5 @@
 """The oracle under AddressSanitizer and UndefinedBehaviorSanitizer (host code only): builds
-oracle/dqo.c with oracle/sanitize_check.c and runs the driver on the CPU."""
+oracle/dqo.c with tests/oracle_sanitize_check.c and runs the driver on the CPU."""
 import os
 import shutil
 import subprocess
@@ -14,7 +14,7 @@ def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
     exe = str(tmp_path / "sanitize_check")
     cmd = ["gcc", "-O1", "-g", "-std=c99", "-ffp-contract=off", "-fno-omit-frame-pointer",
            "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-static-libasan", "-static-libubsan",
-           os.path.join(ROOT, "oracle", "dqo.c"), os.path.join(ROOT, "oracle", "sanitize_check.c"), "-o", exe, "-lm"]
+           os.path.join(ROOT, "oracle", "dqo.c"), os.path.join(ROOT, "tests", "oracle_sanitize_check.c"), "-o", exe, "-lm"]
     build = subprocess.run(cmd, capture_output=True, text=True)
     if build.returncode != 0 and "cannot find" in build.stderr:
         pytest.skip("static sanitizer runtimes are not installed")
