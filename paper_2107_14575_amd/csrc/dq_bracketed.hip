@@ -202,12 +202,12 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
     {
         uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
         const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
-        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
     }
     {
         uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + (chunk0 >> 3) * B);
         const uint4* src = reinterpret_cast<const uint4*>(lds_level);
-        for (uint32_t i = tid; i < n_elems / 128 * B; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < n_elems / 128 * B; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
     }
     if (tid == 0) {
         blk->count = lds_count;
@@ -390,14 +390,14 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed_v(
     {
         uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
         const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
-        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
     }
     {
         const int last = seg_last - seg_first;
         const uint32_t level_bytes = static_cast<uint32_t>(lds_level_base[last]) + (n_elems >> 3) * lds_b[last];
         uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + chunk_level0);
         const uint4* src = reinterpret_cast<const uint4*>(lds_level);
-        for (uint32_t i = tid; i < level_bytes / 16; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < level_bytes / 16; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
     }
     if (tid == 0) {
         blk->count = lds_count;

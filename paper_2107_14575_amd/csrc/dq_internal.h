@@ -122,6 +122,41 @@ int dq_zero_floats(float* dst_dev, int64_t n, hipStream_t stream);
 // and makes that GPU current.
 int dq_plan_check_device(const dq_plan* plan);
 
+// Streaming accesses: data that passes through once (a message being written or read, the averaged
+// gradient) is stored and loaded with the non-temporal hint, so it does not displace what the caches
+// could keep.  Measured at D = 2^28, M = 16, b = 4: quantize+pack 3.67 -> 3.48 ms with such stores,
+// the reduce 0.68 -> 0.59 ms with such loads and stores, the norm pass 2.69 -> 2.57 ms with such loads
+// (in quantize+pack non-temporal loads of the gradients cost 4 % instead: they stay plain there).
+typedef uint32_t dq_v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t dq_v2u __attribute__((ext_vector_type(2)));
+typedef float dq_v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void dq_store_stream(uint4* dst, const uint4& v)
+{
+    const dq_v4u t = { v.x, v.y, v.z, v.w };
+    __builtin_nontemporal_store(t, reinterpret_cast<dq_v4u*>(dst));
+}
+__device__ __forceinline__ void dq_store_stream(float4* dst, const float4& v)
+{
+    const dq_v4f t = { v.x, v.y, v.z, v.w };
+    __builtin_nontemporal_store(t, reinterpret_cast<dq_v4f*>(dst));
+}
+__device__ __forceinline__ float4 dq_load_stream(const float4* src)
+{
+    const dq_v4f t = __builtin_nontemporal_load(reinterpret_cast<const dq_v4f*>(src));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ uint4 dq_load_stream(const uint4* src)
+{
+    const dq_v4u t = __builtin_nontemporal_load(reinterpret_cast<const dq_v4u*>(src));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ uint2 dq_load_stream(const uint2* src)
+{
+    const dq_v2u t = __builtin_nontemporal_load(reinterpret_cast<const dq_v2u*>(src));
+    return make_uint2(t.x, t.y);
+}
+__device__ __forceinline__ uint32_t dq_load_stream(const uint32_t* src) { return __builtin_nontemporal_load(src); }
+
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies, key
 // bumped by the Weyl constants between rounds.  The three-input XOR is one v_bitop3_b32.
 __device__ __forceinline__ uint32_t dq_xor3(uint32_t a, uint32_t b, uint32_t c)

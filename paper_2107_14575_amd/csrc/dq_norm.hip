@@ -89,7 +89,8 @@ __global__ __launch_bounds__(256) void k_norm_partial(const float* __restrict__ 
         const int e = (k * 256 + tid) * 4;
         // the padded allocation is a multiple of 128 elements, so a float4 that starts inside the
         // item's valid range never leaves the worker's buffer
-        v[k] = e < item.count ? *reinterpret_cast<const float4*>(g + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+        // read once here (non-temporal): measured 2.69 -> 2.57 ms at D = 2^28, M = 16
+        v[k] = e < item.count ? dq_load_stream(reinterpret_cast<const float4*>(g + e)) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     if constexpr (LINF) {
         float m = 0.f;
@@ -235,8 +236,8 @@ __global__ __launch_bounds__(256) void k_norm_chunk(const float* __restrict__ gr
     for (int it = 0; it < 2; ++it) {
         uint32_t e = it * 2048 + tid * 8;
         e = e < n_elems ? e : n_elems - 8; // clamped: always in bounds, masked out below
-        x[it][0] = *reinterpret_cast<const float4*>(g + e);
-        x[it][1] = *reinterpret_cast<const float4*>(g + e + 4);
+        x[it][0] = dq_load_stream(reinterpret_cast<const float4*>(g + e));
+        x[it][1] = dq_load_stream(reinterpret_cast<const float4*>(g + e + 4));
         seg[it] = gseg[e >> 7];
     }
     const int32_t seg_first = gseg[0];

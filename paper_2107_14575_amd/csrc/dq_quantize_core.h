@@ -172,12 +172,12 @@ __device__ __forceinline__ void quantize_pack_chunk(
     {
         uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
         const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
-        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
     }
     {
         uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + (chunk0 >> 3) * B);
         const uint4* src = reinterpret_cast<const uint4*>(lds_level);
-        for (uint32_t i = tid; i < n_elems / 128 * B; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < n_elems / 128 * B; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
     }
 }
 
@@ -336,14 +336,14 @@ __device__ __forceinline__ void quantize_pack_chunk_v(
     {
         uint4* dst = reinterpret_cast<uint4*>(msg + (chunk0 >> 3));
         const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
-        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
     }
     {
         const int last = seg_last - seg_first;
         const uint32_t level_bytes = static_cast<uint32_t>(lds_level_base[last]) + (n_elems >> 3) * lds_b[last];
         uint4* dst = reinterpret_cast<uint4*>(msg + (padded_elems >> 3) + chunk_level0);
         const uint4* src = reinterpret_cast<const uint4*>(lds_level);
-        for (uint32_t i = tid; i < level_bytes / 16; i += QP_THREADS) dst[i] = src[i];
+        for (uint32_t i = tid; i < level_bytes / 16; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
     }
 }
 

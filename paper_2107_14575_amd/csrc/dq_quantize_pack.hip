@@ -93,7 +93,7 @@ __global__ __launch_bounds__(QP_THREADS) void k_sign_pack(const float* __restric
     __syncthreads();
     uint4* dst = reinterpret_cast<uint4*>(packed + static_cast<int64_t>(w) * packed_stride + (chunk0 >> 3));
     const uint4* src = reinterpret_cast<const uint4*>(lds_sign);
-    for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dst[i] = src[i];
+    for (uint32_t i = tid; i < n_elems / 128; i += QP_THREADS) dq_store_stream(dst + i, src[i]);
 }
 
 template <int B, int NORM>

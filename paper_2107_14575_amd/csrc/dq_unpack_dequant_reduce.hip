@@ -244,23 +244,23 @@ __device__ __forceinline__ void accumulate_lane(const uint8_t* __restrict__ sign
 {
     // one worker's sign dword and B level dwords of this lane
     auto load_worker = [&](int w, uint32_t& sg, uint32_t (&wd)[B]) {
-        sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
+        sg = dq_load_stream(reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride));
         const uint32_t* lp = reinterpret_cast<const uint32_t*>(level_ptr + static_cast<int64_t>(w) * packed_stride);
         if constexpr (B % 4 == 0) {
 #pragma unroll
             for (int q = 0; q < B / 4; ++q) {
-                const uint4 t = reinterpret_cast<const uint4*>(lp)[q];
+                const uint4 t = dq_load_stream(reinterpret_cast<const uint4*>(lp) + q);
                 wd[4 * q] = t.x; wd[4 * q + 1] = t.y; wd[4 * q + 2] = t.z; wd[4 * q + 3] = t.w;
             }
         } else if constexpr (B % 2 == 0) {
 #pragma unroll
             for (int q = 0; q < B / 2; ++q) {
-                const uint2 t = reinterpret_cast<const uint2*>(lp)[q];
+                const uint2 t = dq_load_stream(reinterpret_cast<const uint2*>(lp) + q);
                 wd[2 * q] = t.x; wd[2 * q + 1] = t.y;
             }
         } else {
 #pragma unroll
-            for (int q = 0; q < B; ++q) wd[q] = lp[q];
+            for (int q = 0; q < B; ++q) wd[q] = dq_load_stream(lp + q);
         }
     };
     // Workers in groups whose loads are all issued before the first is used: the pass is bound by
@@ -318,7 +318,11 @@ __device__ __forceinline__ void finish_tile(float (&acc)[UR_PER_LANE], bool acti
 #pragma unroll
     for (int q = 0; q < 8; ++q)
         wave_out[lane * 8 + (q ^ (lane & 7))] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
-    __syncthreads();
+    // the transposition stays inside the wavefront's own 512 slots: its lanes only have to see one
+    // another's LDS writes, no other wavefront's
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         // store j of the wave covers its elements [256j, 256j + 256); this lane takes 4 of them
@@ -326,7 +330,7 @@ __device__ __forceinline__ void finish_tile(float (&acc)[UR_PER_LANE], bool acti
         const float4 v = wave_out[src_lane * 8 + (q ^ (src_lane & 7))];
         const int64_t P = tile0 + wave * 2048 + 256 * j + 4 * lane;
         if (P < tile_end) {
-            if (!UPDATE || out) *reinterpret_cast<float4*>(out + P) = v;
+            if (!UPDATE || out) dq_store_stream(reinterpret_cast<float4*>(out + P), v);
             if constexpr (UPDATE) { // model update of Algorithm 1: x <- x - eta * g_hat (pads: g_hat is +0, x unchanged)
                 float4 xv = *reinterpret_cast<const float4*>(x + P);
                 xv.x = __builtin_fmaf(-eta, v.x, xv.x);
@@ -525,9 +529,9 @@ __global__ __launch_bounds__(UR_THREADS, UR_MIN_WAVES) void k_unpack_dequant_red
                     const int64_t msg = static_cast<int64_t>(w0 + i) * packed_stride;
                     const uint32_t* lp =
                         reinterpret_cast<const uint32_t*>(level_plane + msg + we[i].level_base + (P0 >> 3) * we[i].b);
-                    sg[i] = *reinterpret_cast<const uint32_t*>(sign_ptr + msg);
+                    sg[i] = dq_load_stream(reinterpret_cast<const uint32_t*>(sign_ptr + msg));
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) wd[i][q] = q < we[i].b ? lp[q] : 0u;
+                    for (int q = 0; q < 8; ++q) wd[i][q] = q < we[i].b ? dq_load_stream(lp + q) : 0u;
                 }
             }
 #pragma unroll
@@ -607,12 +611,12 @@ __global__ __launch_bounds__(UR_THREADS) void k_sign_reduce_scaled(
             uint32_t sg[GROUP];
 #pragma unroll
             for (int i = 0; i < GROUP; ++i)
-                sg[i] = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w + i) * packed_stride);
+                sg[i] = dq_load_stream(reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w + i) * packed_stride));
 #pragma unroll
             for (int i = 0; i < GROUP; ++i) add_signed_scale(sg[i], unit_ptr[w + i], acc);
         }
         for (; w < M; ++w) {
-            const uint32_t sg = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride);
+            const uint32_t sg = dq_load_stream(reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride));
             add_signed_scale(sg, unit_ptr[w], acc);
         }
     }
@@ -662,12 +666,12 @@ __global__ __launch_bounds__(UR_THREADS) void k_sign_reduce_count(
             uint32_t sg[GROUP];
 #pragma unroll
             for (int i = 0; i < GROUP; ++i)
-                sg[i] = *reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w + i) * packed_stride);
+                sg[i] = dq_load_stream(reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w + i) * packed_stride));
 #pragma unroll
             for (int i = 0; i < GROUP; ++i) add(sg[i]);
         }
         for (; w < M; ++w)
-            add(*reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride));
+            add(dq_load_stream(reinterpret_cast<const uint32_t*>(sign_ptr + static_cast<int64_t>(w) * packed_stride)));
 #pragma unroll
         for (int k = 0; k < UR_PER_LANE; ++k) {
             uint32_t count = 0;
