@@ -92,7 +92,7 @@ constexpr float UR_FP8_SCALE = 512.0f;
 constexpr int UR_MIN_WAVES = 4;
 constexpr int UR_SUM_BLOCK = 8; // workers per block of the two-level sum (a power of two)
 // workers whose loads are issued together (measured per width at D = 2^28, M = 16)
-__host__ __device__ constexpr int ur_group(int b) { return b == 2 ? 16 : b == 3 ? 8 : 4; }
+__host__ __device__ constexpr int ur_group(int b) { return b <= 4 ? 16 : b <= 6 ? 2 : 4; }
 
 // bytes of {hi, lo} picked by the four selector bytes of sel: 0..3 = bytes of lo, 4..7 = bytes of hi
 __device__ __forceinline__ uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel)
