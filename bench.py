@@ -360,9 +360,7 @@ def main() -> None:
         by the widths of the timed steps; for kernels whose traffic does not depend on b the
         single-width summary.  None when no summary covers the workload."""
         import re
-        if args.workload != "flat_student_t":
-            return None
-        shape = f"flat_student_t_d2p{dp.bit_length() - 1}_m{M}"
+        shape = f"flat_student_t_d2p{dp.bit_length() - 1}_m{M}" if args.workload == "flat_student_t" else f"{args.workload}_m{M}"
         pdir = os.path.join(ROOT, "profiles")
         table = os.path.join(pdir, f"{kernel_tag}__{shape}_b1to8.txt")
         if os.path.exists(table):
