@@ -1,5 +1,6 @@
 """Accuracy of the M-way average (Algorithm 1 "Average", Eq. (2)) where it is hardest for binary32
-sums: many workers (M = 16, the benchmark's, and M = 64, the largest a call accepts), every term of
+sums: many workers (M = 16, the benchmark's, M = 64, the largest a call accepts, and counts that leave
+partial blocks), every term of
 one sign so nothing cancels, levels at or near s, norms equal, geometric or spread over four decades.
 The messages are written by the oracle from chosen codes; the GPU's average is compared with the
 oracle's binary64 one element by element at the benchmark spec's tolerance: 1e-6 of the mean magnitude of
@@ -22,7 +23,7 @@ def _norm_sets(M, rng):
     yield "one large, rest small", np.concatenate([[np.float32(3.3)], np.full(M - 1, np.float32(1.1e-3))]).astype(np.float32)
 
 
-@pytest.mark.parametrize("M", [16, 64])
+@pytest.mark.parametrize("M", [9, 16, 23, 42, 64])   # whole and partial blocks of eight, every load-group tail
 @pytest.mark.parametrize("b", [1, 2, 3, 4, 6, 8])
 def test_same_sign_terms_near_the_top_level(dq, oracle, M, b):
     rng = np.random.default_rng(1000 * M + b)
