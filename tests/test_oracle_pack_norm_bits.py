@@ -259,3 +259,37 @@ def test_range_forms_equal_slices_of_the_whole(oracle):
         assert np.array_equal(s2, sign[:, p0:p1]) and np.array_equal(l2, level[:, p0:p1])
         o2 = oracle.dequant_reduce_range(seg, s2, l2, norms, b, p0, p1)
         assert np.array_equal(o2, out[p0:p1])
+
+
+def test_gbar_is_the_plain_index_order_sum_of_lemma_1(oracle):
+    """G-bar_t^2 = (1/M) sum_i ||g^(i)||^2 with ||g^(i)||^2 = sum_l N_{i,l}^2 (Lemma 1): the oracle adds a
+    worker's squares one after the other in index order in binary64 -- no blocks, no pairing.  Checked on
+    5000 tensors against exact rational arithmetic (the running sum's error bound) and against the same
+    running sum spelled out in Python floats; on some of the inputs a sum taken in blocks of 1024 gives a
+    different G-bar, so the check can tell the two orders apart."""
+    from fractions import Fraction
+    n_seg, M = 5000, 2
+    told_apart = 0
+    for seed in range(12):
+        rng = np.random.default_rng(770 + seed)
+        norms = (10 ** rng.uniform(-6, 2, size=(M, n_seg))).astype(np.float32)
+        _, gbar = oracle.select_bits(norms, 0, 10, 1.0, 0.9, 1, 8)
+        if seed == 0:
+            exact = sum(Fraction(float(x)) ** 2 for x in norms.reshape(-1)) / M
+            assert abs(Fraction(gbar) ** 2 - exact) <= exact * n_seg * Fraction(1, 2 ** 52)
+        total = blocked = 0.0
+        for i in range(M):
+            worker = 0.0
+            for x in norms[i]:
+                worker += float(x) * float(x)
+            total += worker
+            worker = 0.0
+            for base in range(0, n_seg, 1024):
+                blk = 0.0
+                for x in norms[i, base:base + 1024]:
+                    blk += float(x) * float(x)
+                worker += blk
+            blocked += worker
+        assert gbar == float(np.sqrt(total / M)), seed
+        told_apart += float(np.sqrt(blocked / M)) != gbar
+    assert told_apart >= 1
