@@ -29,7 +29,7 @@
 
 namespace {
 
-// One element again with another scale: the level of quantize4 for element value v and word r.
+// One element again with another scale: the level of Eq. (5)-(6) for element value v and random word r.
 template <int B>
 __device__ __forceinline__ uint32_t level_of(float v, float scale, uint32_t r)
 {
@@ -163,15 +163,11 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
         const uint32_t e = it * QP_TILE + tid * QP_PER_LANE;
         if (e < n_elems) {
             const uint32_t quad = quad_lo0 + (e >> 2);
-            uint32_t r0[4], r1[4];
-            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
-            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
-
             // levels at the low end of the bracket: the largest any norm inside it can give
-            uint32_t sign = 0, lv_lo, lv_hi;
-            quantize4<B>(x[it][1], lds_scale_hi[local[it]], r1, sign, lv_hi);
-            quantize4<B>(x[it][0], lds_scale_hi[local[it]], r0, sign, lv_lo);
-            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * B));
+            uint32_t sign, rr[2][4];
+            uint64_t level;
+            quantize8<B>(x[it][0], x[it][1], lds_scale_hi[local[it]], 0.0f, 0, quad, quad_hi, worker, step, key0, key1,
+                         sign, level, rr);
             const int nv = valid[it] >= QP_PER_LANE ? QP_PER_LANE : (valid[it] > 0 ? valid[it] : 0);
             if (nv < QP_PER_LANE) {
                 sign &= (1u << nv) - 1u;
@@ -181,7 +177,7 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed(
                 const float scale_lo = lds_scale_lo[local[it]];
                 const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
                                      x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
-                const uint32_t r[8] = { r0[0], r0[1], r0[2], r0[3], r1[0], r1[1], r1[2], r1[3] };
+                const uint32_t r[8] = { rr[0][0], rr[0][1], rr[0][2], rr[0][3], rr[1][0], rr[1][1], rr[1][2], rr[1][3] };
 #pragma unroll
                 for (int k = 0; k < QP_PER_LANE; ++k) {
                     const uint32_t top = static_cast<uint32_t>(level >> (k * B)) & static_cast<uint32_t>(FIELD);
@@ -342,14 +338,10 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed_v(
             const int b = lds_b[local[it]];
             const uint64_t field = (static_cast<uint64_t>(1) << b) - 1u;
             const uint32_t quad = quad_lo0 + (e >> 2);
-            uint32_t r0[4], r1[4];
-            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
-            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
-
-            uint32_t sign = 0, lv_lo, lv_hi;
-            quantize4_v(x[it][1], lds_scale_hi[local[it]], S, b, r1, sign, lv_hi);
-            quantize4_v(x[it][0], lds_scale_hi[local[it]], S, b, r0, sign, lv_lo);
-            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * b));
+            uint32_t sign, rr[2][4];
+            uint64_t level;
+            quantize8<0>(x[it][0], x[it][1], lds_scale_hi[local[it]], S, b, quad, quad_hi, worker, step, key0, key1,
+                         sign, level, rr);
             const int nv = valid[it] >= QP_PER_LANE ? QP_PER_LANE : (valid[it] > 0 ? valid[it] : 0);
             if (nv < QP_PER_LANE) {
                 sign &= (1u << nv) - 1u;
@@ -359,7 +351,7 @@ __global__ __launch_bounds__(QP_THREADS) void k_quantize_pack_bracketed_v(
                 const float scale_lo = lds_scale_lo[local[it]];
                 const float v[8] = { x[it][0].x, x[it][0].y, x[it][0].z, x[it][0].w,
                                      x[it][1].x, x[it][1].y, x[it][1].z, x[it][1].w };
-                const uint32_t r[8] = { r0[0], r0[1], r0[2], r0[3], r1[0], r1[1], r1[2], r1[3] };
+                const uint32_t r[8] = { rr[0][0], rr[0][1], rr[0][2], rr[0][3], rr[1][0], rr[1][1], rr[1][2], rr[1][3] };
 #pragma unroll
                 for (int k = 0; k < QP_PER_LANE; ++k) {
                     const uint32_t top = static_cast<uint32_t>(level >> (k * b)) & static_cast<uint32_t>(field);

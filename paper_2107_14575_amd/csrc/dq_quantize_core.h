@@ -32,23 +32,63 @@ __device__ __forceinline__ void stage_bytes(uint8_t* dst, uint64_t v)
     }
 }
 
-// Four elements (one Philox block): sign bits into bits 0..3 of `sign` (shifted in from the top
-// element down), levels into a 4*B-bit little-endian field.
+// A lane's eight consecutive elements (two Philox blocks with counters quad, quad + 1): the sign
+// byte (element 0 in bit 0) and the 8*B level bits (element 0 in the low B bits).  Per element, with
+// a = min(|g| * scale, s) in binary32 and u = (word >> 8) * 2^-24: level = floor(a) + [u < a - floor(a)]
+// (Eq. (5)-(6)).  Three routes, chosen per wavefront, all giving exactly those bits:
+//   * every lane's eight products |g| * scale are zero (exact-zero stretches of a gradient, or a
+//     tensor whose norm is unusable): every level is 0 whatever the random numbers, none are drawn;
+//   * every product is below 1 (the usual case for a tensor of many elements: |g|/N ~ 1/sqrt(d)):
+//     then a = min(a, s) = a, floor(a) = 0 and a - floor(a) = a, so the level is [u < a] -- no clamp,
+//     no fract, no float-to-integer conversion;
+//   * otherwise the general form: clamp, v_fract, convert, compare, add with carry.
+// The wavefront-wide test costs a maximum over the eight products and two votes.
+// S, b: the level count and bits of the tensor (template argument B > 0 fixes them at compile time).
+// r[h][k] receives the random word of element 4h + k unless the all-zero route was taken (then no
+// caller needs it: every level is zero).
 template <int B>
-__device__ __forceinline__ void quantize4(const float4 x, const float scale, const uint32_t (&r)[4],
-                                          uint32_t& sign, uint32_t& level)
+__device__ __forceinline__ void quantize8(const float4 x_lo, const float4 x_hi, const float scale, const float S_arg,
+                                          const int b_arg, const uint32_t quad, const uint32_t quad_hi,
+                                          const uint32_t worker, const uint32_t step, const uint32_t key0,
+                                          const uint32_t key1, uint32_t& sign, uint64_t& level, uint32_t (&r)[2][4])
 {
-    constexpr float S = static_cast<float>((1 << B) - 1);
-    const float v[4] = { x.x, x.y, x.z, x.w };
-    level = 0;
+    const float S = B > 0 ? static_cast<float>((1 << (B > 0 ? B : 1)) - 1) : S_arg;
+    const int b = B > 0 ? B : b_arg;
+    const float v[8] = { x_lo.x, x_lo.y, x_lo.z, x_lo.w, x_hi.x, x_hi.y, x_hi.z, x_hi.w };
+    float a[8];
+    sign = 0;
 #pragma unroll
-    for (int k = 3; k >= 0; --k) {
-        sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31); // (sign << 1) | sign bit
-        const float a = fminf(fabsf(v[k]) * scale, S);                     // s|g|/N, one rounding, clamped
-        const float p = __builtin_amdgcn_fractf(a);                         // a - floor(a), exact
-        const float u = static_cast<float>(r[k] >> 8) * 0x1p-24f;           // exact, in [0,1)
-        level = (level << B) + static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
+    for (int k = 7; k >= 0; --k) {
+        sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31); // element 0 ends in bit 0
+        a[k] = fabsf(v[k]) * scale;                                         // s|g|/N, one rounding
     }
+    const float top = fmaxf(fmaxf(__builtin_fmaxf(__builtin_fmaxf(a[0], a[1]), a[2]), __builtin_fmaxf(__builtin_fmaxf(a[3], a[4]), a[5])),
+                            __builtin_fmaxf(a[6], a[7]));
+    level = 0;
+    if (__all(top == 0.0f)) return;
+    dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r[0]);
+    dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r[1]);
+    uint32_t lv[2] = { 0u, 0u };
+    if (__all(top < 1.0f)) {
+#pragma unroll
+        for (int h = 1; h >= 0; --h)
+#pragma unroll
+            for (int k = 3; k >= 0; --k) {
+                const float u = static_cast<float>(r[h][k] >> 8) * 0x1p-24f; // exact, in [0,1)
+                lv[h] = (lv[h] << b) + (u < a[4 * h + k] ? 1u : 0u);
+            }
+    } else {
+#pragma unroll
+        for (int h = 1; h >= 0; --h)
+#pragma unroll
+            for (int k = 3; k >= 0; --k) {
+                const float c = fminf(a[4 * h + k], S);                      // clamped
+                const float p = __builtin_amdgcn_fractf(c);                  // c - floor(c), exact
+                const float u = static_cast<float>(r[h][k] >> 8) * 0x1p-24f;
+                lv[h] = (lv[h] << b) + static_cast<uint32_t>(c) + (u < p ? 1u : 0u);
+            }
+    }
+    level = static_cast<uint64_t>(lv[0]) | (static_cast<uint64_t>(lv[1]) << (4 * b));
 }
 
 // NORM = 0: the norms are an input.  NORM = 1 (l2) or 2 (max): chunk-local plans only; the kernel
@@ -147,14 +187,10 @@ __device__ __forceinline__ void quantize_pack_chunk(
             const int32_t n_valid = lds_valid_end[local] - static_cast<int32_t>(e); // may be <= 0 or > 8
 
             const uint32_t quad = quad_lo0 + (e >> 2); // even; quad + 1 cannot carry
-            uint32_t r0[4], r1[4];
-            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
-            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
-
-            uint32_t sign = 0, lv_lo, lv_hi;
-            quantize4<B>(x[it][1], scale, r1, sign, lv_hi); // elements 4..7 first: element 0 ends in bit 0
-            quantize4<B>(x[it][0], scale, r0, sign, lv_lo);
-            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * B));
+            uint32_t sign;
+            uint64_t level;
+            uint32_t r[2][4];
+            quantize8<B>(x[it][0], x[it][1], scale, 0.0f, 0, quad, quad_hi, worker, step, key0, key1, sign, level, r);
             if (n_valid < QP_PER_LANE) { // the tensor ends inside (or before) this lane's eight elements
                 const int nv = n_valid > 0 ? n_valid : 0;
                 sign &= (1u << nv) - 1u;
@@ -187,21 +223,6 @@ __device__ __forceinline__ void quantize_pack_chunk(
 // still one contiguous stretch of the message (every segment's stretch is a whole number of
 // 16-byte pieces per granule), so they are staged and stored the same way.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void quantize4_v(const float4 x, const float scale, const float S, const int b,
-                                            const uint32_t (&r)[4], uint32_t& sign, uint32_t& level)
-{
-    const float v[4] = { x.x, x.y, x.z, x.w };
-    level = 0;
-#pragma unroll
-    for (int k = 3; k >= 0; --k) {
-        sign = __builtin_amdgcn_alignbit(sign, __float_as_uint(v[k]), 31);
-        const float a = fminf(fabsf(v[k]) * scale, S);
-        const float p = __builtin_amdgcn_fractf(a);
-        const float u = static_cast<float>(r[k] >> 8) * 0x1p-24f;
-        level = (level << b) + static_cast<uint32_t>(a) + (u < p ? 1u : 0u);
-    }
-}
-
 template <int TILES, int NORM> // NORM as in quantize_pack_chunk
 __device__ __forceinline__ void quantize_pack_chunk_v(
     const float* __restrict__ grads, int64_t worker_stride, const float* __restrict__ norms, int32_t n_seg,
@@ -301,14 +322,9 @@ __device__ __forceinline__ void quantize_pack_chunk_v(
             const int32_t n_valid = lds_valid_end[local] - static_cast<int32_t>(e);
 
             const uint32_t quad = quad_lo0 + (e >> 2);
-            uint32_t r0[4], r1[4];
-            dq_philox4x32_10(quad, quad_hi, worker, step, key0, key1, r0);
-            dq_philox4x32_10(quad + 1u, quad_hi, worker, step, key0, key1, r1);
-
-            uint32_t sign = 0, lv_lo, lv_hi;
-            quantize4_v(x[it][1], scale, S, b, r1, sign, lv_hi);
-            quantize4_v(x[it][0], scale, S, b, r0, sign, lv_lo);
-            uint64_t level = static_cast<uint64_t>(lv_lo) | (static_cast<uint64_t>(lv_hi) << (4 * b));
+            uint32_t sign, r[2][4];
+            uint64_t level;
+            quantize8<0>(x[it][0], x[it][1], scale, S, b, quad, quad_hi, worker, step, key0, key1, sign, level, r);
             if (n_valid < QP_PER_LANE) {
                 const int nv = n_valid > 0 ? n_valid : 0;
                 sign &= (1u << nv) - 1u;
