@@ -173,9 +173,10 @@ def main() -> None:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    def timed_loop(fn, reps: int = 5) -> float:
-        """ms per call, after one untimed call, with events on the stream the kernels run on"""
-        fn()
+    def timed_loop(fn, reps: int = 5, warm: int = 1) -> float:
+        """ms per call, after `warm` untimed calls, with events on the stream the kernels run on"""
+        for _ in range(warm):
+            fn()
         torch.cuda.synchronize()
         u0, u1 = ev(), ev()
         u0.record()
@@ -480,8 +481,10 @@ def main() -> None:
     per_b = {}
     for b in range(1, 9):
         pk_b = packed[:, :plan.packed_bytes(b)]
-        tq = timed_loop(lambda: dq.quantize_pack(plan, grads, norms_dev, b, wl.QUANT_SEED, T, pk_b), 3)
-        tr = timed_loop(lambda: dq.unpack_dequant_reduce(plan, pk_b, norms_dev, b, out), 3)
+        # three untimed calls first: whichever width runs first after the host-side pause before this
+        # sweep otherwise measures 5 % slow (clocks still rising), whatever that width is
+        tq = timed_loop(lambda: dq.quantize_pack(plan, grads, norms_dev, b, wl.QUANT_SEED, T, pk_b), 4, warm=3 if b == 1 else 1)
+        tr = timed_loop(lambda: dq.unpack_dequant_reduce(plan, pk_b, norms_dev, b, out), 4)
         q, r = rl(M * dp * (4 + (b + 1) / 8), tq), rl(dp * (M * (b + 1) / 8 + 4), tr)
         row = {"quantize_pack_ms": q["avg_ms"], "quantize_pack_GBps": q["achieved"], "quantize_pack_frac": q["frac"],
                "reduce_ms": r["avg_ms"], "reduce_GBps": r["achieved"], "reduce_frac": r["frac"]}
