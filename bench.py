@@ -3,7 +3,7 @@
 
 A "step" is one pass of the whole path over one batch of synthetic gradients that are already
 resident in HBM:  dq_norm -> (norms to host) -> dq_select_bits -> dq_quantize_pack (all M workers)
--> dq_unpack_dequant_reduce.  The default workload is the benchmark's large flat gradient
+-> dq_unpack_dequant_reduce.  The default workload is the large flat gradient of the headline metric
 (D = 2^28 fp32 per worker, M = 16, Student-t(3) * 1e-3, b_t from the dynamic rule in 2..8), the
 one the >= 70 %-of-HBM target is quoted on.
 
