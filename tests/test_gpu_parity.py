@@ -252,6 +252,33 @@ def test_reduce_accepts_any_message(dq, oracle):
     plan.close()
 
 
+@pytest.mark.parametrize("b", range(1, 9))
+def test_every_sign_and_level_decodes_exactly_at_every_position(dq, oracle, b):
+    """M = 1 and a norm of s * 2^e make the unit N / s a power of two, so the average is exactly
+    +-level * 2^e: every level 0..s with both signs, at every one of the 32 positions a lane decodes
+    (the code (sign, level) walks through the positions), equal to the oracle bit for bit"""
+    s = (1 << b) - 1
+    n_codes = 2 * (s + 1)
+    d = 32 * n_codes * 2                         # every code meets every position at least once
+    P = np.arange(d)
+    code = (P // 32 + P % 32) % n_codes          # shifts by one position from run to run
+    sign = (code & 1).astype(np.uint8)
+    level = (code >> 1).astype(np.uint8)
+    seg_len = [d]
+    plan = dq.Plan(seg_len)
+    dp = plan.padded_elems
+    sg = np.zeros((1, dp), np.uint8); lv = np.zeros((1, dp), np.uint8)
+    sg[0, :d] = sign; lv[0, :d] = level
+    for e in (-7, 3):
+        norms = np.array([[np.float32(s) * np.float32(2.0) ** e]], dtype=np.float32)
+        packed = oracle.pack(sg[0], lv[0], b)[None, :].copy()
+        out = gpu_reduce(dq, plan, torch.from_numpy(packed).cuda(), torch.from_numpy(norms).cuda(), b).cpu().numpy()
+        expect = np.where(sg[0] == 1, -1.0, 1.0) * lv[0].astype(np.float64) * 2.0 ** e
+        assert np.array_equal(out.astype(np.float64), expect)
+        assert np.array_equal(out.view(np.uint32), oracle.dequant_reduce(seg_len, sg, lv, norms, b).view(np.uint32))
+    plan.close()
+
+
 def test_stream_argument_and_determinism(dq):
     """work goes to the stream that is passed in; two runs give identical bytes"""
     seg_len, grads = wl.ragged_mix(M=2)
