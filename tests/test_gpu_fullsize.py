@@ -303,7 +303,7 @@ def test_config5_other_entry_points_sampled(dq, oracle):
 
 
 def test_config5_worker0_in_full_and_slices_of_every_worker(dq, oracle):
-    """Config 5 (D = 2^28, M = 16) against the oracle at depth, for b in {2, 4, 8} and for both
+    """Config 5 (D = 2^28, M = 16) against the oracle at depth, for every width b = 1..8 and for both
     dq_quantize_pack and the single-pass dq_norm_quantize_pack_bracketed:
       * worker 0's whole message (2^28 elements) byte for byte;
       * a 2^24-element slice of every other worker, each at its own place along the gradient, byte for byte;
@@ -362,7 +362,7 @@ def test_config5_worker0_in_full_and_slices_of_every_worker(dq, oracle):
     lo, hi = torch.empty_like(norms_dev), torch.empty_like(norms_dev)
     dq.norm_bracket(norms_dev, 0.125, lo, hi)
     norms2_dev = torch.empty_like(norms_dev)
-    for b, step in ((2, 11), (4, 12), (8, 13)):
+    for b, step in ((1, 21), (2, 11), (3, 22), (4, 12), (5, 23), (6, 24), (7, 25), (8, 13)):
         pk = packed[:, :plan.packed_bytes(b)]
         dq.quantize_pack(plan, g, norms_dev, b, SEED, step, pk)
         dq.unpack_dequant_reduce(plan, pk, norms_dev, b, out)
